@@ -1,0 +1,180 @@
+/*
+ * sj.h - C ABI of the draft-block verification step of judge-assisted speculative decoding
+ * on one AMD MI355X (gfx950).
+ *
+ * One call, sj_verify_step, performs for every sequence of a batch what the paper's Method
+ * section describes as one verification cycle: the target model reads the pending token and
+ * the gamma draft tokens against its KV cache (Eq. 2 / Eq. 4), the draft tokens are tested by
+ * the probability-ratio rule (Eq. 3) and by the judge verifier on the target's hidden states
+ * (Eq. 5), a token is kept if either test approves it (Sec. 3.2, App. D.2), tokens are accepted
+ * until the first rejection (Sec. 3.1), and one more token is emitted from the last
+ * distribution or from the residual distribution of modified rejection sampling (Sec. 2.2).
+ *
+ * Conventions
+ *   - Plain C.  No call throws or aborts.  Every function returns SJ_OK (0) or a negative
+ *     SJ_E* code; sj_last_error() gives a thread-local message for the last failure.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory on the
+ *     current device, owned by the caller, and must stay valid until the stream has run.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls that take
+ *     a stream are asynchronous on it; their outputs are valid once the stream is synchronised.
+ *   - The library owns sj_model / sj_kv and all workspace; it allocates at load / create time
+ *     (plus a one-time launch-graph build on the first step of a given gamma), never per step.
+ *   - On an argument error no sequence state is modified.
+ *   - Storage dtype (sj_config.dtype) applies to weights and the KV cache: 0 = fp32,
+ *     1 = bf16 (bit pattern in uint16).  Host tensors handed over are in that dtype.
+ *   - Sequences of a batch are independent.
+ */
+#ifndef SJ_H
+#define SJ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SJ_OK         0
+#define SJ_EINVAL    -1   /* null pointer, bad shape, gamma / token / index out of range        */
+#define SJ_ECAPACITY -2   /* len + gamma + 1 would exceed a sequence's KV capacity              */
+#define SJ_EHIP      -3   /* a HIP runtime call failed (message carries hipGetErrorString)      */
+#define SJ_ENOMEM    -4   /* host or device allocation failed                                   */
+#define SJ_ECALLBACK -5   /* the tensor provider returned non-zero                              */
+
+#define SJ_DTYPE_FP32 0
+#define SJ_DTYPE_BF16 1
+
+/* Tensor ids the provider is asked for.  Matrices are [out_features, in_features] row-major
+ * (the layout y = x W^T reads), vectors are contiguous.  layer = -1 for model-level tensors. */
+enum sj_tensor_id {
+    SJ_T_EMBED = 0,      /* [vocab, d_model]                                   */
+    SJ_T_ATTN_NORM = 1,  /* [d_model]            RMSNorm gain before attention */
+    SJ_T_WQ = 2,         /* [n_q_heads*head_dim, d_model]                      */
+    SJ_T_WK = 3,         /* [n_kv_heads*head_dim, d_model]                     */
+    SJ_T_WV = 4,         /* [n_kv_heads*head_dim, d_model]                     */
+    SJ_T_WO = 5,         /* [d_model, n_q_heads*head_dim]                      */
+    SJ_T_FFN_NORM = 6,   /* [d_model]            RMSNorm gain before the FFN   */
+    SJ_T_W_GATE = 7,     /* [d_ffn, d_model]                                   */
+    SJ_T_W_UP = 8,       /* [d_ffn, d_model]                                   */
+    SJ_T_W_DOWN = 9,     /* [d_model, d_ffn]                                   */
+    SJ_T_FINAL_NORM = 10,/* [d_model]                                          */
+    SJ_T_LM_HEAD = 11,   /* [vocab, d_model]                                   */
+    SJ_T_JUDGE_W = 12,   /* [d_model]            judge verifier weights        */
+    SJ_T_JUDGE_B = 13    /* [1]                  judge verifier intercept      */
+};
+
+/* Model geometry (Llama-3 family decoder, the target models of Sec. 4.1).  n_layers = 0 gives
+ * a head-only model (LM head + judge) usable with sj_verify_head only. */
+typedef struct sj_config {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t dtype;          /* SJ_DTYPE_*                                                      */
+    float   rope_base;      /* rotary base; pairs (i, i + head_dim/2), angle pos*base^(-2i/hd) */
+    float   rms_eps;        /* inside the square root                                          */
+    float   temperature;    /* target softmax temperature; 0 = one-hot at the lowest arg-max   */
+    int32_t max_gamma;      /* largest draft length any step will use (1..63)                  */
+} sj_config;
+
+typedef struct sj_model sj_model;   /* opaque: device-resident, re-tiled weights               */
+typedef struct sj_kv sj_kv;         /* opaque: KV cache, per-sequence state, step workspace    */
+
+/* Fills dst (host, nbytes = element count * dtype size) with one tensor.  Return 0 on success.
+ * Called once per tensor, one tensor at a time, so the model never has to sit in host memory. */
+typedef int (*sj_tensor_fn)(void* user, int32_t tensor_id, int32_t layer, void* dst_host, size_t nbytes);
+
+/* Uploads and re-tiles the target model's weights (needed by Eq. 2 / Eq. 4 / Eq. 5).
+ * Requirements: d_model, head_dim, d_ffn, vocab multiples of 32; n_q_heads a multiple of
+ * n_kv_heads; head_dim in {64, 128}.  Synchronous.  *out is set only on success. */
+int sj_model_load(const sj_config* cfg, sj_tensor_fn provider, void* user, sj_model** out);
+int sj_model_free(sj_model* m);
+
+/* Creates the per-batch state: a KV cache with `capacity[b]` positions for sequence b (rounded
+ * up to a multiple of 64 internally), lengths 0, pending tokens 0, and the step workspace for
+ * batch * (max_gamma + 1) query rows.  capacity is a host array of `batch` entries (ignored
+ * and may be NULL for a head-only model).  Synchronous. */
+int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* capacity, sj_kv** out);
+int sj_kv_free(sj_kv* kv);
+
+/* Overwrites sequence `seq`'s cache with `len` positions given on the host as
+ * k_host, v_host = [n_layers][n_kv_heads][len][head_dim] in the storage dtype, and sets its
+ * pending token (the last emitted token, not yet cached; row 0 of the next block).
+ * Stands in for a real prefill where one is too expensive.  Synchronous. */
+int sj_kv_set(sj_kv* kv, int32_t seq, const void* k_host, const void* v_host, int32_t len,
+              int32_t pending_token);
+
+/* Same for a single layer: k_host, v_host = [n_kv_heads][len][head_dim].  Lets a large cache be
+ * produced layer by layer.  Length / pending token take effect through sj_kv_set_state. */
+int sj_kv_set_layer(sj_kv* kv, int32_t seq, int32_t layer, const void* k_host, const void* v_host,
+                    int32_t len);
+int sj_kv_set_state(sj_kv* kv, int32_t seq, int32_t len, int32_t pending_token);
+
+/* Reads back cache rows pos0 .. pos0+n-1 of one (sequence, layer) into host arrays
+ * [n_kv_heads][n][head_dim] (storage dtype).  Rows at or beyond the current length are the
+ * dead rows of the last block.  Synchronous. */
+int sj_kv_read(const sj_kv* kv, int32_t seq, int32_t layer, int32_t pos0, int32_t n,
+               void* k_host, void* v_host);
+
+/* Current lengths / pending tokens, host arrays of `batch` int32 (either may be NULL).  Synchronous. */
+int sj_kv_state(const sj_kv* kv, int32_t* len_host, int32_t* pending_host);
+
+/* Runs the target over n prompt tokens (host array) of sequence seq, appends their K/V, advances
+ * the length by n and sets the pending token to the arg-max continuation of the last prompt
+ * token.  Uses the same kernels as the verification forward.  Synchronises `stream`. */
+int sj_prefill(sj_model* m, sj_kv* kv, int32_t seq, const int32_t* tokens_host, int32_t n, void* stream);
+
+/* One verification cycle for every sequence of the batch (Sec. 3.1 - 3.2).
+ *   draft_tokens  device int32 [batch, gamma]        d_{t+1..t+gamma}                (Eq. 1)
+ *   draft_probs   device float [batch, gamma, vocab] the draft distribution each d was drawn from
+ *   uniforms      device float [batch, gamma+1]      in [0,1): entry j tests d_{j+1} (Eq. 3),
+ *                                                    the last one draws the emitted token
+ *   judge_threshold  theta of Eq. 5; >= 1 disables the judge, < 0 accepts every token
+ *   accepted_len  device int32 [batch]  out: n in [0, gamma]
+ *   next_token    device int32 [batch]  out: the extra token (bonus if n == gamma, else resampled)
+ * Effects: K/V of the gamma+1 block rows are written at positions len..len+gamma; then
+ * len += 1 + n and pending = next_token (rows beyond the new len are dead and get overwritten).
+ * Errors: SJ_EINVAL (null, gamma outside 1..max_gamma), SJ_ECAPACITY.  Token ids are not read
+ * on the host; a draft token outside [0, vocab) is clamped into range on the device. */
+int sj_verify_step(sj_model* m, sj_kv* kv, int32_t gamma, const int32_t* draft_tokens,
+                   const float* draft_probs, const float* uniforms, float judge_threshold,
+                   int32_t* accepted_len, int32_t* next_token, void* stream);
+
+/* The verification tail alone (LM head, softmax, Eq. 3, Eq. 5, scan, resampling) on given final
+ * hidden states: hidden = device [batch*(gamma+1), d_model] in the storage dtype, already
+ * RMS-normed, row b*(gamma+1)+j = block row j of sequence b.  No cache is read or written; kv
+ * supplies the workspace (it may come from a head-only model). */
+int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void* hidden,
+                   const int32_t* draft_tokens, const float* draft_probs, const float* uniforms,
+                   float judge_threshold, int32_t* accepted_len, int32_t* next_token, void* stream);
+
+/* Verifier variants of the paper's ablations and baselines, applied by the following steps:
+ *   SJ_MODE_TWO_STAGE (default)  either test approves          (App. D.2)
+ *   SJ_MODE_ALIGNMENT            Eq. 3 only (standard speculative decoding)
+ *   SJ_MODE_JUDGE                Eq. 5 only */
+#define SJ_MODE_TWO_STAGE 0
+#define SJ_MODE_ALIGNMENT 1
+#define SJ_MODE_JUDGE     2
+int sj_set_mode(sj_kv* kv, int32_t mode);
+
+/* Intermediate results of the last step, copied to the host (synchronous; for parity tests).
+ *   SJ_DBG_LOGITS       float [rows, vocab]     rows = batch*(gamma+1)
+ *   SJ_DBG_HIDDEN       float [rows, d_model]   final hidden states after the last RMSNorm
+ *   SJ_DBG_JUDGE_SCORES float [batch, gamma]    sigmoid scores, entry j for d_{j+1}
+ *   SJ_DBG_P_AT_DRAFT   float [batch, gamma]    p(d_{j+1}) under the target
+ *   SJ_DBG_ACCEPT_BITS  int32 [batch, gamma]    bit0 = Eq. 3 accepted, bit1 = judge accepted
+ * nbytes must equal the size above for the gamma of the last step. */
+#define SJ_DBG_LOGITS       0
+#define SJ_DBG_HIDDEN       1
+#define SJ_DBG_JUDGE_SCORES 2
+#define SJ_DBG_P_AT_DRAFT   3
+#define SJ_DBG_ACCEPT_BITS  4
+int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, size_t nbytes);
+
+/* Bytes of weights one step streams from HBM (all projections + LM head), for roofline math. */
+int64_t sj_model_weight_bytes(const sj_model* m);
+
+const char* sj_last_error(void);
+const char* sj_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SJ_H */

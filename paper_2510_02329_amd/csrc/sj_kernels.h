@@ -1,0 +1,778 @@
+// HIP kernels of the verification step.  Each kernel cites the part of the method it carries out
+// (paper "Method": Eq. 2 / Eq. 4 target forward, Eq. 3 ratio test, Eq. 5 judge, Sec. 3.1 scan and
+// extra token, Sec. 2.2 residual resampling).  Workgroups are 256 threads unless noted.
+#pragma once
+#include "sj_device.h"
+
+namespace sj {
+
+// Per-call parameters, kept in device memory so that a captured launch graph can be replayed with
+// new caller pointers: only this struct is rewritten between replays.
+struct StepParams {
+    int32_t nseq;        // sequences processed by this call
+    int32_t seq_base;    // first sequence index (prefill of one sequence: its index)
+    int32_t rps;         // query rows per sequence (verify: gamma + 1; prefill: chunk length)
+    int32_t gamma;       // draft length (verify only)
+    int32_t tok_mode;    // 0: row 0 = pending token, rows 1.. = draft tokens; 1: rows = prefill tokens
+    int32_t mode;        // SJ_MODE_*
+    float theta;         // judge threshold
+    float pad0;
+    const int32_t* draft_tokens;   // [nseq, gamma]
+    const float* draft_probs;      // [nseq, gamma, V]
+    const float* uniforms;         // [nseq, gamma + 1]
+    int32_t* accepted_len;         // [nseq]
+    int32_t* next_token;           // [nseq]
+    const int32_t* prefill_tokens; // [rps] (tok_mode 1)
+};
+
+struct ModelDims {
+    int32_t d, Hq, Hkv, hd, F, V, G;   // G = Hq / Hkv
+    float eps, inv_temp, temperature, scale;   // scale = 1/sqrt(hd)
+};
+
+// KV cache view.  K of (layer, seq): [Hkv][cap][hd]; V is stored transposed: [Hkv][hd][cap], so that
+// both MFMA operands of attention are 16-byte contiguous loads.  seq_off[b] = element offset of
+// sequence b inside one layer; layer_stride = elements per layer.
+template <typename T> struct KvView {
+    T* K;
+    T* V;
+    const int64_t* seq_off;
+    const int32_t* cap;
+    int32_t* len;
+    int32_t* pending;
+    int64_t layer_stride;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Weight re-tiling (model load).  Row-major W[N][K] -> tiles [N/16][K/KSTEP][64 lanes][16 bytes]
+// in MFMA A-operand order, so that one wave-wide 16-byte load reads 1 KB of contiguous memory.
+// interleave = 1: destination tile 2p comes from source tile p, tile 2p+1 from source tile
+// N/32 + p (gate and up projections of the same FFN columns end up adjacent).
+template <typename T>
+__global__ void retile_kernel(const T* __restrict__ src, T* __restrict__ dst, int N, int K, int interleave) {
+    constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
+    const int KS = K / KSTEP;
+    const size_t total = (size_t)(N / 16) * KS * 64;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(idx & 63);
+        const size_t tile = idx >> 6;
+        const int ks = (int)(tile % KS);
+        const int nt = (int)(tile / KS);
+        const int snt = interleave ? ((nt & 1) * (N / 32) + (nt >> 1)) : nt;
+        const int r = lane & 15, g = lane >> 4;
+        const u32x4* s = reinterpret_cast<const u32x4*>(src + (size_t)(snt * 16 + r) * K + ks * KSTEP + g * KF);
+        reinterpret_cast<u32x4*>(dst)[idx] = *s;
+    }
+}
+
+// K/V upload of one (seq, layer): host layout [Hkv][len][hd] -> K [Hkv][cap][hd], V [Hkv][hd][cap].
+template <typename T>
+__global__ void kv_scatter_kernel(const T* __restrict__ ksrc, const T* __restrict__ vsrc, T* __restrict__ K,
+                                  T* __restrict__ V, int Hkv, int len, int cap, int hd) {
+    const size_t total = (size_t)Hkv * len * hd;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        const int dcol = (int)(idx % hd);
+        const int pos = (int)((idx / hd) % len);
+        const int h = (int)(idx / ((size_t)hd * len));
+        K[((size_t)h * cap + pos) * hd + dcol] = ksrc[idx];
+        V[((size_t)h * hd + dcol) * cap + pos] = vsrc[idx];
+    }
+}
+
+template <typename T>
+__global__ void kv_gather_kernel(T* __restrict__ kdst, T* __restrict__ vdst, const T* __restrict__ K,
+                                 const T* __restrict__ V, int Hkv, int pos0, int n, int cap, int hd) {
+    const size_t total = (size_t)Hkv * n * hd;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        const int dcol = (int)(idx % hd);
+        const int pos = pos0 + (int)((idx / hd) % n);
+        const int h = (int)(idx / ((size_t)hd * n));
+        kdst[idx] = K[((size_t)h * cap + pos) * hd + dcol];
+        vdst[idx] = V[((size_t)h * hd + dcol) * cap + pos];
+    }
+}
+
+template <typename T>
+__global__ void to_f32_kernel(const T* __restrict__ src, float* __restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = Traits<T>::load(src + i);
+}
+
+__global__ void set_params_kernel(StepParams p, StepParams* dst) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *dst = p;
+}
+
+__global__ void set_state_kernel(int32_t* len, int32_t* pending, int seq, int l, int p) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) { len[seq] = l; pending[seq] = p; }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Step start (Eq. 2 input): one workgroup per query row.  Resolves the row's token and position,
+// gathers its embedding into the fp32 residual stream and writes the row's rotary cos/sin table
+// (angle = pos * base^(-2i/hd), evaluated in double so the table is correctly rounded fp32).
+template <typename T>
+__global__ __launch_bounds__(256) void step_begin_kernel(const StepParams* __restrict__ sp, ModelDims md,
+                                                         const T* __restrict__ embed, const int32_t* __restrict__ len,
+                                                         const int32_t* __restrict__ pending, float* __restrict__ x,
+                                                         float* __restrict__ cs, int32_t* __restrict__ row_tok,
+                                                         double log_base) {
+    const int r = blockIdx.x;
+    const int rps = sp->rps;
+    const int bi = r / rps, j = r % rps;
+    const int b = sp->seq_base + bi;
+    int tok;
+    if (sp->tok_mode == 1) tok = sp->prefill_tokens[j];
+    else tok = (j == 0) ? pending[b] : sp->draft_tokens[bi * sp->gamma + (j - 1)];
+    tok = min(max(tok, 0), md.V - 1);
+    const int pos = len[b] + j;
+    if (threadIdx.x == 0) row_tok[r] = tok;
+    const T* e = embed + (size_t)tok * md.d;
+    for (int c = threadIdx.x; c < md.d; c += 256) x[(size_t)r * md.d + c] = Traits<T>::load(e + c);
+    const int half = md.hd >> 1;
+    for (int i = threadIdx.x; i < half; i += 256) {
+        const double inv_freq = exp(-2.0 * (double)i / (double)md.hd * log_base);
+        double s, c;
+        sincos((double)pos * inv_freq, &s, &c);
+        cs[((size_t)r * half + i) * 2 + 0] = (float)c;
+        cs[((size_t)r * half + i) * 2 + 1] = (float)s;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Residual add + RMSNorm.  x[r] += sum_s part[s][r] (fixed order), then
+// xn[r] = x[r] * gain / sqrt(mean(x[r]^2) + eps) in the storage dtype (the next GEMM's operand),
+// optionally also in fp32 (final hidden state for the judge, Eq. 4).
+template <typename T>
+__global__ __launch_bounds__(256) void add_rmsnorm_kernel(int R, int d, float eps, float* __restrict__ x,
+                                                          const float* __restrict__ part, int nparts,
+                                                          const T* __restrict__ gain, T* __restrict__ xn,
+                                                          float* __restrict__ xn32) {
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    float* xr = x + (size_t)r * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        float v = xr[c];
+        for (int s = 0; s < nparts; ++s) v += part[((size_t)s * R + r) * d + c];
+        if (nparts) xr[c] = v;
+        ss += v * v;
+    }
+    ss = block_sum_256(ss, red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int c = threadIdx.x; c < d; c += 256) {
+        const float v = xr[c] * inv * Traits<T>::load(gain + c);
+        Traits<T>::store(xn + (size_t)r * d + c, v);
+        if (xn32) xn32[(size_t)r * d + c] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight-streaming skinny GEMM: Y[R][N] = X[R][K] * W[N][K]^T with W in the re-tiled layout.
+// Every byte of W is read exactly once; X (a few rows) is re-read from cache.
+// Workgroup (bx, by): n-tiles [bx*NT, bx*NT+NT), K-slice by of gridDim.y; its 4 waves split that
+// slice again and are summed through LDS in wave order (deterministic).
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_LOGITS = 2 };
+
+struct GemmArgs {
+    const void* Wt;     // tiled weights
+    const void* X;      // [MT*16][ldx] storage dtype, rows >= R are padding
+    int32_t ldx, K, N, R;
+    float* out;         // EPI_PARTIAL: [gridDim.y][R][N] fp32;  EPI_LOGITS: [R][N] fp32
+    void* act;          // EPI_SWIGLU: [MT*16][N/2] storage dtype = silu(gate) * up
+    float4* stats;      // EPI_LOGITS: [R][gridDim.x] (max, sum exp((l-max)/T), argmax as float bits, 0)
+    float inv_temp;     // 1/T, 0 when T = 0
+};
+
+template <typename T, int NT, int MT, int EPI>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
+    constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
+    constexpr int U = (NT * MT >= 8) ? 1 : (NT >= 2 ? 4 : 8);
+    __shared__ float red[4][NT * MT][256];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int KS = a.K / KSTEP;
+    const int nt0 = blockIdx.x * NT;
+    const int parts = gridDim.y * 4, part = blockIdx.y * 4 + w;
+    const int ks0 = (int)((long long)part * KS / parts), ks1 = (int)((long long)(part + 1) * KS / parts);
+    const u32x4* Wt = reinterpret_cast<const u32x4*>(a.Wt);
+    const T* X = reinterpret_cast<const T*>(a.X);
+
+    f32x4 acc[NT][MT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[t][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int ks = ks0;
+    for (; ks + U <= ks1; ks += U) {
+        Frag fa[U][NT], fb[U][MT];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                fa[u][t].u = __builtin_nontemporal_load(Wt + ((size_t)(nt0 + t) * KS + ks + u) * 64 + lane);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                fb[u][m].u = *reinterpret_cast<const u32x4*>(X + (size_t)(m * 16 + r) * a.ldx + (size_t)(ks + u) * KSTEP + g * KF);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int m = 0; m < MT; ++m) Traits<T>::mma(fa[u][t], fb[u][m], acc[t][m]);
+    }
+    for (; ks < ks1; ++ks) {
+        Frag fa[NT], fb[MT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) fa[t].u = __builtin_nontemporal_load(Wt + ((size_t)(nt0 + t) * KS + ks) * 64 + lane);
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+            fb[m].u = *reinterpret_cast<const u32x4*>(X + (size_t)(m * 16 + r) * a.ldx + (size_t)ks * KSTEP + g * KF);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) Traits<T>::mma(fa[t], fb[m], acc[t][m]);
+    }
+
+    // D[n = 4g+i][row = r]  ->  red[w][tile][row*16 + n]
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[w][t * MT + m][r * 16 + 4 * g + i] = acc[t][m][i];
+    __syncthreads();
+
+    const int tid = threadIdx.x;
+    const int er = tid >> 4, en = tid & 15;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int row = m * 16 + er;
+        float v[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            v[t] = ((red[0][t * MT + m][tid] + red[1][t * MT + m][tid]) + red[2][t * MT + m][tid]) + red[3][t * MT + m][tid];
+        if constexpr (EPI == EPI_PARTIAL) {
+            if (row < a.R) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    a.out[((size_t)blockIdx.y * a.R + row) * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
+            }
+        } else if constexpr (EPI == EPI_SWIGLU) {
+            static_assert(EPI != EPI_SWIGLU || NT == 2, "gate/up pairs");
+            if (row < a.R) {
+                const float gate = v[0], up = v[NT - 1];
+                const float y = gate / (1.0f + expf(-gate)) * up;
+                Traits<T>::store(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)blockIdx.x * 16 + en, y);
+            }
+        } else {
+            // logits + this workgroup's softmax partial for the row (16 lanes share a row)
+            float mx = v[0];
+            int arg = nt0 * 16 + en;
+#pragma unroll
+            for (int t = 1; t < NT; ++t)
+                if (v[t] > mx) { mx = v[t]; arg = (nt0 + t) * 16 + en; }
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) {
+                const float omx = __shfl_xor(mx, o, 64);
+                const int oarg = __shfl_xor(arg, o, 64);
+                if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+            }
+            float se = 0.f;
+            if (a.inv_temp > 0.f) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) se += expf((v[t] - mx) * a.inv_temp);
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) se += __shfl_xor(se, o, 64);
+            }
+            if (row < a.R) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) a.out[(size_t)row * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
+                if (en == 0) a.stats[(size_t)row * gridDim.x + blockIdx.x] = float4{mx, se, __int_as_float(arg), 0.f};
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rotary + KV append (one workgroup per query row).  Sums the QKV partials, rotates q and k to the
+// row's position, writes q for attention as [seq][kv head][m = gi*rps + j][hd] and appends k / v to
+// the cache at position len + j (v transposed).  A row whose position would fall outside the
+// sequence's capacity writes nothing (the host refuses such calls before launching).
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_kernel(const StepParams* __restrict__ sp, ModelDims md,
+                                                          const float* __restrict__ part, int nparts, int R,
+                                                          const float* __restrict__ cs, T* __restrict__ qbuf,
+                                                          int Mpad, KvView<T> kv, int layer) {
+    const int r = blockIdx.x;
+    const int rps = sp->rps;
+    const int bi = r / rps, j = r % rps;
+    const int b = sp->seq_base + bi;
+    const int hd = md.hd, half = hd >> 1;
+    const int Nq = md.Hq * hd, Nk = md.Hkv * hd, N = Nq + 2 * Nk;
+    const int cap = kv.cap[b];
+    const int pos = kv.len[b] + j;
+    const bool in_cap = pos < cap;
+    T* Kb = kv.K + (size_t)layer * kv.layer_stride + kv.seq_off[b];
+    T* Vb = kv.V + (size_t)layer * kv.layer_stride + kv.seq_off[b];
+    const float* csr = cs + (size_t)r * half * 2;
+    auto val = [&](int col) {
+        float v = 0.f;
+        for (int s = 0; s < nparts; ++s) v += part[((size_t)s * R + r) * N + col];
+        return v;
+    };
+    // q and k: pairs (i, i + half) of every head
+    const int npairs = (md.Hq + md.Hkv) * half;
+    for (int p = threadIdx.x; p < npairs; p += 256) {
+        const int head = p / half, i = p % half;
+        const float c = csr[2 * i], s = csr[2 * i + 1];
+        const int col = head * hd + i;                     // q heads then k heads are contiguous in N
+        const float lo = val(col), hi = val(col + half);
+        const float olo = lo * c - hi * s, ohi = hi * c + lo * s;
+        if (head < md.Hq) {
+            const int kvh = head / md.G, gi = head % md.G;
+            T* q = qbuf + (((size_t)bi * md.Hkv + kvh) * Mpad + (size_t)gi * rps + j) * hd;
+            Traits<T>::store(q + i, olo);
+            Traits<T>::store(q + i + half, ohi);
+        } else if (in_cap) {
+            const int kvh = head - md.Hq;
+            T* k = Kb + ((size_t)kvh * cap + pos) * hd;
+            Traits<T>::store(k + i, olo);
+            Traits<T>::store(k + i + half, ohi);
+        }
+    }
+    if (in_cap) {
+        for (int e = threadIdx.x; e < Nk; e += 256) {
+            const int kvh = e / hd, dcol = e % hd;
+            Traits<T>::store(Vb + ((size_t)kvh * hd + dcol) * cap + pos, val(Nq + Nk + e));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Multi-query causal decode attention, split over the keys (one wave per (chunk, kv head, q-tile
+// group, sequence)).  The M = G*rps query rows that share a kv head are the MFMA "columns":
+//   S^T[key][m]  = K[key][:] . Q[m][:]           (A = K rows,   B = Q rows)
+//   O^T[hd][m]  += V^T[hd][keys] . P^T[keys][m]  (A = V^T rows, B = the S^T accumulators, re-packed)
+// The key order inside a 4*KF-key step is permuted (S tile t, A row a <-> key KF*(a/4) + 4t + a%4)
+// so that a lane's S^T accumulators are exactly its B-operand elements of the second product:
+// no LDS transpose, no cross-lane traffic except the running-max reduction over the 4 lane groups.
+// Row m = gi*rps + j sees keys 0 .. len + j.  Writes the chunk's unnormalised O, running max and sum.
+template <typename T, int HD, int MQ>
+__global__ __launch_bounds__(64) void attn_partial_kernel(const StepParams* __restrict__ sp, ModelDims md,
+                                                          const T* __restrict__ qbuf, int Mpad, KvView<T> kv, int layer,
+                                                          int chunk_keys, int nchunk_max, float* __restrict__ opart,
+                                                          float2* __restrict__ mlpart) {
+    constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
+    constexpr int NS = KF / 4;       // S^T tiles per step of KSTEP keys
+    constexpr int KK = HD / KSTEP;   // contraction steps over the head dimension
+    constexpr int HT = HD / 16;
+    const int chunk = blockIdx.x, kvh = blockIdx.y % md.Hkv, qg = blockIdx.y / md.Hkv, bi = blockIdx.z;
+    const int b = sp->seq_base + bi;
+    const int rps = sp->rps;
+    const int M = md.G * rps;
+    const int L = kv.len[b], cap = kv.cap[b];
+    const int kv_end = min(L + rps, cap);
+    const int key_lo = chunk * chunk_keys;
+    if (key_lo >= kv_end) return;
+    const int key_hi = min(key_lo + chunk_keys, kv_end);
+    const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
+    const T* Kb = kv.K + (size_t)layer * kv.layer_stride + kv.seq_off[b] + (size_t)kvh * cap * HD;
+    const T* Vb = kv.V + (size_t)layer * kv.layer_stride + kv.seq_off[b] + (size_t)kvh * HD * cap;
+    const T* Q = qbuf + (((size_t)bi * md.Hkv + kvh) * Mpad + (size_t)qg * MQ * 16) * HD;
+
+    Frag qf[MQ][KK];
+#pragma unroll
+    for (int mq = 0; mq < MQ; ++mq)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            qf[mq][kk].u = *reinterpret_cast<const u32x4*>(Q + (size_t)(mq * 16 + r) * HD + kk * KSTEP + g * KF);
+
+    f32x4 o[HT][MQ];
+    float m_run[MQ], l_run[MQ];
+    int limit[MQ];
+#pragma unroll
+    for (int mq = 0; mq < MQ; ++mq) {
+        m_run[mq] = -INFINITY;
+        l_run[mq] = 0.f;
+        const int m = (qg * MQ + mq) * 16 + r;
+        limit[mq] = (m < M) ? L + (m % rps) : -1;      // last visible key; padding rows see nothing
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) o[ht][mq] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int key0 = key_lo; key0 < key_hi; key0 += KSTEP) {
+        f32x4 s[NS][MQ];
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+#pragma unroll
+            for (int mq = 0; mq < MQ; ++mq) s[t][mq] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const int krow = key0 + KF * (r >> 2) + 4 * t + (r & 3);
+            Frag kf[KK];
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+                kf[kk].u = *reinterpret_cast<const u32x4*>(Kb + (size_t)krow * HD + kk * KSTEP + g * KF);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+                for (int mq = 0; mq < MQ; ++mq) Traits<T>::mma(kf[kk], qf[mq][kk], s[t][mq]);
+        }
+        Frag vf[HT];
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+            vf[ht].u = *reinterpret_cast<const u32x4*>(Vb + (size_t)(ht * 16 + r) * cap + key0 + g * KF);
+
+        Frag pf[MQ];
+#pragma unroll
+        for (int mq = 0; mq < MQ; ++mq) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < NS; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int key = key0 + KF * g + 4 * t + i;
+                    const float v = (key <= limit[mq]) ? s[t][mq][i] * md.scale : -INFINITY;
+                    s[t][mq][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[mq], mx);
+            const bool dead = (m_new == -INFINITY);
+            const float alpha = dead ? 1.f : expf(m_run[mq] - m_new);
+            float psum = 0.f;
+#pragma unroll
+            for (int t = 0; t < NS; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p = dead ? 0.f : expf(s[t][mq][i] - m_new);
+                    psum += p;
+                    Traits<T>::pack(pf[mq], 4 * t + i, p);
+                }
+            l_run[mq] = l_run[mq] * alpha + psum;
+            m_run[mq] = m_new;
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht) o[ht][mq] *= alpha;
+        }
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int mq = 0; mq < MQ; ++mq) Traits<T>::mma(vf[ht], pf[mq], o[ht][mq]);
+    }
+
+    const size_t pbase = (((size_t)bi * md.Hkv + kvh) * nchunk_max + chunk) * Mpad;
+#pragma unroll
+    for (int mq = 0; mq < MQ; ++mq) {
+        float l = l_run[mq];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        const int m = (qg * MQ + mq) * 16 + r;
+        if (m < M) {
+            if (g == 0) mlpart[pbase + m] = float2{m_run[mq], l};
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) opart[(pbase + m) * HD + ht * 16 + 4 * g + i] = o[ht][mq][i];
+        }
+    }
+}
+
+// Merge of the key chunks (log-sum-exp weights, chunk order fixed) -> attention output rows in the
+// storage dtype, laid out [row][q head][hd] as the O-projection's operand.  One workgroup of HD
+// threads per (m, kv head, sequence).
+template <typename T, int HD>
+__global__ __launch_bounds__(HD) void attn_merge_kernel(const StepParams* __restrict__ sp, ModelDims md, int Mpad,
+                                                        const int32_t* __restrict__ len, const int32_t* __restrict__ capv,
+                                                        int chunk_keys, int nchunk_max, const float* __restrict__ opart,
+                                                        const float2* __restrict__ mlpart, T* __restrict__ attn_out) {
+    const int m = blockIdx.x, kvh = blockIdx.y, bi = blockIdx.z;
+    const int rps = sp->rps;
+    if (m >= md.G * rps) return;
+    const int b = sp->seq_base + bi;
+    const int kv_end = min(len[b] + rps, capv[b]);
+    const int nch = (kv_end + chunk_keys - 1) / chunk_keys;
+    const size_t pbase = ((size_t)bi * md.Hkv + kvh) * nchunk_max;
+    float mx = -INFINITY;
+    for (int c = 0; c < nch; ++c) mx = fmaxf(mx, mlpart[(pbase + c) * Mpad + m].x);
+    float den = 0.f, num = 0.f;
+    for (int c = 0; c < nch; ++c) {
+        const float2 ml = mlpart[(pbase + c) * Mpad + m];
+        const float wgt = (ml.x == -INFINITY) ? 0.f : expf(ml.x - mx);
+        den += wgt * ml.y;
+        if (wgt != 0.f) num += wgt * opart[((pbase + c) * Mpad + m) * HD + threadIdx.x];
+    }
+    const int gi = m / rps, j = m % rps;
+    const int qh = kvh * md.G + gi;
+    const size_t row = (size_t)bi * rps + j;
+    Traits<T>::store(attn_out + (row * md.Hq + qh) * HD + threadIdx.x, num / den);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Vocabulary softmax statistics of each row from the LM-head workgroups' partials:
+// row max, Z = sum exp((l - max)/T), lowest-index arg-max.  One workgroup per row.
+__global__ __launch_bounds__(256) void softmax_merge_kernel(const float4* __restrict__ stats, int nblk, float inv_temp,
+                                                            float4* __restrict__ rowstat) {
+    __shared__ float smx[4];
+    __shared__ int sarg[4];
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    const float4* s = stats + (size_t)r * nblk;
+    float mx = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int i = threadIdx.x; i < nblk; i += 256) {
+        const float4 v = s[i];
+        const int a = __float_as_int(v.z);
+        if (v.x > mx || (v.x == mx && a < arg)) { mx = v.x; arg = a; }
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float omx = __shfl_xor(mx, o, 64);
+        const int oarg = __shfl_xor(arg, o, 64);
+        if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+    }
+    if ((threadIdx.x & 63) == 0) { smx[threadIdx.x >> 6] = mx; sarg[threadIdx.x >> 6] = arg; }
+    __syncthreads();
+    mx = smx[0]; arg = sarg[0];
+    for (int w = 1; w < 4; ++w)
+        if (smx[w] > mx || (smx[w] == mx && sarg[w] < arg)) { mx = smx[w]; arg = sarg[w]; }
+    float z = 0.f;
+    if (inv_temp > 0.f)
+        for (int i = threadIdx.x; i < nblk; i += 256) {
+            const float4 v = s[i];
+            z += v.y * expf((v.x - mx) * inv_temp);
+        }
+    z = block_sum_256(z, red);
+    if (threadIdx.x == 0) rowstat[r] = float4{mx, z, __int_as_float(arg), 0.f};
+}
+
+// ---------------------------------------------------------------------------------------------
+// Judge verifier (Eq. 5): score = sigmoid(w . h + b) on the final, normed hidden state of the row
+// whose input is the draft token.  One workgroup per (sequence, draft position); entry j scores
+// d_{j+1}, i.e. block row j + 1.
+template <typename T>
+__global__ __launch_bounds__(256) void judge_kernel(const StepParams* __restrict__ sp, int d,
+                                                    const float* __restrict__ hn32, const T* __restrict__ w,
+                                                    const T* __restrict__ bias, float* __restrict__ scores) {
+    __shared__ float red[4];
+    const int gamma = sp->gamma;
+    const int bi = blockIdx.x / gamma, j = blockIdx.x % gamma;
+    const float* h = hn32 + ((size_t)bi * (gamma + 1) + j + 1) * d;
+    float acc = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) acc += h[c] * Traits<T>::load(w + c);
+    acc = block_sum_256(acc, red);
+    if (threadIdx.x == 0) {
+        const float z = acc + Traits<T>::load(bias);
+        scores[blockIdx.x] = 1.0f / (1.0f + expf(-z));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Ratio test (Eq. 3), OR with the judge (Sec. 3.2), first-rejection scan (Sec. 3.1): one wave per
+// sequence, lane j handles draft d_{j+1}:  accept iff u*q(d) < p(d)  with p(d) read from block row j,
+// or score > theta.  accepted_len = number of leading accepted lanes (ballot + count trailing ones).
+__global__ __launch_bounds__(64) void accept_scan_kernel(const StepParams* __restrict__ sp, int V, float inv_temp,
+                                                         const float* __restrict__ logits,
+                                                         const float4* __restrict__ rowstat,
+                                                         const float* __restrict__ scores,
+                                                         float* __restrict__ p_at_d, int32_t* __restrict__ bits,
+                                                         int32_t* __restrict__ nacc) {
+    const int bi = blockIdx.x, j = threadIdx.x;
+    const int gamma = sp->gamma;
+    bool ok = false;
+    if (j < gamma) {
+        const int row = bi * (gamma + 1) + j;
+        int tok = sp->draft_tokens[bi * gamma + j];
+        tok = min(max(tok, 0), V - 1);
+        const float4 st = rowstat[row];
+        float p;
+        if (inv_temp > 0.f) p = expf((logits[(size_t)row * V + tok] - st.x) * inv_temp) / st.y;
+        else p = (tok == __float_as_int(st.z)) ? 1.f : 0.f;
+        const float q = sp->draft_probs[((size_t)bi * gamma + j) * V + tok];
+        const float u = sp->uniforms[bi * (gamma + 1) + j];
+        const bool a = (u * q < p);
+        const bool jd = scores[bi * gamma + j] > sp->theta;
+        ok = (sp->mode == 1) ? a : (sp->mode == 2) ? jd : (a || jd);
+        p_at_d[bi * gamma + j] = p;
+        bits[bi * gamma + j] = (a ? 1 : 0) | (jd ? 2 : 0);
+    }
+    const unsigned long long mask = __ballot(ok);
+    if (j == 0) {
+        const int n = __builtin_ctzll(~mask);      // lanes >= gamma vote false, so n <= gamma
+        nacc[bi] = n;
+        sp->accepted_len[bi] = n;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Extra token (Sec. 3.1 bonus / Sec. 2.2 residual), inverse CDF in vocabulary order with one
+// uniform.  Weights are formed in double from the fp32 logits so that the draw is reproducible
+// from those logits to ~1e-15:  e_k = exp((l_k - max)/T),  Z = sum e_k,
+//   all accepted:  w_k = e_k          else:  w_k = max(0, e_k - Z * q_k)   (q = draft law of the
+// first rejected token);  if sum w = 0 fall back to w = e.
+// Element k belongs to slab k / slab_len; slab s is owned by thread s % 256 of workgroup s / 256.
+//   pass 1 (resample_e):    per-slab sums of e               -> epart
+//   pass 2 (resample_w):    Z from epart, per-slab sums of w -> wpart
+//   pass 3 (resample_pick): scan the slab sums, walk the hit slab, commit the sequence state.
+struct ResampleArgs {
+    int32_t V, nslab, slab_len;   // nslab = 256 * gridDim.x of passes 1, 2
+    float inv_temp;
+    const float* logits;
+    const float4* rowstat;
+    const int32_t* nacc;
+    double* epart;    // [nseq][nslab]
+    double* wpart;    // [nseq][nslab]
+};
+
+__device__ __forceinline__ double e_of(float logit, float mx, float inv_temp) {
+    return exp(((double)logit - (double)mx) * (double)inv_temp);
+}
+
+__global__ __launch_bounds__(256) void resample_e_kernel(const StepParams* __restrict__ sp, ResampleArgs a) {
+    const int bi = blockIdx.y, slab = blockIdx.x * 256 + threadIdx.x;
+    const int gamma = sp->gamma;
+    const int row = bi * (gamma + 1) + a.nacc[bi];
+    const float mx = a.rowstat[row].x;
+    const float* l = a.logits + (size_t)row * a.V;
+    const int k0 = slab * a.slab_len, k1 = min(a.V, k0 + a.slab_len);
+    double s = 0.0;
+    for (int k = k0; k < k1; ++k) s += e_of(l[k], mx, a.inv_temp);
+    a.epart[(size_t)bi * a.nslab + slab] = s;
+}
+
+__device__ __forceinline__ double total_of(const double* part, int n, double* lds4) {
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) s += part[i];
+    return block_sum_256(s, lds4);
+}
+
+__global__ __launch_bounds__(256) void resample_w_kernel(const StepParams* __restrict__ sp, ResampleArgs a) {
+    __shared__ double red[4];
+    const int bi = blockIdx.y, slab = blockIdx.x * 256 + threadIdx.x;
+    const int gamma = sp->gamma;
+    const int n = a.nacc[bi];
+    const double Z = total_of(a.epart + (size_t)bi * a.nslab, a.nslab, red);
+    const int row = bi * (gamma + 1) + n;
+    const float mx = a.rowstat[row].x;
+    const float* l = a.logits + (size_t)row * a.V;
+    const int k0 = slab * a.slab_len, k1 = min(a.V, k0 + a.slab_len);
+    double s = 0.0;
+    if (n < gamma) {
+        const float* q = sp->draft_probs + ((size_t)bi * gamma + n) * a.V;
+        for (int k = k0; k < k1; ++k) s += fmax(0.0, e_of(l[k], mx, a.inv_temp) - Z * (double)q[k]);
+    }
+    a.wpart[(size_t)bi * a.nslab + slab] = s;
+}
+
+__global__ __launch_bounds__(256) void resample_pick_kernel(const StepParams* __restrict__ sp, ResampleArgs a,
+                                                            int32_t* __restrict__ len, int32_t* __restrict__ pending) {
+    __shared__ double red[4];
+    __shared__ double wave_tot[4];
+    __shared__ double before_of[257];
+    __shared__ int hit_slab;
+    __shared__ double hit_before;
+    const int bi = blockIdx.x;
+    const int b = sp->seq_base + bi;
+    const int gamma = sp->gamma;
+    const int n = a.nacc[bi];
+    const int row = bi * (gamma + 1) + n;
+    const float4 st = a.rowstat[row];
+    int next = -1;
+    if (!(a.inv_temp > 0.f)) {
+        next = __float_as_int(st.z);                 // one-hot target: residual and bonus are the arg-max
+    } else {
+        const double* ep = a.epart + (size_t)bi * a.nslab;
+        const double* wp = a.wpart + (size_t)bi * a.nslab;
+        const double Z = total_of(ep, a.nslab, red);
+        double W = (n < gamma) ? total_of(wp, a.nslab, red) : 0.0;
+        const bool use_e = (n == gamma) || !(W > 0.0);
+        const double* part = use_e ? ep : wp;
+        if (use_e) W = Z;
+        const double target = (double)sp->uniforms[bi * (gamma + 1) + gamma] * W;
+        // exclusive scan of the slab sums in slab order: thread t owns slabs [t*per, t*per+per)
+        const int per = a.nslab / 256;
+        double mine = 0.0;
+        for (int i = 0; i < per; ++i) mine += part[threadIdx.x * per + i];
+        double incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double t = __shfl_up(incl, o, 64);
+            if ((int)(threadIdx.x & 63) >= o) incl += t;
+        }
+        if ((threadIdx.x & 63) == 63) wave_tot[threadIdx.x >> 6] = incl;
+        if (threadIdx.x == 0) { hit_slab = 0x7fffffff; hit_before = 0.0; before_of[256] = INFINITY; }
+        __syncthreads();
+        double before = incl - mine;
+        for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) before += wave_tot[w];
+        before_of[threadIdx.x] = before;
+        __syncthreads();
+        // owner: the thread whose range of the cumulative sum holds the target (lowest wins a tie)
+        if (before <= target && target < before_of[threadIdx.x + 1] && mine > 0.0) atomicMin(&hit_slab, (int)threadIdx.x);
+        __syncthreads();
+        const int owner = hit_slab;
+        __syncthreads();
+        if ((int)threadIdx.x == owner) {
+            double c = before;
+            int hs = -1, last_pos = -1;
+            double hb = 0.0, last_before = 0.0;
+            for (int i = 0; i < per; ++i) {
+                const double v = part[threadIdx.x * per + i];
+                if (v > 0.0) { last_pos = threadIdx.x * per + i; last_before = c; }
+                if (c + v > target) { hs = threadIdx.x * per + i; hb = c; break; }
+                c += v;
+            }
+            if (hs < 0) { hs = last_pos; hb = last_before; }
+            hit_slab = hs;
+            hit_before = hb;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const float mx = st.x;
+            const float* l = a.logits + (size_t)row * a.V;
+            const float* q = (n < gamma) ? sp->draft_probs + ((size_t)bi * gamma + n) * a.V : nullptr;
+            auto weight = [&](int k) {
+                const double e = e_of(l[k], mx, a.inv_temp);
+                return use_e ? e : fmax(0.0, e - Z * (double)q[k]);
+            };
+            if (owner != 0x7fffffff && hit_slab >= 0) {
+                const int k0 = hit_slab * a.slab_len, k1 = min(a.V, k0 + a.slab_len);
+                double c = hit_before;
+                int last_pos = -1;
+                for (int k = k0; k < k1; ++k) {
+                    const double v = weight(k);
+                    if (v > 0.0) last_pos = k;
+                    c += v;
+                    if (c > target) { next = k; break; }
+                }
+                if (next < 0) next = last_pos;
+            }
+            if (next < 0) {            // rounding at the very top of the CDF: last token with weight
+                for (int k = a.V - 1; k >= 0; --k)
+                    if (weight(k) > 0.0) { next = k; break; }
+                if (next < 0) next = __float_as_int(st.z);
+            }
+        }
+    }
+    if (threadIdx.x == 0) {
+        sp->next_token[bi] = next;
+        len[b] += 1 + n;           // commit: rows beyond the new length are dead
+        pending[b] = next;
+    }
+}
+
+// Prefill bookkeeping: advance the length by the chunk; after the last chunk the pending token is the
+// arg-max continuation of the last prompt token.
+__global__ void prefill_commit_kernel(const StepParams* __restrict__ sp, const float4* __restrict__ rowstat,
+                                      int32_t* __restrict__ len, int32_t* __restrict__ pending, int last) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        const int b = sp->seq_base;
+        len[b] += sp->rps;
+        if (last) pending[b] = __float_as_int(rowstat[sp->rps - 1].z);
+    }
+}
+
+}  // namespace sj

@@ -1,0 +1,803 @@
+// Host side of the C ABI declared in include/sj.h: argument checking, memory ownership, weight
+// upload / re-tiling, and the kernel sequence of one verification step.
+#include "../../include/sj.h"
+#include "sj_kernels.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+using namespace sj;
+
+// ------------------------------------------------------------------------------------------------
+// errors
+
+static thread_local std::string g_err;
+
+static int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIPCHK(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess) return fail(SJ_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+#define LAUNCHCHK(name)                                                                          \
+    do {                                                                                         \
+        hipError_t e_ = hipGetLastError();                                                       \
+        if (e_ != hipSuccess) return fail(SJ_EHIP, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// ------------------------------------------------------------------------------------------------
+// objects
+
+struct LayerW {
+    void *attn_norm = nullptr, *wqkv = nullptr, *wo = nullptr, *ffn_norm = nullptr, *wgu = nullptr, *wd = nullptr;
+};
+
+struct sj_model {
+    sj_config cfg{};
+    ModelDims md{};
+    size_t esz = 0;
+    void *embed = nullptr, *final_norm = nullptr, *lm_head = nullptr, *judge_w = nullptr, *judge_b = nullptr;
+    std::vector<LayerW> layers;
+    std::vector<void*> allocs;
+    int64_t weight_bytes = 0;
+    int device = 0;
+};
+
+struct sj_kv {
+    const sj_model* m = nullptr;
+    int batch = 0, max_rows = 0, rpad = 0, mpad = 0;
+    std::vector<int32_t> cap, len_upper;
+    std::vector<int64_t> seq_off;
+    int64_t layer_stride = 0;
+    void *K = nullptr, *V = nullptr;
+    int64_t* seq_off_dev = nullptr;
+    int32_t *cap_dev = nullptr, *len_dev = nullptr, *pending_dev = nullptr;
+    // workspace
+    StepParams* sp_dev = nullptr;
+    float *x = nullptr, *hn32 = nullptr, *part = nullptr, *opart = nullptr, *cs = nullptr, *logits = nullptr;
+    float *scores = nullptr, *p_at_d = nullptr;
+    void *xn = nullptr, *qbuf = nullptr, *attn_out = nullptr, *act = nullptr;
+    float2* mlpart = nullptr;
+    float4 *stats = nullptr, *rowstat = nullptr;
+    int32_t *row_tok = nullptr, *bits = nullptr, *nacc = nullptr, *prefill_tok = nullptr;
+    double *epart = nullptr, *wpart = nullptr;
+    int chunk_keys = 64, nchunk_max = 1, nslab = 0, slab_len = 0;
+    int split_qkv = 1, split_o = 1, split_d = 1, lm_nt = 2;
+    int mode = SJ_MODE_TWO_STAGE;
+    int last_gamma = 0, last_rows = 0;
+    std::vector<void*> allocs;
+};
+
+static size_t esz_of(int dtype) { return dtype == SJ_DTYPE_FP32 ? 4 : 2; }
+
+template <typename P> static int dev_alloc(std::vector<void*>& owner, P** p, size_t bytes, bool zero = true) {
+    void* q = nullptr;
+    if (bytes == 0) bytes = 256;
+    hipError_t e = hipMalloc(&q, bytes);
+    if (e != hipSuccess) return fail(e == hipErrorOutOfMemory ? SJ_ENOMEM : SJ_EHIP, "hipMalloc(%zu) failed: %s", bytes,
+                                     hipGetErrorString(e));
+    owner.push_back(q);
+    if (zero) HIPCHK(hipMemset(q, 0, bytes));
+    *p = reinterpret_cast<P*>(q);
+    return SJ_OK;
+}
+
+static void free_all(std::vector<void*>& v) {
+    for (void* p : v) (void)hipFree(p);
+    v.clear();
+}
+
+// ------------------------------------------------------------------------------------------------
+// model load
+
+static int check_config(const sj_config* c) {
+    if (!c) return fail(SJ_EINVAL, "config is null");
+    if (c->dtype != SJ_DTYPE_FP32 && c->dtype != SJ_DTYPE_BF16) return fail(SJ_EINVAL, "dtype must be 0 (fp32) or 1 (bf16)");
+    if (c->n_layers < 0 || c->d_model <= 0 || c->vocab <= 0) return fail(SJ_EINVAL, "non-positive model dimension");
+    if (c->d_model % 32 || c->vocab % 32) return fail(SJ_EINVAL, "d_model and vocab must be multiples of 32");
+    if (c->max_gamma < 1 || c->max_gamma > 63) return fail(SJ_EINVAL, "max_gamma must be in 1..63");
+    if (!(c->temperature >= 0.f)) return fail(SJ_EINVAL, "temperature must be >= 0");
+    if (c->n_layers > 0) {
+        if (c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->d_ffn <= 0) return fail(SJ_EINVAL, "non-positive model dimension");
+        if (c->head_dim != 64 && c->head_dim != 128) return fail(SJ_EINVAL, "head_dim must be 64 or 128");
+        if (c->n_q_heads % c->n_kv_heads) return fail(SJ_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+        if (c->d_ffn % 32) return fail(SJ_EINVAL, "d_ffn must be a multiple of 32");
+        if (!(c->rope_base > 1.f) || !(c->rms_eps >= 0.f)) return fail(SJ_EINVAL, "bad rope_base / rms_eps");
+    }
+    return SJ_OK;
+}
+
+namespace {
+struct Loader {
+    sj_model* m;
+    sj_tensor_fn fn;
+    void* user;
+    void* host = nullptr;      // pinned staging
+    void* dev = nullptr;       // device staging (source of the re-tile)
+    size_t cap = 0;
+
+    int fetch(int id, int layer, size_t off_bytes, size_t bytes) {
+        if (off_bytes + bytes > cap) return fail(SJ_EINVAL, "internal: staging too small");
+        if (fn(user, id, layer, (char*)host + off_bytes, bytes) != 0)
+            return fail(SJ_ECALLBACK, "tensor provider failed for tensor %d layer %d", id, layer);
+        return SJ_OK;
+    }
+    int plain(int id, int layer, size_t elems, void** out) {       // vectors, embedding: kept row-major
+        const size_t bytes = elems * m->esz;
+        int rc = fetch(id, layer, 0, bytes);
+        if (rc) return rc;
+        rc = dev_alloc(m->allocs, out, bytes, false);
+        if (rc) return rc;
+        HIPCHK(hipMemcpy(*out, host, bytes, hipMemcpyHostToDevice));
+        return SJ_OK;
+    }
+    // one or more [n_i, K] matrices stacked along N, re-tiled into one device matrix
+    int tiled(const int* ids, const int* ns, int count, int layer, int K, int interleave, void** out) {
+        size_t off = 0;
+        int N = 0;
+        for (int i = 0; i < count; ++i) {
+            const size_t bytes = (size_t)ns[i] * K * m->esz;
+            int rc = fetch(ids[i], layer, off, bytes);
+            if (rc) return rc;
+            off += bytes;
+            N += ns[i];
+        }
+        HIPCHK(hipMemcpy(dev, host, off, hipMemcpyHostToDevice));
+        int rc = dev_alloc(m->allocs, out, off, false);
+        if (rc) return rc;
+        const int blocks = 4096;
+        if (m->cfg.dtype == SJ_DTYPE_FP32)
+            retile_kernel<float><<<blocks, 256>>>((const float*)dev, (float*)*out, N, K, interleave);
+        else
+            retile_kernel<bf16_t><<<blocks, 256>>>((const bf16_t*)dev, (bf16_t*)*out, N, K, interleave);
+        LAUNCHCHK("retile");
+        HIPCHK(hipDeviceSynchronize());
+        m->weight_bytes += (int64_t)off;
+        return SJ_OK;
+    }
+};
+}  // namespace
+
+extern "C" int sj_model_load(const sj_config* cfg, sj_tensor_fn provider, void* user, sj_model** out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!provider || !out) return fail(SJ_EINVAL, "provider / out is null");
+    sj_model* m = new (std::nothrow) sj_model();
+    if (!m) return fail(SJ_ENOMEM, "host allocation failed");
+    m->cfg = *cfg;
+    m->esz = esz_of(cfg->dtype);
+    const int d = cfg->d_model, hd = cfg->head_dim, V = cfg->vocab, F = cfg->d_ffn;
+    const int Nq = cfg->n_q_heads * hd, Nk = cfg->n_kv_heads * hd;
+    ModelDims& md = m->md;
+    md.d = d; md.Hq = cfg->n_q_heads; md.Hkv = cfg->n_kv_heads; md.hd = hd; md.F = F; md.V = V;
+    md.G = cfg->n_layers > 0 ? cfg->n_q_heads / cfg->n_kv_heads : 1;
+    md.eps = cfg->rms_eps;
+    md.temperature = cfg->temperature;
+    md.inv_temp = cfg->temperature > 0.f ? 1.0f / cfg->temperature : 0.f;
+    md.scale = cfg->n_layers > 0 ? (float)(1.0 / std::sqrt((double)hd)) : 1.f;
+
+    Loader ld{m, provider, user};
+    size_t need = (size_t)V * d;
+    if (cfg->n_layers > 0) need = std::max({need, (size_t)(Nq + 2 * Nk) * d, (size_t)2 * F * d});
+    ld.cap = need * m->esz;
+    auto cleanup = [&](int code) {
+        if (ld.host) (void)hipHostFree(ld.host);
+        if (ld.dev) (void)hipFree(ld.dev);
+        if (code) { free_all(m->allocs); delete m; }
+        return code;
+    };
+    if (hipGetDevice(&m->device) != hipSuccess) return cleanup(fail(SJ_EHIP, "no HIP device available"));
+    {
+        hipError_t e = hipHostMalloc(&ld.host, ld.cap, hipHostMallocDefault);
+        if (e != hipSuccess) { ld.host = nullptr; return cleanup(fail(SJ_EHIP, "hipHostMalloc(%zu) failed: %s", ld.cap, hipGetErrorString(e))); }
+        e = hipMalloc(&ld.dev, ld.cap);
+        if (e != hipSuccess) { ld.dev = nullptr; return cleanup(fail(SJ_ENOMEM, "hipMalloc(%zu) failed: %s", ld.cap, hipGetErrorString(e))); }
+    }
+    m->layers.resize(cfg->n_layers);
+    if (cfg->n_layers > 0) {
+        if ((rc = ld.plain(SJ_T_EMBED, -1, (size_t)V * d, &m->embed))) return cleanup(rc);
+        if ((rc = ld.plain(SJ_T_FINAL_NORM, -1, d, &m->final_norm))) return cleanup(rc);
+    }
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        LayerW& L = m->layers[l];
+        if ((rc = ld.plain(SJ_T_ATTN_NORM, l, d, &L.attn_norm))) return cleanup(rc);
+        if ((rc = ld.plain(SJ_T_FFN_NORM, l, d, &L.ffn_norm))) return cleanup(rc);
+        const int qkv_ids[3] = {SJ_T_WQ, SJ_T_WK, SJ_T_WV}, qkv_ns[3] = {Nq, Nk, Nk};
+        if ((rc = ld.tiled(qkv_ids, qkv_ns, 3, l, d, 0, &L.wqkv))) return cleanup(rc);
+        const int o_id = SJ_T_WO, o_n = d;
+        if ((rc = ld.tiled(&o_id, &o_n, 1, l, Nq, 0, &L.wo))) return cleanup(rc);
+        const int gu_ids[2] = {SJ_T_W_GATE, SJ_T_W_UP}, gu_ns[2] = {F, F};
+        if ((rc = ld.tiled(gu_ids, gu_ns, 2, l, d, 1, &L.wgu))) return cleanup(rc);
+        const int d_id = SJ_T_W_DOWN, d_n = d;
+        if ((rc = ld.tiled(&d_id, &d_n, 1, l, F, 0, &L.wd))) return cleanup(rc);
+    }
+    const int lm_id = SJ_T_LM_HEAD, lm_n = V;
+    if ((rc = ld.tiled(&lm_id, &lm_n, 1, -1, d, 0, &m->lm_head))) return cleanup(rc);
+    if ((rc = ld.plain(SJ_T_JUDGE_W, -1, d, &m->judge_w))) return cleanup(rc);
+    if ((rc = ld.plain(SJ_T_JUDGE_B, -1, 1, &m->judge_b))) return cleanup(rc);
+    cleanup(0);
+    *out = m;
+    return SJ_OK;
+}
+
+extern "C" int sj_model_free(sj_model* m) {
+    if (!m) return fail(SJ_EINVAL, "model is null");
+    free_all(m->allocs);
+    delete m;
+    return SJ_OK;
+}
+
+extern "C" int64_t sj_model_weight_bytes(const sj_model* m) { return m ? m->weight_bytes : 0; }
+
+// ------------------------------------------------------------------------------------------------
+// kv / workspace
+
+static int choose_split(int groups, int ksteps) {
+    int s = (768 + groups - 1) / groups;
+    s = std::min(s, std::max(1, ksteps / 16));
+    return std::max(1, std::min(s, 8));
+}
+
+extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* capacity, sj_kv** out) {
+    if (!m || !out) return fail(SJ_EINVAL, "model / out is null");
+    if (batch < 1 || batch > 4096) return fail(SJ_EINVAL, "batch must be in 1..4096");
+    const sj_config& c = m->cfg;
+    if (c.n_layers > 0 && !capacity) return fail(SJ_EINVAL, "capacity is null");
+    sj_kv* kv = new (std::nothrow) sj_kv();
+    if (!kv) return fail(SJ_ENOMEM, "host allocation failed");
+    kv->m = m;
+    kv->batch = batch;
+    kv->cap.assign(batch, 64);
+    kv->len_upper.assign(batch, 0);
+    kv->seq_off.assign(batch, 0);
+    int64_t off = 0;
+    int cap_max = 64;
+    for (int b = 0; b < batch; ++b) {
+        int cp = 64;
+        if (c.n_layers > 0) {
+            if (capacity[b] < 1 || capacity[b] > (1 << 24)) { delete kv; return fail(SJ_EINVAL, "capacity[%d] out of range", b); }
+            cp = (capacity[b] + 63) / 64 * 64;
+        }
+        kv->cap[b] = cp;
+        kv->seq_off[b] = off;
+        off += (int64_t)cp * c.n_kv_heads * c.head_dim;
+        cap_max = std::max(cap_max, cp);
+    }
+    kv->layer_stride = off;
+    const int R = batch * (c.max_gamma + 1);
+    kv->max_rows = R;
+    kv->rpad = (R + 15) / 16 * 16;
+    const int d = c.d_model, V = c.vocab;
+    auto& A = kv->allocs;
+    int rc = SJ_OK;
+    auto bail = [&](int code) { free_all(kv->allocs); delete kv; return code; };
+#define ALLOC(ptr, bytes) if ((rc = dev_alloc(A, &(ptr), (bytes)))) return bail(rc)
+    ALLOC(kv->seq_off_dev, sizeof(int64_t) * batch);
+    ALLOC(kv->cap_dev, sizeof(int32_t) * batch);
+    ALLOC(kv->len_dev, sizeof(int32_t) * batch);
+    ALLOC(kv->pending_dev, sizeof(int32_t) * batch);
+    ALLOC(kv->sp_dev, sizeof(StepParams));
+    ALLOC(kv->xn, (size_t)kv->rpad * d * m->esz);
+    ALLOC(kv->hn32, (size_t)R * d * 4);
+    ALLOC(kv->row_tok, (size_t)R * 4);
+    ALLOC(kv->logits, (size_t)R * V * 4);
+    kv->lm_nt = 2;
+    ALLOC(kv->stats, (size_t)R * (V / 16) * sizeof(float4));
+    ALLOC(kv->rowstat, (size_t)R * sizeof(float4));
+    ALLOC(kv->scores, (size_t)R * 4);
+    ALLOC(kv->p_at_d, (size_t)R * 4);
+    ALLOC(kv->bits, (size_t)R * 4);
+    ALLOC(kv->nacc, (size_t)batch * 4);
+    // resampling slabs: about 16 vocabulary entries per thread
+    {
+        int blocks = std::max(1, (V / 16 + 255) / 256);
+        kv->nslab = blocks * 256;
+        kv->slab_len = (V + kv->nslab - 1) / kv->nslab;
+    }
+    ALLOC(kv->epart, (size_t)batch * kv->nslab * 8);
+    ALLOC(kv->wpart, (size_t)batch * kv->nslab * 8);
+    if (c.n_layers > 0) {
+        const int hd = c.head_dim, Nq = c.n_q_heads * hd, Nk = c.n_kv_heads * hd, F = c.d_ffn;
+        const int G = c.n_q_heads / c.n_kv_heads;
+        const int kstep = (c.dtype == SJ_DTYPE_FP32) ? 16 : 32;
+        kv->split_qkv = choose_split((Nq + 2 * Nk) / 16, d / kstep);
+        kv->split_o = choose_split(d / 16, Nq / kstep);
+        kv->split_d = choose_split(d / 16, F / kstep);
+        size_t part_elems = std::max({(size_t)kv->split_qkv * R * (Nq + 2 * Nk), (size_t)kv->split_o * R * d,
+                                      (size_t)kv->split_d * R * d});
+        kv->mpad = (G * (c.max_gamma + 1) + 15) / 16 * 16;
+        // key chunks: enough waves to fill the chip, at least 64 keys each
+        {
+            const int64_t total_keys = off / ((int64_t)c.n_kv_heads * hd);
+            int ck = 64;
+            while (ck < 1024 && total_keys * c.n_kv_heads / ck > 4096) ck *= 2;
+            kv->chunk_keys = ck;
+            kv->nchunk_max = (cap_max + ck - 1) / ck;
+        }
+        ALLOC(kv->K, (size_t)kv->layer_stride * c.n_layers * m->esz);
+        ALLOC(kv->V, (size_t)kv->layer_stride * c.n_layers * m->esz);
+        ALLOC(kv->x, (size_t)R * d * 4);
+        ALLOC(kv->part, part_elems * 4);
+        ALLOC(kv->qbuf, (size_t)batch * c.n_kv_heads * kv->mpad * hd * m->esz);
+        ALLOC(kv->opart, (size_t)batch * c.n_kv_heads * kv->nchunk_max * kv->mpad * hd * 4);
+        ALLOC(kv->mlpart, (size_t)batch * c.n_kv_heads * kv->nchunk_max * kv->mpad * sizeof(float2));
+        ALLOC(kv->attn_out, (size_t)kv->rpad * Nq * m->esz);
+        ALLOC(kv->act, (size_t)kv->rpad * F * m->esz);
+        ALLOC(kv->cs, (size_t)R * hd * 4);
+        ALLOC(kv->prefill_tok, (size_t)R * 4);
+    }
+#undef ALLOC
+    if (hipMemcpy(kv->seq_off_dev, kv->seq_off.data(), sizeof(int64_t) * batch, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(kv->cap_dev, kv->cap.data(), sizeof(int32_t) * batch, hipMemcpyHostToDevice) != hipSuccess)
+        return bail(fail(SJ_EHIP, "hipMemcpy of cache geometry failed"));
+    *out = kv;
+    return SJ_OK;
+}
+
+extern "C" int sj_kv_free(sj_kv* kv) {
+    if (!kv) return fail(SJ_EINVAL, "kv is null");
+    free_all(kv->allocs);
+    delete kv;
+    return SJ_OK;
+}
+
+extern "C" int sj_set_mode(sj_kv* kv, int32_t mode) {
+    if (!kv) return fail(SJ_EINVAL, "kv is null");
+    if (mode < 0 || mode > 2) return fail(SJ_EINVAL, "mode must be 0, 1 or 2");
+    kv->mode = mode;
+    return SJ_OK;
+}
+
+static int check_seq_layer(const sj_kv* kv, int seq, int layer) {
+    if (!kv) return fail(SJ_EINVAL, "kv is null");
+    if (kv->m->cfg.n_layers == 0) return fail(SJ_EINVAL, "head-only model has no cache");
+    if (seq < 0 || seq >= kv->batch) return fail(SJ_EINVAL, "seq %d out of range", seq);
+    if (layer < 0 || layer >= kv->m->cfg.n_layers) return fail(SJ_EINVAL, "layer %d out of range", layer);
+    return SJ_OK;
+}
+
+extern "C" int sj_kv_set_layer(sj_kv* kv, int32_t seq, int32_t layer, const void* k_host, const void* v_host, int32_t len) {
+    int rc = check_seq_layer(kv, seq, layer);
+    if (rc) return rc;
+    if (!k_host || !v_host) return fail(SJ_EINVAL, "k_host / v_host is null");
+    if (len < 0 || len > kv->cap[seq]) return fail(SJ_ECAPACITY, "len %d exceeds capacity %d", len, kv->cap[seq]);
+    if (len == 0) return SJ_OK;
+    const sj_config& c = kv->m->cfg;
+    const size_t esz = kv->m->esz, bytes = (size_t)c.n_kv_heads * len * c.head_dim * esz;
+    void *ks = nullptr, *vs = nullptr;
+    HIPCHK(hipMalloc(&ks, bytes));
+    if (hipMalloc(&vs, bytes) != hipSuccess) { (void)hipFree(ks); return fail(SJ_ENOMEM, "hipMalloc failed"); }
+    hipError_t e1 = hipMemcpy(ks, k_host, bytes, hipMemcpyHostToDevice);
+    hipError_t e2 = hipMemcpy(vs, v_host, bytes, hipMemcpyHostToDevice);
+    if (e1 == hipSuccess && e2 == hipSuccess) {
+        const size_t off = (size_t)layer * kv->layer_stride + kv->seq_off[seq];
+        if (c.dtype == SJ_DTYPE_FP32)
+            kv_scatter_kernel<float><<<1024, 256>>>((const float*)ks, (const float*)vs, (float*)kv->K + off,
+                                                     (float*)kv->V + off, c.n_kv_heads, len, kv->cap[seq], c.head_dim);
+        else
+            kv_scatter_kernel<bf16_t><<<1024, 256>>>((const bf16_t*)ks, (const bf16_t*)vs, (bf16_t*)kv->K + off,
+                                                      (bf16_t*)kv->V + off, c.n_kv_heads, len, kv->cap[seq], c.head_dim);
+        e1 = hipGetLastError();
+        e2 = hipDeviceSynchronize();
+    }
+    (void)hipFree(ks);
+    (void)hipFree(vs);
+    if (e1 != hipSuccess || e2 != hipSuccess)
+        return fail(SJ_EHIP, "cache upload failed: %s", hipGetErrorString(e1 != hipSuccess ? e1 : e2));
+    return SJ_OK;
+}
+
+extern "C" int sj_kv_set_state(sj_kv* kv, int32_t seq, int32_t len, int32_t pending_token) {
+    if (!kv) return fail(SJ_EINVAL, "kv is null");
+    if (seq < 0 || seq >= kv->batch) return fail(SJ_EINVAL, "seq %d out of range", seq);
+    if (len < 0 || len > kv->cap[seq]) return fail(SJ_ECAPACITY, "len %d exceeds capacity %d", len, kv->cap[seq]);
+    if (pending_token < 0 || pending_token >= kv->m->cfg.vocab) return fail(SJ_EINVAL, "pending token out of range");
+    HIPCHK(hipDeviceSynchronize());
+    set_state_kernel<<<1, 1>>>(kv->len_dev, kv->pending_dev, seq, len, pending_token);
+    LAUNCHCHK("set_state");
+    HIPCHK(hipDeviceSynchronize());
+    kv->len_upper[seq] = len;
+    return SJ_OK;
+}
+
+extern "C" int sj_kv_set(sj_kv* kv, int32_t seq, const void* k_host, const void* v_host, int32_t len, int32_t pending_token) {
+    int rc = check_seq_layer(kv, seq, 0);
+    if (rc) return rc;
+    if (len < 0 || len > kv->cap[seq]) return fail(SJ_ECAPACITY, "len %d exceeds capacity %d", len, kv->cap[seq]);
+    if (pending_token < 0 || pending_token >= kv->m->cfg.vocab) return fail(SJ_EINVAL, "pending token out of range");
+    if (len > 0 && (!k_host || !v_host)) return fail(SJ_EINVAL, "k_host / v_host is null");
+    const sj_config& c = kv->m->cfg;
+    const size_t per_layer = (size_t)c.n_kv_heads * len * c.head_dim * kv->m->esz;
+    for (int l = 0; l < c.n_layers && len > 0; ++l)
+        if ((rc = sj_kv_set_layer(kv, seq, l, (const char*)k_host + l * per_layer, (const char*)v_host + l * per_layer, len)))
+            return rc;
+    return sj_kv_set_state(kv, seq, len, pending_token);
+}
+
+extern "C" int sj_kv_read(const sj_kv* kv, int32_t seq, int32_t layer, int32_t pos0, int32_t n, void* k_host, void* v_host) {
+    int rc = check_seq_layer(kv, seq, layer);
+    if (rc) return rc;
+    if (!k_host || !v_host) return fail(SJ_EINVAL, "k_host / v_host is null");
+    if (pos0 < 0 || n < 1 || pos0 + n > kv->cap[seq]) return fail(SJ_EINVAL, "rows %d..%d outside capacity %d", pos0, pos0 + n, kv->cap[seq]);
+    const sj_config& c = kv->m->cfg;
+    const size_t esz = kv->m->esz, bytes = (size_t)c.n_kv_heads * n * c.head_dim * esz;
+    void *ks = nullptr, *vs = nullptr;
+    HIPCHK(hipDeviceSynchronize());
+    HIPCHK(hipMalloc(&ks, bytes));
+    if (hipMalloc(&vs, bytes) != hipSuccess) { (void)hipFree(ks); return fail(SJ_ENOMEM, "hipMalloc failed"); }
+    const size_t off = (size_t)layer * kv->layer_stride + kv->seq_off[seq];
+    if (c.dtype == SJ_DTYPE_FP32)
+        kv_gather_kernel<float><<<256, 256>>>((float*)ks, (float*)vs, (const float*)kv->K + off, (const float*)kv->V + off,
+                                               c.n_kv_heads, pos0, n, kv->cap[seq], c.head_dim);
+    else
+        kv_gather_kernel<bf16_t><<<256, 256>>>((bf16_t*)ks, (bf16_t*)vs, (const bf16_t*)kv->K + off, (const bf16_t*)kv->V + off,
+                                                c.n_kv_heads, pos0, n, kv->cap[seq], c.head_dim);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpy(k_host, ks, bytes, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(v_host, vs, bytes, hipMemcpyDeviceToHost);
+    (void)hipFree(ks);
+    (void)hipFree(vs);
+    if (e != hipSuccess) return fail(SJ_EHIP, "cache read failed: %s", hipGetErrorString(e));
+    return SJ_OK;
+}
+
+static int refresh_lengths(sj_kv* kv) {
+    HIPCHK(hipDeviceSynchronize());
+    HIPCHK(hipMemcpy(kv->len_upper.data(), kv->len_dev, sizeof(int32_t) * kv->batch, hipMemcpyDeviceToHost));
+    return SJ_OK;
+}
+
+extern "C" int sj_kv_state(const sj_kv* kv, int32_t* len_host, int32_t* pending_host) {
+    if (!kv) return fail(SJ_EINVAL, "kv is null");
+    HIPCHK(hipDeviceSynchronize());
+    if (len_host) HIPCHK(hipMemcpy(len_host, kv->len_dev, sizeof(int32_t) * kv->batch, hipMemcpyDeviceToHost));
+    if (pending_host) HIPCHK(hipMemcpy(pending_host, kv->pending_dev, sizeof(int32_t) * kv->batch, hipMemcpyDeviceToHost));
+    return SJ_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// kernel sequence
+
+template <typename T, int NT, int EPI>
+static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) {
+    switch (mt) {
+        case 1: gemm_skinny_kernel<T, NT, 1, EPI><<<grid, 256, 0, st>>>(a); break;
+        case 2: gemm_skinny_kernel<T, NT, 2, EPI><<<grid, 256, 0, st>>>(a); break;
+        case 3: gemm_skinny_kernel<T, NT, 3, EPI><<<grid, 256, 0, st>>>(a); break;
+        default: return fail(SJ_EINVAL, "internal: unsupported m-tile count %d", mt);
+    }
+    LAUNCHCHK("gemm_skinny");
+    return SJ_OK;
+}
+
+// Y = X W^T for all `rows` rows; rows are processed in groups of at most 48 (3 MFMA tiles).
+template <typename T, int NT, int EPI>
+static int gemm(hipStream_t st, const void* Wt, const void* X, int ldx, int K, int N, int rows, int split, float* out,
+                void* act, float4* stats, float inv_temp) {
+    const int ngroups = N / 16 / NT;
+    for (int row0 = 0; row0 < rows; row0 += 48) {
+        const int nr = std::min(48, rows - row0);
+        GemmArgs a{};
+        a.Wt = Wt;
+        a.X = (const char*)X + (size_t)row0 * ldx * sizeof(T);
+        a.ldx = ldx; a.K = K; a.N = N;
+        a.R = nr;
+        a.inv_temp = inv_temp;
+        if (EPI == EPI_PARTIAL) {
+            // partial layout is [split][rows][N]: a row group writes its rows of every split slice
+            a.out = out + (size_t)row0 * N;
+            a.R = nr;
+        } else if (EPI == EPI_LOGITS) {
+            a.out = out + (size_t)row0 * N;
+            a.stats = stats + (size_t)row0 * ngroups;
+        } else {
+            a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
+        }
+        int rc;
+        if (EPI == EPI_PARTIAL && rows > 48) {
+            // the kernel indexes partials as [s][a.R][N]; with several row groups the slice stride must be
+            // the full row count, so launch one K-slice at a time
+            return fail(SJ_EINVAL, "internal: split-K with more than 48 rows goes through gemm_rows()");
+        }
+        rc = launch_gemm_mt<T, NT, EPI>((nr + 15) / 16, dim3(ngroups, split), st, a);
+        if (rc) return rc;
+    }
+    return SJ_OK;
+}
+
+template <typename T>
+struct Runner {
+    const sj_model* m;
+    sj_kv* kv;
+    hipStream_t st;
+    int nseq, rps, R;
+
+    KvView<T> view() const {
+        KvView<T> v;
+        v.K = (T*)kv->K; v.V = (T*)kv->V; v.seq_off = kv->seq_off_dev; v.cap = kv->cap_dev;
+        v.len = kv->len_dev; v.pending = kv->pending_dev; v.layer_stride = kv->layer_stride;
+        return v;
+    }
+
+    int partial_gemm(const void* W, const void* X, int ldx, int K, int N, int split) {
+        // more than 48 rows: no K split across workgroups (slice stride = row count of the group)
+        if (R > 48) {
+            for (int row0 = 0; row0 < R; row0 += 48) {
+                const int nr = std::min(48, R - row0);
+                GemmArgs a{};
+                a.Wt = W; a.X = (const char*)X + (size_t)row0 * ldx * sizeof(T);
+                a.ldx = ldx; a.K = K; a.N = N; a.R = nr;
+                a.out = kv->part + (size_t)row0 * N;
+                int rc = launch_gemm_mt<T, 1, EPI_PARTIAL>((nr + 15) / 16, dim3(N / 16, 1), st, a);
+                if (rc) return rc;
+            }
+            return SJ_OK;
+        }
+        return gemm<T, 1, EPI_PARTIAL>(st, W, X, ldx, K, N, R, split, kv->part, nullptr, nullptr, 0.f);
+    }
+    int nparts(int split) const { return R > 48 ? 1 : split; }
+
+    int attention(int layer) {
+        const ModelDims& md = m->md;
+        const int M = md.G * rps;
+        const int mtiles = (M + 15) / 16;
+        const int mq = std::min(mtiles, 4);
+        const int qgroups = (mtiles + mq - 1) / mq;
+        dim3 grid(kv->nchunk_max, md.Hkv * qgroups, nseq);
+#define ATTN(HD, MQ)                                                                                          \
+    attn_partial_kernel<T, HD, MQ><<<grid, 64, 0, st>>>(kv->sp_dev, md, (const T*)kv->qbuf, kv->mpad, view(), layer, \
+                                                        kv->chunk_keys, kv->nchunk_max, kv->opart, kv->mlpart)
+        if (md.hd == 128) {
+            switch (mq) { case 1: ATTN(128, 1); break; case 2: ATTN(128, 2); break; case 3: ATTN(128, 3); break; default: ATTN(128, 4); }
+        } else {
+            switch (mq) { case 1: ATTN(64, 1); break; case 2: ATTN(64, 2); break; case 3: ATTN(64, 3); break; default: ATTN(64, 4); }
+        }
+#undef ATTN
+        LAUNCHCHK("attn_partial");
+        dim3 mg(M, md.Hkv, nseq);
+        if (md.hd == 128)
+            attn_merge_kernel<T, 128><<<mg, 128, 0, st>>>(kv->sp_dev, md, kv->mpad, kv->len_dev, kv->cap_dev, kv->chunk_keys,
+                                                           kv->nchunk_max, kv->opart, kv->mlpart, (T*)kv->attn_out);
+        else
+            attn_merge_kernel<T, 64><<<mg, 64, 0, st>>>(kv->sp_dev, md, kv->mpad, kv->len_dev, kv->cap_dev, kv->chunk_keys,
+                                                         kv->nchunk_max, kv->opart, kv->mlpart, (T*)kv->attn_out);
+        LAUNCHCHK("attn_merge");
+        return SJ_OK;
+    }
+
+    // decoder layers (Eq. 2 / Eq. 4): leaves the last down-projection partials pending in kv->part
+    int layers() {
+        const ModelDims& md = m->md;
+        const sj_config& c = m->cfg;
+        const int d = md.d, Nq = md.Hq * md.hd, Nk = md.Hkv * md.hd, Nqkv = Nq + 2 * Nk;
+        step_begin_kernel<T><<<R, 256, 0, st>>>(kv->sp_dev, md, (const T*)m->embed, kv->len_dev, kv->pending_dev, kv->x,
+                                                 kv->cs, kv->row_tok, std::log((double)c.rope_base));
+        LAUNCHCHK("step_begin");
+        int pending_parts = 0;
+        int rc;
+        for (int l = 0; l < c.n_layers; ++l) {
+            const LayerW& L = m->layers[l];
+            add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)L.attn_norm,
+                                                      (T*)kv->xn, nullptr);
+            LAUNCHCHK("add_rmsnorm");
+            if ((rc = partial_gemm(L.wqkv, kv->xn, d, d, Nqkv, kv->split_qkv))) return rc;
+            rope_append_kernel<T><<<R, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->split_qkv), R, kv->cs,
+                                                      (T*)kv->qbuf, kv->mpad, view(), l);
+            LAUNCHCHK("rope_append");
+            if ((rc = attention(l))) return rc;
+            if ((rc = partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->split_o))) return rc;
+            add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, nparts(kv->split_o), (const T*)L.ffn_norm,
+                                                      (T*)kv->xn, nullptr);
+            LAUNCHCHK("add_rmsnorm");
+            if ((rc = gemm<T, 2, EPI_SWIGLU>(st, L.wgu, kv->xn, d, d, 2 * md.F, R, 1, nullptr, kv->act, nullptr, 0.f))) return rc;
+            if ((rc = partial_gemm(L.wd, kv->act, md.F, md.F, d, kv->split_d))) return rc;
+            pending_parts = nparts(kv->split_d);
+        }
+        add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)m->final_norm,
+                                                  (T*)kv->xn, kv->hn32);
+        LAUNCHCHK("add_rmsnorm");
+        return SJ_OK;
+    }
+
+    // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max))
+    int lm_head() {
+        const ModelDims& md = m->md;
+        int rc = gemm<T, 2, EPI_LOGITS>(st, m->lm_head, kv->xn, md.d, md.d, md.V, R, 1, kv->logits, nullptr, kv->stats, md.inv_temp);
+        if (rc) return rc;
+        const int nblk = md.V / 32;
+        softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, md.inv_temp, kv->rowstat);
+        LAUNCHCHK("softmax_merge");
+        return SJ_OK;
+    }
+
+    // Eq. 3, Eq. 5, scan, extra token, state commit
+    int tail(int gamma) {
+        const ModelDims& md = m->md;
+        judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores);
+        LAUNCHCHK("judge");
+        accept_scan_kernel<<<nseq, 64, 0, st>>>(kv->sp_dev, md.V, md.inv_temp, kv->logits, kv->rowstat, kv->scores, kv->p_at_d,
+                                                 kv->bits, kv->nacc);
+        LAUNCHCHK("accept_scan");
+        ResampleArgs ra{};
+        ra.V = md.V; ra.nslab = kv->nslab; ra.slab_len = kv->slab_len; ra.inv_temp = md.inv_temp;
+        ra.logits = kv->logits; ra.rowstat = kv->rowstat; ra.nacc = kv->nacc; ra.epart = kv->epart; ra.wpart = kv->wpart;
+        if (md.inv_temp > 0.f) {
+            dim3 g(kv->nslab / 256, nseq);
+            resample_e_kernel<<<g, 256, 0, st>>>(kv->sp_dev, ra);
+            LAUNCHCHK("resample_e");
+            resample_w_kernel<<<g, 256, 0, st>>>(kv->sp_dev, ra);
+            LAUNCHCHK("resample_w");
+        }
+        resample_pick_kernel<<<nseq, 256, 0, st>>>(kv->sp_dev, ra, kv->len_dev, kv->pending_dev);
+        LAUNCHCHK("resample_pick");
+        return SJ_OK;
+    }
+};
+
+static int set_params(sj_kv* kv, hipStream_t st, const StepParams& p) {
+    set_params_kernel<<<1, 1, 0, st>>>(p, kv->sp_dev);
+    LAUNCHCHK("set_params");
+    return SJ_OK;
+}
+
+template <typename T>
+static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,
+                            const void* hidden) {
+    int rc = set_params(kv, st, p);
+    if (rc) return rc;
+    Runner<T> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
+    if (head_only) {
+        const size_t n = (size_t)run.R * m->md.d;
+        HIPCHK(hipMemcpyAsync(kv->xn, hidden, n * sizeof(T), hipMemcpyDeviceToDevice, st));
+        to_f32_kernel<T><<<1024, 256, 0, st>>>((const T*)hidden, kv->hn32, n);
+        LAUNCHCHK("to_f32");
+    } else {
+        if ((rc = run.layers())) return rc;
+    }
+    if ((rc = run.lm_head())) return rc;
+    return run.tail(gamma);
+}
+
+static int check_step_args(sj_model* m, sj_kv* kv, int gamma, const void* a, const void* b, const void* c, const void* d,
+                           const void* e) {
+    if (!m || !kv) return fail(SJ_EINVAL, "model / kv is null");
+    if (kv->m != m) return fail(SJ_EINVAL, "kv was created for a different model");
+    if (gamma < 1 || gamma > m->cfg.max_gamma) return fail(SJ_EINVAL, "gamma %d outside 1..%d", gamma, m->cfg.max_gamma);
+    if (!a || !b || !c || !d || !e) return fail(SJ_EINVAL, "null device pointer argument");
+    return SJ_OK;
+}
+
+extern "C" int sj_verify_step(sj_model* m, sj_kv* kv, int32_t gamma, const int32_t* draft_tokens, const float* draft_probs,
+                              const float* uniforms, float judge_threshold, int32_t* accepted_len, int32_t* next_token,
+                              void* stream) {
+    int rc = check_step_args(m, kv, gamma, draft_tokens, draft_probs, uniforms, accepted_len, next_token);
+    if (rc) return rc;
+    if (m->cfg.n_layers == 0) return fail(SJ_EINVAL, "head-only model: use sj_verify_head");
+    if (!(judge_threshold == judge_threshold)) return fail(SJ_EINVAL, "judge_threshold is NaN");
+    // capacity: the host keeps an upper bound of every length; refresh it only when the bound trips
+    bool tight = true;
+    for (int b = 0; b < kv->batch; ++b) tight = tight && (kv->len_upper[b] + gamma + 1 <= kv->cap[b]);
+    if (!tight) {
+        if ((rc = refresh_lengths(kv))) return rc;
+        for (int b = 0; b < kv->batch; ++b)
+            if (kv->len_upper[b] + gamma + 1 > kv->cap[b])
+                return fail(SJ_ECAPACITY, "sequence %d: len %d + gamma + 1 exceeds capacity %d", b, kv->len_upper[b], kv->cap[b]);
+    }
+    StepParams p{};
+    p.nseq = kv->batch; p.seq_base = 0; p.rps = gamma + 1; p.gamma = gamma; p.tok_mode = 0; p.mode = kv->mode;
+    p.theta = judge_threshold;
+    p.draft_tokens = draft_tokens; p.draft_probs = draft_probs; p.uniforms = uniforms;
+    p.accepted_len = accepted_len; p.next_token = next_token;
+    hipStream_t st = (hipStream_t)stream;
+    rc = (m->cfg.dtype == SJ_DTYPE_FP32) ? verify_step_impl<float>(m, kv, gamma, p, st, false, nullptr)
+                                         : verify_step_impl<bf16_t>(m, kv, gamma, p, st, false, nullptr);
+    if (rc) return rc;
+    for (int b = 0; b < kv->batch; ++b) kv->len_upper[b] += gamma + 1;
+    kv->last_gamma = gamma;
+    kv->last_rows = kv->batch * (gamma + 1);
+    return SJ_OK;
+}
+
+extern "C" int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void* hidden, const int32_t* draft_tokens,
+                              const float* draft_probs, const float* uniforms, float judge_threshold, int32_t* accepted_len,
+                              int32_t* next_token, void* stream) {
+    int rc = check_step_args(m, kv, gamma, draft_tokens, draft_probs, uniforms, accepted_len, next_token);
+    if (rc) return rc;
+    if (!hidden) return fail(SJ_EINVAL, "hidden is null");
+    if (!(judge_threshold == judge_threshold)) return fail(SJ_EINVAL, "judge_threshold is NaN");
+    StepParams p{};
+    p.nseq = kv->batch; p.seq_base = 0; p.rps = gamma + 1; p.gamma = gamma; p.tok_mode = 0; p.mode = kv->mode;
+    p.theta = judge_threshold;
+    p.draft_tokens = draft_tokens; p.draft_probs = draft_probs; p.uniforms = uniforms;
+    p.accepted_len = accepted_len; p.next_token = next_token;
+    hipStream_t st = (hipStream_t)stream;
+    rc = (m->cfg.dtype == SJ_DTYPE_FP32) ? verify_step_impl<float>(m, kv, gamma, p, st, true, hidden)
+                                         : verify_step_impl<bf16_t>(m, kv, gamma, p, st, true, hidden);
+    if (rc) return rc;
+    kv->last_gamma = gamma;
+    kv->last_rows = kv->batch * (gamma + 1);
+    return SJ_OK;
+}
+
+template <typename T>
+static int prefill_impl(sj_model* m, sj_kv* kv, int seq, const int32_t* tokens, int n, hipStream_t st) {
+    const int chunk_max = std::min(kv->max_rows, m->cfg.max_gamma + 1);
+    for (int t0 = 0; t0 < n; t0 += chunk_max) {
+        const int cn = std::min(chunk_max, n - t0);
+        const bool last = (t0 + cn == n);
+        HIPCHK(hipMemcpyAsync(kv->prefill_tok, tokens + t0, sizeof(int32_t) * cn, hipMemcpyHostToDevice, st));
+        StepParams p{};
+        p.nseq = 1; p.seq_base = seq; p.rps = cn; p.gamma = cn - 1; p.tok_mode = 1; p.prefill_tokens = kv->prefill_tok;
+        int rc = set_params(kv, st, p);
+        if (rc) return rc;
+        Runner<T> run{m, kv, st, 1, cn, cn};
+        if ((rc = run.layers())) return rc;
+        if (last && (rc = run.lm_head())) return rc;
+        prefill_commit_kernel<<<1, 1, 0, st>>>(kv->sp_dev, kv->rowstat, kv->len_dev, kv->pending_dev, last ? 1 : 0);
+        LAUNCHCHK("prefill_commit");
+        HIPCHK(hipStreamSynchronize(st));     // the pageable token copy of the next chunk must not race
+    }
+    return SJ_OK;
+}
+
+extern "C" int sj_prefill(sj_model* m, sj_kv* kv, int32_t seq, const int32_t* tokens_host, int32_t n, void* stream) {
+    if (!m || !kv || !tokens_host) return fail(SJ_EINVAL, "null argument");
+    if (kv->m != m) return fail(SJ_EINVAL, "kv was created for a different model");
+    if (m->cfg.n_layers == 0) return fail(SJ_EINVAL, "head-only model has no cache");
+    if (seq < 0 || seq >= kv->batch) return fail(SJ_EINVAL, "seq %d out of range", seq);
+    if (n < 1) return fail(SJ_EINVAL, "n must be positive");
+    for (int i = 0; i < n; ++i)
+        if (tokens_host[i] < 0 || tokens_host[i] >= m->cfg.vocab) return fail(SJ_EINVAL, "token %d out of range", i);
+    int rc = refresh_lengths(kv);
+    if (rc) return rc;
+    if (kv->len_upper[seq] + n > kv->cap[seq]) return fail(SJ_ECAPACITY, "prefill of %d tokens exceeds capacity", n);
+    hipStream_t st = (hipStream_t)stream;
+    rc = (m->cfg.dtype == SJ_DTYPE_FP32) ? prefill_impl<float>(m, kv, seq, tokens_host, n, st)
+                                         : prefill_impl<bf16_t>(m, kv, seq, tokens_host, n, st);
+    if (rc) return rc;
+    kv->len_upper[seq] += n;
+    kv->last_gamma = 0;
+    kv->last_rows = std::min(n, std::min(kv->max_rows, m->cfg.max_gamma + 1));
+    return SJ_OK;
+}
+
+extern "C" int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, size_t nbytes) {
+    if (!kv || !dst_host) return fail(SJ_EINVAL, "null argument");
+    const int R = kv->last_rows, gamma = kv->last_gamma;
+    if (R <= 0) return fail(SJ_EINVAL, "no step has run yet");
+    const void* src = nullptr;
+    size_t want = 0;
+    switch (what) {
+        case SJ_DBG_LOGITS: src = kv->logits; want = (size_t)R * kv->m->cfg.vocab * 4; break;
+        case SJ_DBG_HIDDEN: src = kv->hn32; want = (size_t)R * kv->m->cfg.d_model * 4; break;
+        case SJ_DBG_JUDGE_SCORES: src = kv->scores; want = (size_t)kv->batch * gamma * 4; break;
+        case SJ_DBG_P_AT_DRAFT: src = kv->p_at_d; want = (size_t)kv->batch * gamma * 4; break;
+        case SJ_DBG_ACCEPT_BITS: src = kv->bits; want = (size_t)kv->batch * gamma * 4; break;
+        default: return fail(SJ_EINVAL, "unknown debug item %d", what);
+    }
+    if (want == 0) return fail(SJ_EINVAL, "item not produced by the last call");
+    if (nbytes != want) return fail(SJ_EINVAL, "nbytes %zu != expected %zu", nbytes, want);
+    HIPCHK(hipDeviceSynchronize());
+    HIPCHK(hipMemcpy(dst_host, src, want, hipMemcpyDeviceToHost));
+    return SJ_OK;
+}
+
+extern "C" const char* sj_last_error(void) { return g_err.c_str(); }
+extern "C" const char* sj_version(void) { return "sj-verify 0.1 (gfx950)"; }

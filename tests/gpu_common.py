@@ -1,0 +1,111 @@
+"""Helpers for the GPU parity tests: build both sides from the same seeded inputs and compare.
+(Test glue only; no method arithmetic.)"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2510_02329_amd as sj
+import synth
+from oracle import selfjudge_oracle as orc
+from tests import helpers
+
+TOL = {"fp32": (1e-4, 1e-4), "bf16": (1e-2, 2e-2)}      # (abs, rel) of the spec parity bar
+
+
+def sj_config(shape: synth.ModelShape, max_gamma: int | None = None) -> sj.SJConfig:
+    return sj.SJConfig(n_layers=shape.n_layers, d_model=shape.d_model, n_q_heads=shape.n_q_heads,
+                       n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, d_ffn=shape.d_ffn, vocab=shape.vocab,
+                       dtype=0 if shape.dtype == "fp32" else 1, rope_base=shape.rope_base, rms_eps=shape.rms_eps,
+                       temperature=shape.temperature, max_gamma=max_gamma or shape.gamma)
+
+
+def load_model(shape: synth.ModelShape, src: synth.WeightSource, max_gamma: int | None = None) -> int:
+    return sj.sj_model_load(sj_config(shape, max_gamma), lambda name, layer: src.tensor(name, layer))
+
+
+class Gpu:
+    """One model + one batch state on the device, with the draft inputs of a step as torch tensors."""
+
+    def __init__(self, shape, src, capacity, max_gamma=None):
+        self.shape = shape
+        self.model = load_model(shape, src, max_gamma)
+        self.kv = sj.sj_kv_create(self.model, shape.batch, capacity)
+        self.dev = torch.device("cuda:0")
+
+    def close(self):
+        sj.sj_kv_free(self.kv)
+        sj.sj_model_free(self.model)
+
+    def step(self, draft, theta, gamma=None, head_hidden=None):
+        gamma = gamma or self.shape.gamma
+        B = self.shape.batch
+        dt = torch.from_numpy(np.ascontiguousarray(draft["tokens"])).to(self.dev)
+        dp = torch.from_numpy(np.ascontiguousarray(draft["probs"])).to(self.dev)
+        un = torch.from_numpy(np.ascontiguousarray(draft["uniforms"])).to(self.dev)
+        acc = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        nxt = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        stream = torch.cuda.current_stream()
+        if head_hidden is None:
+            sj.sj_verify_step(self.model, self.kv, gamma, dt, dp, un, theta, acc, nxt, stream)
+        else:
+            sj.sj_verify_head(self.model, self.kv, gamma, head_hidden, dt, dp, un, theta, acc, nxt, stream)
+        torch.cuda.synchronize()
+        R, V, d = B * (gamma + 1), self.shape.vocab, self.shape.d_model
+        out = {
+            "accepted_len": acc.cpu().numpy(), "next_token": nxt.cpu().numpy(),
+            "logits": sj.sj_debug_fetch(self.kv, sj.SJ_DBG_LOGITS, np.empty((R, V), np.float32)).reshape(B, gamma + 1, V),
+            "hn": sj.sj_debug_fetch(self.kv, sj.SJ_DBG_HIDDEN, np.empty((R, d), np.float32)).reshape(B, gamma + 1, d),
+            "judge_scores": sj.sj_debug_fetch(self.kv, sj.SJ_DBG_JUDGE_SCORES, np.empty((B, gamma), np.float32)),
+            "p_at_draft": sj.sj_debug_fetch(self.kv, sj.SJ_DBG_P_AT_DRAFT, np.empty((B, gamma), np.float32)),
+            "bits": sj.sj_debug_fetch(self.kv, sj.SJ_DBG_ACCEPT_BITS, np.empty((B, gamma), np.int32)),
+        }
+        return out
+
+    def kv_rows(self, seq, layer, pos0, n):
+        s = self.shape
+        dt = np.float32 if s.dtype == "fp32" else np.uint16
+        k = np.empty((s.n_kv_heads, n, s.head_dim), dt)
+        v = np.empty((s.n_kv_heads, n, s.head_dim), dt)
+        sj.sj_kv_read(self.kv, seq, layer, pos0, n, k, v)
+        return synth.to_f64(k), synth.to_f64(v)
+
+
+def close_enough(got, ref, dtype, what="", scale=1.0):
+    a, r = TOL[dtype]
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    err = np.abs(got - ref)
+    bound = scale * (a + r * np.abs(ref))
+    worst = float((err / bound).max()) if err.size else 0.0
+    assert (err <= bound).all(), f"{what}: max err {err.max():.3e}, worst err/bound {worst:.2f}"
+    return float(err.max()) if err.size else 0.0, worst
+
+
+def replay_matches(shape, gpu_out, draft, theta, mode="two_stage"):
+    """Decision replay: the oracle's tail run on the device's own fp32 logits and judge scores must
+    give the same bits, accepted length and token, except where a decision margin is at fp32 rounding
+    level.  Returns (mismatches, excused)."""
+    B, gamma = draft["tokens"].shape
+    bad, excused = [], 0
+    for b in range(B):
+        res = orc.verify_tail(gpu_out["logits"][b].astype(np.float64), gpu_out["judge_scores"][b].astype(np.float64),
+                              draft["tokens"][b], draft["probs"][b], draft["uniforms"][b], theta, shape.temperature, mode)
+        bits = [(1 if a else 0) | (2 if g else 0) for a, g in zip(res["align_bits"], res["judge_bits"])]
+        ok = True
+        for j in range(gamma):
+            if bits[j] != int(gpu_out["bits"][b, j]):
+                # excused only if the ratio test sits at fp32 rounding level
+                p, q, u = res["p_at_draft"][j], float(draft["probs"][b, j, draft["tokens"][b, j]]), float(draft["uniforms"][b, j])
+                margin = abs(np.log(max(p, 1e-300)) - np.log(max(u * q, 1e-300)))
+                jm = abs(float(gpu_out["judge_scores"][b, j]) - theta)
+                if margin < 1e-4 or jm < 1e-6:
+                    excused += 1
+                else:
+                    ok = False
+        if res["accepted_len"] != int(gpu_out["accepted_len"][b]) or res["next_token"] != int(gpu_out["next_token"][b]):
+            ok = ok and False if excused == 0 else ok
+            if excused == 0:
+                ok = False
+        if not ok:
+            bad.append((b, res["accepted_len"], int(gpu_out["accepted_len"][b]), res["next_token"], int(gpu_out["next_token"][b])))
+    return bad, excused
