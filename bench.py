@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the draft-block verification step on one MI355X.
+
+A "step" is one sj_verify_step over the whole batch: target forward over gamma+1 rows per sequence
+against the KV cache, LM head, softmax, ratio test, judge, scan, extra token, state commit.  Default
+workload: the 8B-shaped bf16 decoder at batch 1, gamma 5, cache length 1024 (the configuration the
+headline metric is quoted on).  Inputs are synthetic (seeded) and resident in HBM before timing; the
+sequence state is rewound before every step so that all timed steps are identical.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(shape, lens, gamma) -> dict:
+    """Bytes one step must move at least once: every projection weight + LM head, the live K/V of
+    every sequence, one draft-probability row and one logits row per sequence."""
+    es = shape.elem_bytes()
+    w = shape.params_streamed() * es
+    kv = int(sum(int(l) + gamma + 1 for l in lens)) * shape.n_layers * 2 * shape.n_kv_heads * shape.head_dim * es
+    other = shape.batch * shape.vocab * 4 * 2
+    return {"weights": w, "kv": kv, "other": other, "total": w + kv + other}
+
+
+def cpu_baseline(shape, seed, sample_layers=4, lm_rows=16384, repeats=5):
+    """The fp64 oracle timed on this host on a bounded sample of the same workload: `sample_layers`
+    decoder layers of the step plus `lm_rows` rows of the LM head, scaled to the whole step."""
+    import synth
+    from oracle import selfjudge_oracle as orc
+    from tests import helpers
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:  # noqa: BLE001
+        cores = os.cpu_count() or 1
+    sub = shape.scaled(n_layers=sample_layers)
+    cfg = helpers.oracle_config(sub)
+    src = synth.WeightSource(sub, seed)
+    # weights are prepared before the clock starts: the baseline times the method, not the generator
+    store = {}
+    for l in range(sample_layers):
+        for n in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"):
+            store[(n, l)] = synth.to_f64(src.tensor(n, l))
+    store[("final_norm", -1)] = synth.to_f64(src.tensor("final_norm"))
+    lm = synth.to_f64(src.tensor("lm_head", -1, (0, lm_rows)))
+    lens = shape.kv_lengths(seed)
+    pend = synth.make_pending(shape, seed)
+    caches = []
+    for b in range(shape.batch):
+        c = orc.SeqCache(cfg, int(lens[b]) + 64, storage=shape.dtype)
+        for l in range(sample_layers):
+            k, v = synth.make_kv_cache(shape, seed, b, l, int(lens[b]))
+            c.k[l][:, :lens[b]] = synth.to_f64(k)
+            c.v[l][:, :lens[b]] = synth.to_f64(v)
+        c.length, c.pending = int(lens[b]), int(pend[b])
+        caches.append(c)
+    emb = {}
+
+    def W(name, layer=-1, rows=None):
+        if name == "embed":
+            key = rows[0]
+            if key not in emb:
+                emb[key] = synth.to_f64(src.tensor("embed", -1, rows))
+            return emb[key]
+        if name == "lm_head":
+            return lm
+        return store[(name, layer)]
+
+    draft = synth.make_draft(shape, seed)
+    toks = [[caches[b].pending] + [int(t) for t in draft["tokens"][b]] for b in range(shape.batch)]
+    for seq in toks:                      # embedding rows fetched before timing as well
+        for t in seq:
+            W("embed", -1, (t, t + 1))
+    t_layers, t_lm, spent = [], [], 0.0
+    for _ in range(repeats):
+        t0 = time.perf_counter()
+        fw = orc.block_forward(cfg, W, caches, toks, want_logits=False)      # does not commit the caches
+        t1 = time.perf_counter()
+        hn = np.concatenate([f["hn"] for f in fw])
+        part = hn @ lm.T
+        for r in range(part.shape[0]):
+            orc.target_distribution(part[r], max(shape.temperature, 1.0))
+        t2 = time.perf_counter()
+        t_layers.append(t1 - t0)
+        t_lm.append(t2 - t1)
+        spent += t2 - t0
+        if spent > 30.0:
+            break
+    t_layers, t_lm = float(np.median(t_layers)), float(np.median(t_lm))
+    step_s = t_layers * shape.n_layers / sample_layers + t_lm * shape.vocab / lm_rows
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{sample_layers} of {shape.n_layers} decoder layers + {lm_rows} of {shape.vocab} "
+                      f"LM-head rows and their softmax; median of {repeats} passes = {1e3 * (t_layers + t_lm):.0f} ms, "
+                      f"scaled linearly to one step (= {step_s:.2f} s)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="index into synth.CONFIGS (2 = 8B-shaped batch 1)")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalid as a result)")
+    ap.add_argument("--planes", type=int, default=0, help="bf16 operand planes (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--theta", type=float, default=0.5)
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; the verification step is data-parallel over sequences "
+              "and has no multi-GPU path to time. Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2510_02329_amd as sj
+    import synth
+    from tests import gpu_common as G
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    shape = synth.CONFIGS[args.workload]
+    if args.layers:
+        shape = shape.scaled(n_layers=args.layers)
+    if shape.n_layers == 0:
+        print("bench.py: the head-only workload is timed by tests, not by this benchmark", file=sys.stderr)
+        return 2
+    gamma, B = shape.gamma, shape.batch
+    dev = torch.device("cuda:0")
+    t0 = time.time()
+    log(f"[bench] workload {args.workload}: {shape.name}; generating + loading weights ...")
+    src = synth.WeightSource(shape, args.seed)
+    model = G.load_model(shape, src)
+    lens = shape.kv_lengths(args.seed)
+    cap = [int(l) + 64 for l in lens]
+    kv = sj.sj_kv_create(model, B, cap)
+    if args.planes:
+        sj.sj_set_operand_planes(kv, args.planes)
+    pend = synth.make_pending(shape, args.seed)
+    for b in range(B):
+        for l in range(shape.n_layers):
+            k, v = synth.make_kv_cache(shape, args.seed, b, l, int(lens[b]))
+            sj.sj_kv_set_layer(kv, b, l, k, v, int(lens[b]))
+        sj.sj_kv_set_state(kv, b, int(lens[b]), int(pend[b]))
+    draft = synth.make_draft(shape, args.seed)
+    dt = torch.from_numpy(draft["tokens"]).to(dev)
+    dp = torch.from_numpy(draft["probs"]).to(dev)
+    un = torch.from_numpy(draft["uniforms"]).to(dev)
+    acc = torch.zeros(B, dtype=torch.int32, device=dev)
+    nxt = torch.zeros(B, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+    log(f"[bench] inputs resident after {time.time() - t0:.1f} s")
+
+    def one_step():
+        sj.sj_kv_rewind(kv, lens.tolist(), pend.tolist(), stream)
+        sj.sj_verify_step(model, kv, gamma, dt, dp, un, args.theta, acc, nxt, stream)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        one_step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t_wall
+    gpu_s = e0.elapsed_time(e1) / 1e3
+    total_s = max(wall_s, gpu_s)
+    ms_per_step = total_s / args.steps * 1e3
+    steps_per_s = args.steps / total_s
+    mean_tokens = float((acc.cpu().numpy() + 1).mean())
+
+    ab = algorithmic_bytes(shape, lens, gamma)
+    step_gbps = ab["total"] / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel (gate/up projection + SwiGLU: the largest weight stream of a layer), timed with HIP
+    # events around each of its launches on the step's stream, in a separate pass of the same steps
+    sj.sj_set_kernel_timing(kv, 3)
+    n_timed = min(args.steps, 50)
+    for _ in range(n_timed):
+        one_step()
+    k_ms, k_launches = sj.sj_get_kernel_timing(kv)
+    sj.sj_set_kernel_timing(kv, 0)
+    k_bytes = 2 * shape.d_ffn * shape.d_model * shape.elem_bytes()      # gate + up weights of one layer
+    k_avg_s = k_ms / max(1, k_launches) * 1e-3
+    k_gbps = k_bytes / k_avg_s / 1e9 if k_launches else 0.0
+
+    out = {
+        "metric": "verify_steps_per_s", "value": round(steps_per_s, 3), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"cfg{args.workload} {shape.name}: {shape.n_layers} layers d={shape.d_model} "
+                               f"heads {shape.n_q_heads}/{shape.n_kv_heads}x{shape.head_dim} ffn={shape.d_ffn} "
+                               f"vocab={shape.vocab}", "batch": B, "gamma": gamma,
+                   "kv_len": [int(x) for x in lens] if B <= 4 else f"U[{shape.kv_len[0]},{shape.kv_len[1]}] per sequence",
+                   "judge_threshold": args.theta, "temperature": shape.temperature, "parallelism": "single GPU"},
+        "verified_tokens_per_s": round(steps_per_s * B * mean_tokens, 2),
+        "mean_tokens_per_seq_step": round(mean_tokens, 3),
+        "step_hbm": {"algorithmic_bytes": ab["total"], "achieved_gbps": round(step_gbps, 1),
+                     "frac_of_8TBps": round(step_gbps / HBM_PEAK_GBPS, 4)},
+        "roofline": {"kernel": "gemm_skinny (gate/up projection + SwiGLU epilogue)", "bound": "hbm",
+                     "achieved": round(k_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(k_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": k_bytes, "avg_launch_us": round(k_avg_s * 1e6, 2), "launches_timed": int(k_launches)},
+    }
+    sj.sj_kv_free(kv)
+    sj.sj_model_free(model)
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(shape, args.seed)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

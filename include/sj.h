@@ -154,6 +154,24 @@ int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void* hidden,
 #define SJ_MODE_JUDGE     2
 int sj_set_mode(sj_kv* kv, int32_t mode);
 
+/* Sets every sequence's length and pending token from host arrays of `batch` entries, asynchronously
+ * on `stream` (a benchmark or a caller rolling back uses it to replay a step from the same state).
+ * Cache contents are not touched: rows below the new length must already hold valid K/V. */
+int sj_kv_rewind(sj_kv* kv, const int32_t* len_host, const int32_t* pending_host, void* stream);
+
+/* Measurement aid.  kernel_class != 0 makes the following sj_verify_step calls bracket every launch
+ * of that class with HIP events on the step's stream: 1 = QKV projection, 2 = O projection,
+ * 3 = gate/up projection + SwiGLU, 4 = down projection.  sj_get_kernel_timing synchronises, returns
+ * the summed duration and launch count since the last call, and clears them.  0 switches it off. */
+int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class);
+int sj_get_kernel_timing(sj_kv* kv, double* total_ms, int64_t* launches);
+
+/* bf16 models only: how many bf16 planes carry the fp32 activations (the few-row operand of every
+ * matrix product) into the matrix cores.  1 = activations rounded to bf16 at each product
+ * (relative 2^-9), 2 = hi + lo planes (2^-18, the default), 3 = exact fp32.  Weights and cache are
+ * bf16 in every case and the bytes streamed from HBM do not change.  Ignored for fp32 models. */
+int sj_set_operand_planes(sj_kv* kv, int32_t planes);
+
 /* Intermediate results of the last step, copied to the host (synchronous; for parity tests).
  *   SJ_DBG_LOGITS       float [rows, vocab]     rows = batch*(gamma+1)
  *   SJ_DBG_HIDDEN       float [rows, d_model]   final hidden states after the last RMSNorm

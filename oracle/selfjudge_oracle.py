@@ -37,6 +37,10 @@ Readings of points the paper leaves open (each is also listed in the design note
       no biases; untied embedding / LM head; eps inside the square root.              [parity unpinned]
   R8  the cache holds positions 0..L-1; the pending token (last emitted, not yet cached)
       is row 0 of the block; after the step L += 1 + n.
+  R9  the cache is held in the model's storage type (bf16 or fp32), like the weights: the K/V
+      of a new row are rounded to it (nearest even) when appended, and every read - also the
+      block's own rows in the same step - sees the stored value.  This keeps "one block
+      forward == gamma+1 single-token decodes" exact on what the cache holds.
 """
 from __future__ import annotations
 
@@ -66,11 +70,32 @@ class OracleConfig:
 WeightFn = Callable[..., np.ndarray]
 
 
-class SeqCache:
-    """KV cache of one sequence: k[l], v[l] are float64 [n_kv_heads, capacity, head_dim];
-    positions 0..length-1 are valid; `pending` is the last emitted, not yet cached token (R8)."""
+def round_to_storage(a: np.ndarray, storage: str) -> np.ndarray:
+    """Round float64 values to the cache's storage type and return them as float64 (R9).
+    "bf16": 8 significant bits, round to nearest, ties to even, done directly on the float64
+    bit pattern (values are far inside bf16's exponent range); "fp32": IEEE single; "fp64": as is."""
+    a = np.asarray(a, F64)
+    if storage == "fp64":
+        return a
+    if storage == "fp32":
+        return a.astype(np.float32).astype(F64)
+    if storage == "bf16":
+        u = np.ascontiguousarray(a).view(np.uint64)
+        drop = np.uint64(52 - 7)                                   # mantissa bits beyond bf16's 7
+        half = (np.uint64(1) << (drop - np.uint64(1))) - np.uint64(1)
+        odd = (u >> drop) & np.uint64(1)
+        r = (u + half + odd) & ~((np.uint64(1) << drop) - np.uint64(1))
+        return r.view(F64)
+    raise ValueError(storage)
 
-    def __init__(self, cfg: OracleConfig, capacity: int):
+
+class SeqCache:
+    """KV cache of one sequence: k[l], v[l] are float64 [n_kv_heads, capacity, head_dim] holding
+    values representable in `storage`; positions 0..length-1 are valid; `pending` is the last
+    emitted, not yet cached token (R8)."""
+
+    def __init__(self, cfg: OracleConfig, capacity: int, storage: str = "fp64"):
+        self.storage = storage
         self.k = [np.zeros((cfg.n_kv_heads, capacity, cfg.head_dim), F64) for _ in range(cfg.n_layers)]
         self.v = [np.zeros((cfg.n_kv_heads, capacity, cfg.head_dim), F64) for _ in range(cfg.n_layers)]
         self.length = 0
@@ -145,8 +170,8 @@ def block_forward(cfg: OracleConfig, W: WeightFn, caches: Sequence[SeqCache],
                     q[r, h] = rotary(q[r, h], L + j, cfg.rope_base)
                 for h in range(Hkv):
                     k[r, h] = rotary(k[r, h], L + j, cfg.rope_base)
-                cache.k[l][:, L + j, :] = k[r]
-                cache.v[l][:, L + j, :] = v[r]
+                cache.k[l][:, L + j, :] = round_to_storage(k[r], cache.storage)
+                cache.v[l][:, L + j, :] = round_to_storage(v[r], cache.storage)
             for j in range(counts[b]):
                 r = offs[b] + j
                 for h in range(Hq):

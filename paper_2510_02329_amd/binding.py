@@ -66,6 +66,10 @@ def load_library() -> C.CDLL:
         "sj_verify_step": (C.c_int, [vp, vp, i32, vp, vp, vp, f32, vp, vp, vp]),
         "sj_verify_head": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, f32, vp, vp, vp]),
         "sj_set_mode": (C.c_int, [vp, i32]),
+        "sj_set_operand_planes": (C.c_int, [vp, i32]),
+        "sj_kv_rewind": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
+        "sj_set_kernel_timing": (C.c_int, [vp, i32]),
+        "sj_get_kernel_timing": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "sj_debug_fetch": (C.c_int, [vp, i32, vp, sz]),
         "sj_last_error": (C.c_char_p, []),
         "sj_version": (C.c_char_p, []),
@@ -198,6 +202,26 @@ def sj_verify_head(model: int, kv: int, gamma: int, hidden, draft_tokens, draft_
 
 def sj_set_mode(kv: int, mode: int) -> None:
     _check(load_library().sj_set_mode(kv, mode))
+
+
+def sj_kv_rewind(kv: int, lengths: Sequence[int], pending: Sequence[int], stream=None) -> None:
+    n = len(lengths)
+    ln, pd = (C.c_int32 * n)(*[int(x) for x in lengths]), (C.c_int32 * n)(*[int(x) for x in pending])
+    _check(load_library().sj_kv_rewind(kv, ln, pd, _stream(stream)))
+
+
+def sj_set_kernel_timing(kv: int, kernel_class: int) -> None:
+    _check(load_library().sj_set_kernel_timing(kv, kernel_class))
+
+
+def sj_get_kernel_timing(kv: int):
+    ms, n = C.c_double(), C.c_int64()
+    _check(load_library().sj_get_kernel_timing(kv, C.byref(ms), C.byref(n)))
+    return ms.value, n.value
+
+
+def sj_set_operand_planes(kv: int, planes: int) -> None:
+    _check(load_library().sj_set_operand_planes(kv, planes))
 
 
 def sj_debug_fetch(kv: int, what: int, out: np.ndarray) -> np.ndarray:

@@ -7,6 +7,15 @@
 //   bf16: KF = 8, one v_mfma_f32_16x16x32_bf16 per fragment pair.
 //   fp32: KF = 4, four v_mfma_f32_16x16x4_f32 (element i of both fragments feeds product i), so
 //         the contraction covers the same 16 k-values in a different order.
+//
+// Activations (the few-row operand) are fp32 values.  In bf16 mode they are written as three bf16
+// planes (hi = bf16(x), mid = bf16(x - hi), lo = x - hi - mid, together all 24 significant bits)
+// and a kernel multiplies the first SPL of them by the same weight fragment, accumulating in fp32:
+// SPL = 1 is plain bf16 rounding (2^-9), SPL = 2 carries 16 bits (2^-18), SPL = 3 is exact.
+// Only the weights and the cache are bf16.  Rounding every GEMM input to bf16 leaves the logits
+// of a 32-layer decoder outside the parity bar against an fp64 reference; two planes are well
+// inside it.  The weight stream from HBM - the bound of this path - is unchanged; the matrix cores
+// have the headroom for the extra products.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -37,6 +46,7 @@ template <typename T> struct Traits;
 template <> struct Traits<float> {
     static constexpr int KF = 4;
     static constexpr int KSTEP = 16;
+    static constexpr int NS = 1;          // activation planes: fp32 operands are exact
     static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x4& c) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.f[i], b.f[i], c, 0, 0, 0);
@@ -45,17 +55,39 @@ template <> struct Traits<float> {
     static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
     // packs 4*KF/4.. probabilities of one lane into a B fragment: fp32 takes 4 values
     static __device__ __forceinline__ void pack(Frag& f, int j, float v) { f.f[j] = v; }
+    template <int SPL> static __device__ __forceinline__ void pack_split(Frag* f, int j, float v) { f[0].f[j] = v; }
+    static __device__ __forceinline__ void store_split(float* p, size_t, float v) { *p = v; }
 };
 
 template <> struct Traits<bf16_t> {
     static constexpr int KF = 8;
     static constexpr int KSTEP = 32;
+    static constexpr int NS = 3;          // fp32 activations are carried as three bf16 planes
     static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x4& c) {
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.h, b.h, c, 0, 0, 0);
     }
     static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
     static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
     static __device__ __forceinline__ void pack(Frag& f, int j, float v) { f.s[j] = f32_to_bf16(v); }
+    // v = hi + mid + lo exactly: each part takes the next 8 significant bits of the fp32 value
+    template <int SPL> static __device__ __forceinline__ void pack_split(Frag* f, int j, float v) {
+        const bf16_t h = f32_to_bf16(v);
+        f[0].s[j] = h;
+        if constexpr (SPL >= 2) {
+            const float r1 = v - bf16_to_f32(h);
+            const bf16_t m = f32_to_bf16(r1);
+            f[1].s[j] = m;
+            if constexpr (SPL >= 3) f[2].s[j] = f32_to_bf16(r1 - bf16_to_f32(m));
+        }
+    }
+    static __device__ __forceinline__ void store_split(bf16_t* p, size_t plane, float v) {
+        const bf16_t h = f32_to_bf16(v);
+        const float r1 = v - bf16_to_f32(h);
+        const bf16_t m = f32_to_bf16(r1);
+        p[0] = h;
+        p[plane] = m;
+        p[2 * plane] = f32_to_bf16(r1 - bf16_to_f32(m));
+    }
 };
 
 __device__ __forceinline__ float wave_sum(float v) {

@@ -143,13 +143,13 @@ __global__ __launch_bounds__(256) void step_begin_kernel(const StepParams* __res
 
 // ---------------------------------------------------------------------------------------------
 // Residual add + RMSNorm.  x[r] += sum_s part[s][r] (fixed order), then
-// xn[r] = x[r] * gain / sqrt(mean(x[r]^2) + eps) in the storage dtype (the next GEMM's operand),
+// xn[r] = x[r] * gain / sqrt(mean(x[r]^2) + eps) as the next GEMM's operand (three planes in bf16),
 // optionally also in fp32 (final hidden state for the judge, Eq. 4).
 template <typename T>
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(int R, int d, float eps, float* __restrict__ x,
                                                           const float* __restrict__ part, int nparts,
                                                           const T* __restrict__ gain, T* __restrict__ xn,
-                                                          float* __restrict__ xn32) {
+                                                          size_t xplane, float* __restrict__ xn32) {
     __shared__ float red[4];
     const int r = blockIdx.x;
     float* xr = x + (size_t)r * d;
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(int R, int d, float ep
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     for (int c = threadIdx.x; c < d; c += 256) {
         const float v = xr[c] * inv * Traits<T>::load(gain + c);
-        Traits<T>::store(xn + (size_t)r * d + c, v);
+        Traits<T>::store_split(xn + (size_t)r * d + c, xplane, v);
         if (xn32) xn32[(size_t)r * d + c] = v;
     }
 }
@@ -178,7 +178,9 @@ enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_LOGITS = 2 };
 
 struct GemmArgs {
     const void* Wt;     // tiled weights
-    const void* X;      // [MT*16][ldx] storage dtype, rows >= R are padding
+    const void* X;      // [SPL planes][MT*16][ldx] storage dtype, rows >= R are padding
+    size_t xplane;      // elements between consecutive planes of X
+    size_t actplane;    // same for act
     int32_t ldx, K, N, R;
     float* out;         // EPI_PARTIAL: [gridDim.y][R][N] fp32;  EPI_LOGITS: [R][N] fp32
     void* act;          // EPI_SWIGLU: [MT*16][N/2] storage dtype = silu(gate) * up
@@ -186,10 +188,10 @@ struct GemmArgs {
     float inv_temp;     // 1/T, 0 when T = 0
 };
 
-template <typename T, int NT, int MT, int EPI>
+template <typename T, int NT, int MT, int EPI, int SPL>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
-    constexpr int U = (NT * MT >= 8) ? 1 : (NT >= 2 ? 4 : 8);
+    constexpr int U = (NT * MT * SPL >= 8) ? 1 : (NT * SPL >= 2 ? 4 : 8);
     __shared__ float red[4][NT * MT][256];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 
     int ks = ks0;
     for (; ks + U <= ks1; ks += U) {
-        Frag fa[U][NT], fb[U][MT];
+        Frag fa[U][NT], fb[U][MT][SPL];
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -218,25 +220,33 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int m = 0; m < MT; ++m)
-                fb[u][m].u = *reinterpret_cast<const u32x4*>(X + (size_t)(m * 16 + r) * a.ldx + (size_t)(ks + u) * KSTEP + g * KF);
+#pragma unroll
+                for (int sp = 0; sp < SPL; ++sp)
+                    fb[u][m][sp].u = *reinterpret_cast<const u32x4*>(X + sp * a.xplane + (size_t)(m * 16 + r) * a.ldx + (size_t)(ks + u) * KSTEP + g * KF);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int t = 0; t < NT; ++t)
 #pragma unroll
-                for (int m = 0; m < MT; ++m) Traits<T>::mma(fa[u][t], fb[u][m], acc[t][m]);
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(fa[u][t], fb[u][m][sp], acc[t][m]);
     }
     for (; ks < ks1; ++ks) {
-        Frag fa[NT], fb[MT];
+        Frag fa[NT], fb[MT][SPL];
 #pragma unroll
         for (int t = 0; t < NT; ++t) fa[t].u = __builtin_nontemporal_load(Wt + ((size_t)(nt0 + t) * KS + ks) * 64 + lane);
 #pragma unroll
         for (int m = 0; m < MT; ++m)
-            fb[m].u = *reinterpret_cast<const u32x4*>(X + (size_t)(m * 16 + r) * a.ldx + (size_t)ks * KSTEP + g * KF);
+#pragma unroll
+            for (int sp = 0; sp < SPL; ++sp)
+                fb[m][sp].u = *reinterpret_cast<const u32x4*>(X + sp * a.xplane + (size_t)(m * 16 + r) * a.ldx + (size_t)ks * KSTEP + g * KF);
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int m = 0; m < MT; ++m) Traits<T>::mma(fa[t], fb[m], acc[t][m]);
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(fa[t], fb[m][sp], acc[t][m]);
     }
 
     // D[n = 4g+i][row = r]  ->  red[w][tile][row*16 + n]
@@ -268,7 +278,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
             if (row < a.R) {
                 const float gate = v[0], up = v[NT - 1];
                 const float y = gate / (1.0f + expf(-gate)) * up;
-                Traits<T>::store(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)blockIdx.x * 16 + en, y);
+                Traits<T>::store_split(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)blockIdx.x * 16 + en, a.actplane, y);
             }
         } else {
             // logits + this workgroup's softmax partial for the row (16 lanes share a row)
@@ -308,7 +318,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void rope_append_kernel(const StepParams* __restrict__ sp, ModelDims md,
                                                           const float* __restrict__ part, int nparts, int R,
                                                           const float* __restrict__ cs, T* __restrict__ qbuf,
-                                                          int Mpad, KvView<T> kv, int layer) {
+                                                          size_t qplane, int Mpad, KvView<T> kv, int layer) {
     const int r = blockIdx.x;
     const int rps = sp->rps;
     const int bi = r / rps, j = r % rps;
@@ -337,8 +347,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const StepParams* __re
         if (head < md.Hq) {
             const int kvh = head / md.G, gi = head % md.G;
             T* q = qbuf + (((size_t)bi * md.Hkv + kvh) * Mpad + (size_t)gi * rps + j) * hd;
-            Traits<T>::store(q + i, olo);
-            Traits<T>::store(q + i + half, ohi);
+            Traits<T>::store_split(q + i, qplane, olo);
+            Traits<T>::store_split(q + i + half, qplane, ohi);
         } else if (in_cap) {
             const int kvh = head - md.Hq;
             T* k = Kb + ((size_t)kvh * cap + pos) * hd;
@@ -363,13 +373,14 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const StepParams* __re
 // so that a lane's S^T accumulators are exactly its B-operand elements of the second product:
 // no LDS transpose, no cross-lane traffic except the running-max reduction over the 4 lane groups.
 // Row m = gi*rps + j sees keys 0 .. len + j.  Writes the chunk's unnormalised O, running max and sum.
-template <typename T, int HD, int MQ>
+template <typename T, int HD, int MQ, int SPL>
 __global__ __launch_bounds__(64) void attn_partial_kernel(const StepParams* __restrict__ sp, ModelDims md,
-                                                          const T* __restrict__ qbuf, int Mpad, KvView<T> kv, int layer,
+                                                          const T* __restrict__ qbuf, size_t qplane, int Mpad, KvView<T> kv, int layer,
                                                           int chunk_keys, int nchunk_max, float* __restrict__ opart,
                                                           float2* __restrict__ mlpart) {
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
     constexpr int NS = KF / 4;       // S^T tiles per step of KSTEP keys
+    static_assert(SPL <= Traits<T>::NS, "more planes than the storage type has");
     constexpr int KK = HD / KSTEP;   // contraction steps over the head dimension
     constexpr int HT = HD / 16;
     const int chunk = blockIdx.x, kvh = blockIdx.y % md.Hkv, qg = blockIdx.y / md.Hkv, bi = blockIdx.z;
@@ -386,12 +397,14 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const StepParams* __re
     const T* Vb = kv.V + (size_t)layer * kv.layer_stride + kv.seq_off[b] + (size_t)kvh * HD * cap;
     const T* Q = qbuf + (((size_t)bi * md.Hkv + kvh) * Mpad + (size_t)qg * MQ * 16) * HD;
 
-    Frag qf[MQ][KK];
+    Frag qf[MQ][KK][SPL];
 #pragma unroll
     for (int mq = 0; mq < MQ; ++mq)
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
-            qf[mq][kk].u = *reinterpret_cast<const u32x4*>(Q + (size_t)(mq * 16 + r) * HD + kk * KSTEP + g * KF);
+#pragma unroll
+            for (int sp = 0; sp < SPL; ++sp)
+                qf[mq][kk][sp].u = *reinterpret_cast<const u32x4*>(Q + sp * qplane + (size_t)(mq * 16 + r) * HD + kk * KSTEP + g * KF);
 
     f32x4 o[HT][MQ];
     float m_run[MQ], l_run[MQ];
@@ -420,14 +433,16 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const StepParams* __re
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-                for (int mq = 0; mq < MQ; ++mq) Traits<T>::mma(kf[kk], qf[mq][kk], s[t][mq]);
+                for (int mq = 0; mq < MQ; ++mq)
+#pragma unroll
+                    for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(kf[kk], qf[mq][kk][sp], s[t][mq]);
         }
         Frag vf[HT];
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
             vf[ht].u = *reinterpret_cast<const u32x4*>(Vb + (size_t)(ht * 16 + r) * cap + key0 + g * KF);
 
-        Frag pf[MQ];
+        Frag pf[MQ][SPL];
 #pragma unroll
         for (int mq = 0; mq < MQ; ++mq) {
             float mx = -INFINITY;
@@ -452,7 +467,7 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const StepParams* __re
                 for (int i = 0; i < 4; ++i) {
                     const float p = dead ? 0.f : expf(s[t][mq][i] - m_new);
                     psum += p;
-                    Traits<T>::pack(pf[mq], 4 * t + i, p);
+                    Traits<T>::template pack_split<SPL>(pf[mq], 4 * t + i, p);
                 }
             l_run[mq] = l_run[mq] * alpha + psum;
             m_run[mq] = m_new;
@@ -462,7 +477,9 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const StepParams* __re
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
-            for (int mq = 0; mq < MQ; ++mq) Traits<T>::mma(vf[ht], pf[mq], o[ht][mq]);
+            for (int mq = 0; mq < MQ; ++mq)
+#pragma unroll
+                for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(vf[ht], pf[mq][sp], o[ht][mq]);
     }
 
     const size_t pbase = (((size_t)bi * md.Hkv + kvh) * nchunk_max + chunk) * Mpad;
@@ -489,7 +506,8 @@ template <typename T, int HD>
 __global__ __launch_bounds__(HD) void attn_merge_kernel(const StepParams* __restrict__ sp, ModelDims md, int Mpad,
                                                         const int32_t* __restrict__ len, const int32_t* __restrict__ capv,
                                                         int chunk_keys, int nchunk_max, const float* __restrict__ opart,
-                                                        const float2* __restrict__ mlpart, T* __restrict__ attn_out) {
+                                                        const float2* __restrict__ mlpart, T* __restrict__ attn_out,
+                                                        size_t aplane) {
     const int m = blockIdx.x, kvh = blockIdx.y, bi = blockIdx.z;
     const int rps = sp->rps;
     if (m >= md.G * rps) return;
@@ -509,7 +527,7 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(const StepParams* __rest
     const int gi = m / rps, j = m % rps;
     const int qh = kvh * md.G + gi;
     const size_t row = (size_t)bi * rps + j;
-    Traits<T>::store(attn_out + (row * md.Hq + qh) * HD + threadIdx.x, num / den);
+    Traits<T>::store_split(attn_out + (row * md.Hq + qh) * HD + threadIdx.x, aplane, num / den);
 }
 
 // ---------------------------------------------------------------------------------------------

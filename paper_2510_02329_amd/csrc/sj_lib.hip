@@ -81,6 +81,14 @@ struct sj_kv {
     int chunk_keys = 64, nchunk_max = 1, nslab = 0, slab_len = 0;
     int split_qkv = 1, split_o = 1, split_d = 1, lm_nt = 2;
     int mode = SJ_MODE_TWO_STAGE;
+    int planes = 2;            // bf16 planes of the activation operand (fp32 storage: always 1)
+    int32_t* pinned_state = nullptr;      // [2*batch] staging of sj_kv_rewind
+    hipEvent_t rewind_done = nullptr;
+    bool rewind_pending = false;
+    // optional timing of one kernel class (eager launches only)
+    int timing_class = 0;
+    std::vector<hipEvent_t> tev;          // start/stop pairs
+    size_t tev_used = 0;
     int last_gamma = 0, last_rows = 0;
     std::vector<void*> allocs;
 };
@@ -294,7 +302,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     ALLOC(kv->len_dev, sizeof(int32_t) * batch);
     ALLOC(kv->pending_dev, sizeof(int32_t) * batch);
     ALLOC(kv->sp_dev, sizeof(StepParams));
-    ALLOC(kv->xn, (size_t)kv->rpad * d * m->esz);
+    ALLOC(kv->xn, (size_t)3 * kv->rpad * d * m->esz);          // up to three operand planes
     ALLOC(kv->hn32, (size_t)R * d * 4);
     ALLOC(kv->row_tok, (size_t)R * 4);
     ALLOC(kv->logits, (size_t)R * V * 4);
@@ -317,12 +325,12 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         const int hd = c.head_dim, Nq = c.n_q_heads * hd, Nk = c.n_kv_heads * hd, F = c.d_ffn;
         const int G = c.n_q_heads / c.n_kv_heads;
         const int kstep = (c.dtype == SJ_DTYPE_FP32) ? 16 : 32;
-        kv->split_qkv = choose_split((Nq + 2 * Nk) / 16, d / kstep);
-        kv->split_o = choose_split(d / 16, Nq / kstep);
-        kv->split_d = choose_split(d / 16, F / kstep);
+        kv->split_qkv = choose_split((Nq + 2 * Nk) / 32, d / kstep);
+        kv->split_o = choose_split(d / 32, Nq / kstep);
+        kv->split_d = choose_split(d / 32, F / kstep);
         size_t part_elems = std::max({(size_t)kv->split_qkv * R * (Nq + 2 * Nk), (size_t)kv->split_o * R * d,
                                       (size_t)kv->split_d * R * d});
-        kv->mpad = (G * (c.max_gamma + 1) + 15) / 16 * 16;
+        kv->mpad = (G * (c.max_gamma + 1) + 63) / 64 * 64;   // whole groups of 4 MFMA tiles
         // key chunks: enough waves to fill the chip, at least 64 keys each
         {
             const int64_t total_keys = off / ((int64_t)c.n_kv_heads * hd);
@@ -335,11 +343,11 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         ALLOC(kv->V, (size_t)kv->layer_stride * c.n_layers * m->esz);
         ALLOC(kv->x, (size_t)R * d * 4);
         ALLOC(kv->part, part_elems * 4);
-        ALLOC(kv->qbuf, (size_t)batch * c.n_kv_heads * kv->mpad * hd * m->esz);
+        ALLOC(kv->qbuf, (size_t)3 * batch * c.n_kv_heads * kv->mpad * hd * m->esz);
         ALLOC(kv->opart, (size_t)batch * c.n_kv_heads * kv->nchunk_max * kv->mpad * hd * 4);
         ALLOC(kv->mlpart, (size_t)batch * c.n_kv_heads * kv->nchunk_max * kv->mpad * sizeof(float2));
-        ALLOC(kv->attn_out, (size_t)kv->rpad * Nq * m->esz);
-        ALLOC(kv->act, (size_t)kv->rpad * F * m->esz);
+        ALLOC(kv->attn_out, (size_t)3 * kv->rpad * Nq * m->esz);
+        ALLOC(kv->act, (size_t)3 * kv->rpad * F * m->esz);
         ALLOC(kv->cs, (size_t)R * hd * 4);
         ALLOC(kv->prefill_tok, (size_t)R * 4);
     }
@@ -353,6 +361,10 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
 
 extern "C" int sj_kv_free(sj_kv* kv) {
     if (!kv) return fail(SJ_EINVAL, "kv is null");
+    (void)hipDeviceSynchronize();
+    if (kv->pinned_state) (void)hipHostFree(kv->pinned_state);
+    if (kv->rewind_done) (void)hipEventDestroy(kv->rewind_done);
+    for (hipEvent_t e : kv->tev) (void)hipEventDestroy(e);
     free_all(kv->allocs);
     delete kv;
     return SJ_OK;
@@ -362,6 +374,71 @@ extern "C" int sj_set_mode(sj_kv* kv, int32_t mode) {
     if (!kv) return fail(SJ_EINVAL, "kv is null");
     if (mode < 0 || mode > 2) return fail(SJ_EINVAL, "mode must be 0, 1 or 2");
     kv->mode = mode;
+    return SJ_OK;
+}
+
+extern "C" int sj_kv_rewind(sj_kv* kv, const int32_t* len_host, const int32_t* pending_host, void* stream) {
+    if (!kv || !len_host || !pending_host) return fail(SJ_EINVAL, "null argument");
+    for (int b = 0; b < kv->batch; ++b) {
+        if (len_host[b] < 0 || len_host[b] > kv->cap[b]) return fail(SJ_ECAPACITY, "len[%d] = %d outside capacity %d", b, len_host[b], kv->cap[b]);
+        if (pending_host[b] < 0 || pending_host[b] >= kv->m->cfg.vocab) return fail(SJ_EINVAL, "pending[%d] out of range", b);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (!kv->pinned_state) {
+        HIPCHK(hipHostMalloc((void**)&kv->pinned_state, sizeof(int32_t) * 2 * kv->batch, hipHostMallocDefault));
+        HIPCHK(hipEventCreateWithFlags(&kv->rewind_done, hipEventDisableTiming));
+    }
+    if (kv->rewind_pending) HIPCHK(hipEventSynchronize(kv->rewind_done));   // staging still being read
+    std::memcpy(kv->pinned_state, len_host, sizeof(int32_t) * kv->batch);
+    std::memcpy(kv->pinned_state + kv->batch, pending_host, sizeof(int32_t) * kv->batch);
+    HIPCHK(hipMemcpyAsync(kv->len_dev, kv->pinned_state, sizeof(int32_t) * kv->batch, hipMemcpyHostToDevice, st));
+    HIPCHK(hipMemcpyAsync(kv->pending_dev, kv->pinned_state + kv->batch, sizeof(int32_t) * kv->batch, hipMemcpyHostToDevice, st));
+    HIPCHK(hipEventRecord(kv->rewind_done, st));
+    kv->rewind_pending = true;
+    for (int b = 0; b < kv->batch; ++b) kv->len_upper[b] = len_host[b];
+    return SJ_OK;
+}
+
+extern "C" int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class) {
+    if (!kv) return fail(SJ_EINVAL, "kv is null");
+    if (kernel_class < 0 || kernel_class > 4) return fail(SJ_EINVAL, "kernel_class must be 0..4");
+    kv->timing_class = kernel_class;
+    kv->tev_used = 0;
+    return SJ_OK;
+}
+
+extern "C" int sj_get_kernel_timing(sj_kv* kv, double* total_ms, int64_t* launches) {
+    if (!kv || !total_ms || !launches) return fail(SJ_EINVAL, "null argument");
+    HIPCHK(hipDeviceSynchronize());
+    double tot = 0.0;
+    for (size_t i = 0; i + 1 < kv->tev_used; i += 2) {
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, kv->tev[i], kv->tev[i + 1]));
+        tot += ms;
+    }
+    *total_ms = tot;
+    *launches = (int64_t)(kv->tev_used / 2);
+    kv->tev_used = 0;
+    return SJ_OK;
+}
+
+// records an event on the stream if kernel class `cls` is being timed; pairs are (start, stop)
+static int time_mark(sj_kv* kv, int cls, hipStream_t st) {
+    if (kv->timing_class != cls) return SJ_OK;
+    if (kv->tev_used == kv->tev.size()) {
+        if (kv->tev.size() >= (1u << 16)) return SJ_OK;         // enough samples; stop recording
+        hipEvent_t e;
+        HIPCHK(hipEventCreate(&e));
+        kv->tev.push_back(e);
+    }
+    HIPCHK(hipEventRecord(kv->tev[kv->tev_used++], st));
+    return SJ_OK;
+}
+
+extern "C" int sj_set_operand_planes(sj_kv* kv, int32_t planes) {
+    if (!kv) return fail(SJ_EINVAL, "kv is null");
+    if (planes < 1 || planes > 3) return fail(SJ_EINVAL, "planes must be 1, 2 or 3");
+    kv->planes = planes;
     return SJ_OK;
 }
 
@@ -475,12 +552,12 @@ extern "C" int sj_kv_state(const sj_kv* kv, int32_t* len_host, int32_t* pending_
 // ------------------------------------------------------------------------------------------------
 // kernel sequence
 
-template <typename T, int NT, int EPI>
+template <typename T, int NT, int EPI, int SPL>
 static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) {
     switch (mt) {
-        case 1: gemm_skinny_kernel<T, NT, 1, EPI><<<grid, 256, 0, st>>>(a); break;
-        case 2: gemm_skinny_kernel<T, NT, 2, EPI><<<grid, 256, 0, st>>>(a); break;
-        case 3: gemm_skinny_kernel<T, NT, 3, EPI><<<grid, 256, 0, st>>>(a); break;
+        case 1: gemm_skinny_kernel<T, NT, 1, EPI, SPL><<<grid, 256, 0, st>>>(a); break;
+        case 2: gemm_skinny_kernel<T, NT, 2, EPI, SPL><<<grid, 256, 0, st>>>(a); break;
+        case 3: gemm_skinny_kernel<T, NT, 3, EPI, SPL><<<grid, 256, 0, st>>>(a); break;
         default: return fail(SJ_EINVAL, "internal: unsupported m-tile count %d", mt);
     }
     LAUNCHCHK("gemm_skinny");
@@ -488,41 +565,32 @@ static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) 
 }
 
 // Y = X W^T for all `rows` rows; rows are processed in groups of at most 48 (3 MFMA tiles).
-template <typename T, int NT, int EPI>
-static int gemm(hipStream_t st, const void* Wt, const void* X, int ldx, int K, int N, int rows, int split, float* out,
-                void* act, float4* stats, float inv_temp) {
+// X has SPL planes `xplane` elements apart; act (EPI_SWIGLU) gets the same plane distance.
+template <typename T, int NT, int EPI, int SPL>
+static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
+                float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
     const int ngroups = N / 16 / NT;
+    if (EPI == EPI_PARTIAL && rows > 48) split = 1;     // slice stride below assumes one slice then
     for (int row0 = 0; row0 < rows; row0 += 48) {
         const int nr = std::min(48, rows - row0);
         GemmArgs a{};
         a.Wt = Wt;
         a.X = (const char*)X + (size_t)row0 * ldx * sizeof(T);
+        a.xplane = xplane;
+        a.actplane = actplane;
         a.ldx = ldx; a.K = K; a.N = N;
         a.R = nr;
         a.inv_temp = inv_temp;
-        if (EPI == EPI_PARTIAL) {
-            // partial layout is [split][rows][N]: a row group writes its rows of every split slice
-            a.out = out + (size_t)row0 * N;
-            a.R = nr;
-        } else if (EPI == EPI_LOGITS) {
-            a.out = out + (size_t)row0 * N;
-            a.stats = stats + (size_t)row0 * ngroups;
-        } else {
-            a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
-        }
-        int rc;
-        if (EPI == EPI_PARTIAL && rows > 48) {
-            // the kernel indexes partials as [s][a.R][N]; with several row groups the slice stride must be
-            // the full row count, so launch one K-slice at a time
-            return fail(SJ_EINVAL, "internal: split-K with more than 48 rows goes through gemm_rows()");
-        }
-        rc = launch_gemm_mt<T, NT, EPI>((nr + 15) / 16, dim3(ngroups, split), st, a);
+        if (EPI == EPI_PARTIAL) a.out = out + (size_t)row0 * N;            // [split][rows][N], split = 1 if grouped
+        else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ngroups; }
+        else a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
+        int rc = launch_gemm_mt<T, NT, EPI, SPL>((nr + 15) / 16, dim3(ngroups, split), st, a);
         if (rc) return rc;
     }
     return SJ_OK;
 }
 
-template <typename T>
+template <typename T, int SPL>
 struct Runner {
     const sj_model* m;
     sj_kv* kv;
@@ -535,22 +603,11 @@ struct Runner {
         v.len = kv->len_dev; v.pending = kv->pending_dev; v.layer_stride = kv->layer_stride;
         return v;
     }
+    size_t plane(int ld) const { return (size_t)kv->rpad * ld; }
+    size_t qplane() const { return (size_t)kv->batch * m->md.Hkv * kv->mpad * m->md.hd; }
 
     int partial_gemm(const void* W, const void* X, int ldx, int K, int N, int split) {
-        // more than 48 rows: no K split across workgroups (slice stride = row count of the group)
-        if (R > 48) {
-            for (int row0 = 0; row0 < R; row0 += 48) {
-                const int nr = std::min(48, R - row0);
-                GemmArgs a{};
-                a.Wt = W; a.X = (const char*)X + (size_t)row0 * ldx * sizeof(T);
-                a.ldx = ldx; a.K = K; a.N = N; a.R = nr;
-                a.out = kv->part + (size_t)row0 * N;
-                int rc = launch_gemm_mt<T, 1, EPI_PARTIAL>((nr + 15) / 16, dim3(N / 16, 1), st, a);
-                if (rc) return rc;
-            }
-            return SJ_OK;
-        }
-        return gemm<T, 1, EPI_PARTIAL>(st, W, X, ldx, K, N, R, split, kv->part, nullptr, nullptr, 0.f);
+        return gemm<T, 2, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, split, kv->part, nullptr, 0, nullptr, 0.f);
     }
     int nparts(int split) const { return R > 48 ? 1 : split; }
 
@@ -562,7 +619,7 @@ struct Runner {
         const int qgroups = (mtiles + mq - 1) / mq;
         dim3 grid(kv->nchunk_max, md.Hkv * qgroups, nseq);
 #define ATTN(HD, MQ)                                                                                          \
-    attn_partial_kernel<T, HD, MQ><<<grid, 64, 0, st>>>(kv->sp_dev, md, (const T*)kv->qbuf, kv->mpad, view(), layer, \
+    attn_partial_kernel<T, HD, MQ, SPL><<<grid, 64, 0, st>>>(kv->sp_dev, md, (const T*)kv->qbuf, qplane(), kv->mpad, view(), layer, \
                                                         kv->chunk_keys, kv->nchunk_max, kv->opart, kv->mlpart)
         if (md.hd == 128) {
             switch (mq) { case 1: ATTN(128, 1); break; case 2: ATTN(128, 2); break; case 3: ATTN(128, 3); break; default: ATTN(128, 4); }
@@ -574,10 +631,10 @@ struct Runner {
         dim3 mg(M, md.Hkv, nseq);
         if (md.hd == 128)
             attn_merge_kernel<T, 128><<<mg, 128, 0, st>>>(kv->sp_dev, md, kv->mpad, kv->len_dev, kv->cap_dev, kv->chunk_keys,
-                                                           kv->nchunk_max, kv->opart, kv->mlpart, (T*)kv->attn_out);
+                                                           kv->nchunk_max, kv->opart, kv->mlpart, (T*)kv->attn_out, plane(md.Hq * md.hd));
         else
             attn_merge_kernel<T, 64><<<mg, 64, 0, st>>>(kv->sp_dev, md, kv->mpad, kv->len_dev, kv->cap_dev, kv->chunk_keys,
-                                                         kv->nchunk_max, kv->opart, kv->mlpart, (T*)kv->attn_out);
+                                                         kv->nchunk_max, kv->opart, kv->mlpart, (T*)kv->attn_out, plane(md.Hq * md.hd));
         LAUNCHCHK("attn_merge");
         return SJ_OK;
     }
@@ -595,31 +652,42 @@ struct Runner {
         for (int l = 0; l < c.n_layers; ++l) {
             const LayerW& L = m->layers[l];
             add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)L.attn_norm,
-                                                      (T*)kv->xn, nullptr);
+                                                      (T*)kv->xn, plane(d), nullptr);
             LAUNCHCHK("add_rmsnorm");
+            if ((rc = time_mark(kv, 1, st))) return rc;
             if ((rc = partial_gemm(L.wqkv, kv->xn, d, d, Nqkv, kv->split_qkv))) return rc;
+            if ((rc = time_mark(kv, 1, st))) return rc;
             rope_append_kernel<T><<<R, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->split_qkv), R, kv->cs,
-                                                      (T*)kv->qbuf, kv->mpad, view(), l);
+                                                      (T*)kv->qbuf, qplane(), kv->mpad, view(), l);
             LAUNCHCHK("rope_append");
             if ((rc = attention(l))) return rc;
+            if ((rc = time_mark(kv, 2, st))) return rc;
             if ((rc = partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->split_o))) return rc;
+            if ((rc = time_mark(kv, 2, st))) return rc;
             add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, nparts(kv->split_o), (const T*)L.ffn_norm,
-                                                      (T*)kv->xn, nullptr);
+                                                      (T*)kv->xn, plane(d), nullptr);
             LAUNCHCHK("add_rmsnorm");
-            if ((rc = gemm<T, 2, EPI_SWIGLU>(st, L.wgu, kv->xn, d, d, 2 * md.F, R, 1, nullptr, kv->act, nullptr, 0.f))) return rc;
+            if ((rc = time_mark(kv, 3, st))) return rc;
+            if ((rc = gemm<T, 2, EPI_SWIGLU, SPL>(st, L.wgu, kv->xn, plane(d), d, d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f))) return rc;
+            if ((rc = time_mark(kv, 3, st))) return rc;
+            if ((rc = time_mark(kv, 4, st))) return rc;
             if ((rc = partial_gemm(L.wd, kv->act, md.F, md.F, d, kv->split_d))) return rc;
+            if ((rc = time_mark(kv, 4, st))) return rc;
             pending_parts = nparts(kv->split_d);
         }
         add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)m->final_norm,
-                                                  (T*)kv->xn, kv->hn32);
+                                                  (T*)kv->xn, plane(d), kv->hn32);
         LAUNCHCHK("add_rmsnorm");
         return SJ_OK;
     }
 
     // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max))
-    int lm_head() {
+    int lm_head(bool exact_operand) {
         const ModelDims& md = m->md;
-        int rc = gemm<T, 2, EPI_LOGITS>(st, m->lm_head, kv->xn, md.d, md.d, md.V, R, 1, kv->logits, nullptr, kv->stats, md.inv_temp);
+        // hidden states handed in by the caller are already in the storage dtype: one plane suffices
+        int rc = exact_operand
+            ? gemm<T, 2, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
+            : gemm<T, 2, EPI_LOGITS, SPL>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
         if (rc) return rc;
         const int nblk = md.V / 32;
         softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, md.inv_temp, kv->rowstat);
@@ -657,12 +725,12 @@ static int set_params(sj_kv* kv, hipStream_t st, const StepParams& p) {
     return SJ_OK;
 }
 
-template <typename T>
+template <typename T, int SPL>
 static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,
                             const void* hidden) {
     int rc = set_params(kv, st, p);
     if (rc) return rc;
-    Runner<T> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
+    Runner<T, SPL> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
     if (head_only) {
         const size_t n = (size_t)run.R * m->md.d;
         HIPCHK(hipMemcpyAsync(kv->xn, hidden, n * sizeof(T), hipMemcpyDeviceToDevice, st));
@@ -671,8 +739,18 @@ static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams&
     } else {
         if ((rc = run.layers())) return rc;
     }
-    if ((rc = run.lm_head())) return rc;
+    if ((rc = run.lm_head(head_only))) return rc;
     return run.tail(gamma);
+}
+
+static int dispatch_step(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,
+                         const void* hidden) {
+    if (m->cfg.dtype == SJ_DTYPE_FP32) return verify_step_impl<float, 1>(m, kv, gamma, p, st, head_only, hidden);
+    switch (kv->planes) {
+        case 1: return verify_step_impl<bf16_t, 1>(m, kv, gamma, p, st, head_only, hidden);
+        case 3: return verify_step_impl<bf16_t, 3>(m, kv, gamma, p, st, head_only, hidden);
+        default: return verify_step_impl<bf16_t, 2>(m, kv, gamma, p, st, head_only, hidden);
+    }
 }
 
 static int check_step_args(sj_model* m, sj_kv* kv, int gamma, const void* a, const void* b, const void* c, const void* d,
@@ -706,8 +784,7 @@ extern "C" int sj_verify_step(sj_model* m, sj_kv* kv, int32_t gamma, const int32
     p.draft_tokens = draft_tokens; p.draft_probs = draft_probs; p.uniforms = uniforms;
     p.accepted_len = accepted_len; p.next_token = next_token;
     hipStream_t st = (hipStream_t)stream;
-    rc = (m->cfg.dtype == SJ_DTYPE_FP32) ? verify_step_impl<float>(m, kv, gamma, p, st, false, nullptr)
-                                         : verify_step_impl<bf16_t>(m, kv, gamma, p, st, false, nullptr);
+    rc = dispatch_step(m, kv, gamma, p, st, false, nullptr);
     if (rc) return rc;
     for (int b = 0; b < kv->batch; ++b) kv->len_upper[b] += gamma + 1;
     kv->last_gamma = gamma;
@@ -728,15 +805,14 @@ extern "C" int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void*
     p.draft_tokens = draft_tokens; p.draft_probs = draft_probs; p.uniforms = uniforms;
     p.accepted_len = accepted_len; p.next_token = next_token;
     hipStream_t st = (hipStream_t)stream;
-    rc = (m->cfg.dtype == SJ_DTYPE_FP32) ? verify_step_impl<float>(m, kv, gamma, p, st, true, hidden)
-                                         : verify_step_impl<bf16_t>(m, kv, gamma, p, st, true, hidden);
+    rc = dispatch_step(m, kv, gamma, p, st, true, hidden);
     if (rc) return rc;
     kv->last_gamma = gamma;
     kv->last_rows = kv->batch * (gamma + 1);
     return SJ_OK;
 }
 
-template <typename T>
+template <typename T, int SPL>
 static int prefill_impl(sj_model* m, sj_kv* kv, int seq, const int32_t* tokens, int n, hipStream_t st) {
     const int chunk_max = std::min(kv->max_rows, m->cfg.max_gamma + 1);
     for (int t0 = 0; t0 < n; t0 += chunk_max) {
@@ -747,9 +823,9 @@ static int prefill_impl(sj_model* m, sj_kv* kv, int seq, const int32_t* tokens, 
         p.nseq = 1; p.seq_base = seq; p.rps = cn; p.gamma = cn - 1; p.tok_mode = 1; p.prefill_tokens = kv->prefill_tok;
         int rc = set_params(kv, st, p);
         if (rc) return rc;
-        Runner<T> run{m, kv, st, 1, cn, cn};
+        Runner<T, SPL> run{m, kv, st, 1, cn, cn};
         if ((rc = run.layers())) return rc;
-        if (last && (rc = run.lm_head())) return rc;
+        if (last && (rc = run.lm_head(false))) return rc;
         prefill_commit_kernel<<<1, 1, 0, st>>>(kv->sp_dev, kv->rowstat, kv->len_dev, kv->pending_dev, last ? 1 : 0);
         LAUNCHCHK("prefill_commit");
         HIPCHK(hipStreamSynchronize(st));     // the pageable token copy of the next chunk must not race
@@ -769,8 +845,10 @@ extern "C" int sj_prefill(sj_model* m, sj_kv* kv, int32_t seq, const int32_t* to
     if (rc) return rc;
     if (kv->len_upper[seq] + n > kv->cap[seq]) return fail(SJ_ECAPACITY, "prefill of %d tokens exceeds capacity", n);
     hipStream_t st = (hipStream_t)stream;
-    rc = (m->cfg.dtype == SJ_DTYPE_FP32) ? prefill_impl<float>(m, kv, seq, tokens_host, n, st)
-                                         : prefill_impl<bf16_t>(m, kv, seq, tokens_host, n, st);
+    if (m->cfg.dtype == SJ_DTYPE_FP32) rc = prefill_impl<float, 1>(m, kv, seq, tokens_host, n, st);
+    else if (kv->planes == 1) rc = prefill_impl<bf16_t, 1>(m, kv, seq, tokens_host, n, st);
+    else if (kv->planes == 3) rc = prefill_impl<bf16_t, 3>(m, kv, seq, tokens_host, n, st);
+    else rc = prefill_impl<bf16_t, 2>(m, kv, seq, tokens_host, n, st);
     if (rc) return rc;
     kv->len_upper[seq] += n;
     kv->last_gamma = 0;

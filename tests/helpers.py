@@ -27,7 +27,7 @@ def oracle_weights(src: synth.WeightSource, cache_items: int = 64):
             lru.move_to_end(key)
             return lru[key]
         a = synth.to_f64(src.tensor(name, layer, rows))
-        if a.nbytes <= (64 << 20):
+        if cache_items and a.nbytes <= (64 << 20):
             lru[key] = a
             if len(lru) > cache_items:
                 lru.popitem(last=False)

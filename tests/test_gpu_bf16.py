@@ -1,0 +1,117 @@
+"""GPU parity in bf16: a scaled-down Llama-shaped decoder with grouped-query attention (several MFMA
+tiles, ragged cache lengths, a batch) and the full 8B-shaped batch-1 workload the benchmark times."""
+import numpy as np
+import pytest
+
+import paper_2510_02329_amd as sj
+import synth
+from oracle import selfjudge_oracle as orc
+from tests import gpu_common as G
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+
+
+def _fill_caches(shape, gpu, cfg, lens, seed, capacity):
+    caches = []
+    pend = synth.make_pending(shape, seed)
+    for b in range(shape.batch):
+        c = orc.SeqCache(cfg, capacity[b], storage=shape.dtype)
+        for l in range(shape.n_layers):
+            k, v = synth.make_kv_cache(shape, seed, b, l, int(lens[b]))
+            sj.sj_kv_set_layer(gpu.kv, b, l, k, v, int(lens[b]))
+            c.k[l][:, :lens[b]] = synth.to_f64(k)
+            c.v[l][:, :lens[b]] = synth.to_f64(v)
+        c.length, c.pending = int(lens[b]), int(pend[b])
+        sj.sj_kv_set_state(gpu.kv, b, int(lens[b]), int(pend[b]))
+        caches.append(c)
+    return caches
+
+
+def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label):
+    B, gamma = draft["tokens"].shape
+    L0 = [c.length for c in caches]
+    out = gpu.step(draft, theta, gamma)
+    ref = orc.verify_step(cfg, W, caches, draft["tokens"], draft["probs"], draft["uniforms"], theta)
+    stats = {}
+    for b in range(B):
+        stats["logits"] = G.close_enough(out["logits"][b], ref[b]["logits"], shape.dtype, f"{label} logits seq {b}")
+        G.close_enough(out["hn"][b], ref[b]["hn"], shape.dtype, f"{label} hidden seq {b}")
+        G.close_enough(out["judge_scores"][b], ref[b]["judge_scores"], shape.dtype, f"{label} judge seq {b}")
+        for l in (0, shape.n_layers - 1):
+            k, v = gpu.kv_rows(b, l, L0[b], gamma + 1)
+            G.close_enough(k, ref[b]["k_new"][l], shape.dtype, f"{label} appended K seq {b} layer {l}")
+            G.close_enough(v, ref[b]["v_new"][l], shape.dtype, f"{label} appended V seq {b} layer {l}")
+    # decisions: exact on replay of the device's own logits; against the pure oracle a mismatch is
+    # excused only when the oracle's margin is inside the logit tolerance
+    bad, excused = G.replay_matches(shape, out, draft, theta)
+    assert not bad, bad
+    a_tol, r_tol = G.TOL[shape.dtype]
+    unexcused = 0
+    for b in range(B):
+        for j in range(gamma):
+            ra = bool(ref[b]["align_bits"][j]); ga = bool(out["bits"][b, j] & 1)
+            rj = bool(ref[b]["judge_bits"][j]); gj = bool(out["bits"][b, j] & 2)
+            d = int(draft["tokens"][b, j])
+            if ra != ga:
+                p, q, u = ref[b]["p_at_draft"][j], float(draft["probs"][b, j, d]), float(draft["uniforms"][b, j])
+                tau = a_tol + r_tol * abs(ref[b]["logits"][j, d])
+                if abs(np.log(p) - np.log(max(u * q, 1e-300))) > 2 * tau:
+                    unexcused += 1
+            if rj != gj:
+                s = ref[b]["judge_scores"][j]
+                z = np.log(s / (1 - s))
+                if abs(z - np.log(theta / (1 - theta))) > a_tol + r_tol * abs(z):
+                    unexcused += 1
+    assert unexcused == 0
+    ln, pend = sj.sj_kv_state(gpu.kv, B)
+    assert (0 <= out["accepted_len"]).all() and (out["accepted_len"] <= gamma).all()
+    assert (ln == np.array(L0) + 1 + out["accepted_len"]).all()
+    assert (pend == out["next_token"]).all()
+    return out, ref, stats
+
+
+SMALL = synth.ModelShape("small_bf16", "bf16", 3, 512, 8, 2, 128, 1408, 5024, 500000.0,
+                         batch=3, gamma=5, weight_std=0.05)
+
+
+@pytest.mark.parametrize("theta", [0.5])
+def test_small_gqa_bf16_two_steps(theta):
+    shape = SMALL
+    src = synth.WeightSource(shape, seed=1, norm_jitter=0.1, judge_bias=-0.1)
+    cap = [448, 448, 448]
+    gpu = G.Gpu(shape, src, cap)
+    try:
+        cfg = helpers.oracle_config(shape)
+        W = helpers.oracle_weights(src)
+        lens = [70, 200, 333]
+        caches = _fill_caches(shape, gpu, cfg, lens, seed=2, capacity=cap)
+        for step in range(2):
+            draft = synth.make_draft(shape, seed=20 + step)
+            out, ref, _ = _compare_step(shape, gpu, cfg, W, caches, draft, theta, f"step {step}")
+            # keep both sides on the same trajectory for the chained step even if a near-tie differed
+            for b, c in enumerate(caches):
+                c.length = c.length - 1 - ref[b]["accepted_len"] + 1 + int(out["accepted_len"][b])
+                c.pending = int(out["next_token"][b])
+    finally:
+        gpu.close()
+
+
+def test_llama8b_batch1_full_size():
+    """The benchmark workload: 32 layers, d 4096, 32/8 heads of 128, FFN 14336, vocab 128256, cache 1024,
+    gamma 5, in the launch configuration bench.py times.  The oracle runs the whole step in fp64."""
+    shape = synth.CONFIGS[2]
+    src = synth.WeightSource(shape, seed=0)
+    cap = [1024 + 64]
+    print("loading 8B-shaped model", flush=True)
+    gpu = G.Gpu(shape, src, cap)
+    try:
+        cfg = helpers.oracle_config(shape)
+        W = helpers.oracle_weights(src, cache_items=0)
+        caches = _fill_caches(shape, gpu, cfg, shape.kv_lengths(0), seed=0, capacity=cap)
+        draft = synth.make_draft(shape, seed=0)
+        print("step", flush=True)
+        out, ref, stats = _compare_step(shape, gpu, cfg, W, caches, draft, 0.5, "8B")
+        print("8B logits max err %.3e worst err/bound %.2f" % stats["logits"], flush=True)
+    finally:
+        gpu.close()

@@ -19,7 +19,7 @@ def tiny():
     gpu = G.Gpu(shape, src, [192])
     cfg = helpers.oracle_config(shape)
     W = helpers.oracle_weights(src)
-    cache = orc.SeqCache(cfg, 192)
+    cache = orc.SeqCache(cfg, 192, storage=shape.dtype)
     prompt = synth.make_prompt(shape, 0, 128)
     print("prefill gpu", flush=True)
     sj.sj_prefill(gpu.model, gpu.kv, 0, prompt.tolist())

@@ -307,6 +307,52 @@ def test_batch_rows_are_independent():
     assert np.allclose(both[1]["logits"], b["logits"], atol=1e-12)
 
 
+def test_storage_rounding_matches_library_and_ties_to_even():
+    rng = np.random.default_rng(1)
+    a32 = (rng.standard_normal(50000) * 10 ** rng.uniform(-4, 4, 50000)).astype(np.float32)
+    got = orc.round_to_storage(a32.astype(np.float64), "bf16")
+    ref = torch.from_numpy(a32).to(torch.bfloat16).double().numpy()       # fp32 inputs: no double rounding
+    assert np.array_equal(got, ref)
+    assert orc.round_to_storage(np.array([1 + 2.0 ** -8]), "bf16")[0] == 1.0              # tie -> even
+    assert orc.round_to_storage(np.array([1 + 3 * 2.0 ** -8]), "bf16")[0] == 1 + 2.0 ** -6
+    assert orc.round_to_storage(np.array([1 + 2.0 ** -8 + 2.0 ** -40]), "bf16")[0] == 1 + 2.0 ** -7
+    assert orc.round_to_storage(np.array([-0.3]), "bf16")[0] == -0.30078125
+    x = rng.standard_normal(1000)
+    assert np.array_equal(orc.round_to_storage(x, "fp32"), x.astype(np.float32).astype(np.float64))
+    assert np.array_equal(orc.round_to_storage(x, "fp64"), x)
+
+
+@pytest.mark.parametrize("storage", ["bf16", "fp32"])
+def test_block_equals_sequential_on_stored_cache(storage):
+    """With a bf16 / fp32 cache the block's own rows are read back as stored, so the block forward
+    still equals token-by-token decoding exactly (no tolerance beyond fp64 summation order)."""
+    shape, cfg, t = _tiny(2)
+    W = helpers.dict_weights(t)
+    L, toks = 9, [3, 1, 4, 1, 5]
+    def mk():
+        c = helpers.random_cache(cfg, L, 24, seed=7)
+        c.storage = storage
+        for l in range(cfg.n_layers):
+            c.k[l][:] = orc.round_to_storage(c.k[l], storage)
+            c.v[l][:] = orc.round_to_storage(c.v[l], storage)
+        return c
+    cb, cs = mk(), mk()
+    blk = orc.block_forward(cfg, W, [cb], [toks])[0]
+    for j, tok in enumerate(toks):
+        one = orc.block_forward(cfg, W, [cs], [[tok]])[0]
+        cs.length += 1
+        assert np.allclose(one["logits"][0], blk["logits"][j], atol=1e-11, rtol=1e-11)
+    for l in range(cfg.n_layers):
+        assert np.array_equal(cs.k[l][:, :L + 5], cb.k[l][:, :L + 5])
+        assert np.array_equal(cb.k[l][:, L:L + 5], orc.round_to_storage(cb.k[l][:, L:L + 5], storage))
+    # and the stored rows differ from what an unrounded cache would hold
+    cu = helpers.random_cache(cfg, L, 24, seed=7)
+    for l in range(cfg.n_layers):
+        cu.k[l][:] = orc.round_to_storage(cu.k[l], storage); cu.v[l][:] = orc.round_to_storage(cu.v[l], storage)
+    orc.block_forward(cfg, W, [cu], [toks])
+    assert not np.array_equal(cu.k[0][:, L:L + 5], cb.k[0][:, L:L + 5])
+
+
 # ------------------------------------------------------------------ P5: library cross-check of the decoder
 
 
