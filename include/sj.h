@@ -82,8 +82,9 @@ typedef struct sj_kv sj_kv;         /* opaque: KV cache, per-sequence state, ste
 typedef int (*sj_tensor_fn)(void* user, int32_t tensor_id, int32_t layer, void* dst_host, size_t nbytes);
 
 /* Uploads and re-tiles the target model's weights (needed by Eq. 2 / Eq. 4 / Eq. 5).
- * Requirements: d_model, head_dim, d_ffn, vocab multiples of 32; n_q_heads a multiple of
- * n_kv_heads; head_dim in {64, 128}.  Synchronous.  *out is set only on success. */
+ * Requirements: d_model and d_ffn multiples of 64, vocab a multiple of 128, d_model <= 16384;
+ * n_q_heads a multiple of n_kv_heads; head_dim in {64, 128}.  Synchronous.  *out is set only on
+ * success. */
 int sj_model_load(const sj_config* cfg, sj_tensor_fn provider, void* user, sj_model** out);
 int sj_model_free(sj_model* m);
 

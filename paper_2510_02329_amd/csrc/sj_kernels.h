@@ -146,26 +146,47 @@ __global__ __launch_bounds__(256) void step_begin_kernel(const StepParams* __res
 // xn[r] = x[r] * gain / sqrt(mean(x[r]^2) + eps) as the next GEMM's operand (three planes in bf16),
 // optionally also in fp32 (final hidden state for the judge, Eq. 4).
 template <typename T>
-__global__ __launch_bounds__(256) void add_rmsnorm_kernel(int R, int d, float eps, float* __restrict__ x,
-                                                          const float* __restrict__ part, int nparts,
-                                                          const T* __restrict__ gain, T* __restrict__ xn,
-                                                          size_t xplane, float* __restrict__ xn32) {
-    __shared__ float red[4];
+__global__ __launch_bounds__(1024) void add_rmsnorm_kernel(int R, int d, float eps, float* __restrict__ x,
+                                                           const float* __restrict__ part, int nparts,
+                                                           const T* __restrict__ gain, T* __restrict__ xn,
+                                                           size_t xplane, float* __restrict__ xn32) {
+    // one workgroup of 1024 threads per row, 4 columns per thread and pass; all loads of a pass are
+    // independent.  Rows wider than 16384 columns are not supported (host-checked).
+    constexpr int MAXP = 4;
+    __shared__ float red[16];
     const int r = blockIdx.x;
     float* xr = x + (size_t)r * d;
+    f32x4 v[MAXP];
     float ss = 0.f;
-    for (int c = threadIdx.x; c < d; c += 256) {
-        float v = xr[c];
-        for (int s = 0; s < nparts; ++s) v += part[((size_t)s * R + r) * d + c];
-        if (nparts) xr[c] = v;
-        ss += v * v;
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        const int c = (p * 1024 + threadIdx.x) * 4;
+        v[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (c < d) {
+            v[p] = *reinterpret_cast<const f32x4*>(xr + c);
+            for (int s = 0; s < nparts; ++s) v[p] += *reinterpret_cast<const f32x4*>(part + ((size_t)s * R + r) * d + c);
+            if (nparts) *reinterpret_cast<f32x4*>(xr + c) = v[p];
+            ss += v[p][0] * v[p][0] + v[p][1] * v[p][1] + v[p][2] * v[p][2] + v[p][3] * v[p][3];
+        }
     }
-    ss = block_sum_256(ss, red);
-    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = threadIdx.x; c < d; c += 256) {
-        const float v = xr[c] * inv * Traits<T>::load(gain + c);
-        Traits<T>::store_split(xn + (size_t)r * d + c, xplane, v);
-        if (xn32) xn32[(size_t)r * d + c] = v;
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w];
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        const int c = (p * 1024 + threadIdx.x) * 4;
+        if (c < d) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float y = v[p][i] * inv * Traits<T>::load(gain + c + i);
+                Traits<T>::store_split(xn + (size_t)r * d + c + i, xplane, y);
+                if (xn32) xn32[(size_t)r * d + c + i] = y;
+            }
+        }
     }
 }
 
@@ -188,19 +209,27 @@ struct GemmArgs {
     float inv_temp;     // 1/T, 0 when T = 0
 };
 
-template <typename T, int NT, int MT, int EPI, int SPL>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
+template <typename T, int NT, int MT, int EPI, int SPL, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
-    constexpr int U = (NT * MT * SPL >= 8) ? 1 : (NT * SPL >= 2 ? 4 : 8);
-    __shared__ float red[4][NT * MT][256];
+    constexpr int UU = 12 / (NT + MT * SPL);
+    constexpr int U = UU < 1 ? 1 : (UU > 4 ? 4 : UU);         // k-steps per register buffer
+    __shared__ float red[WAVES][NT * MT][256];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
     const int KS = a.K / KSTEP;
     const int nt0 = blockIdx.x * NT;
-    const int parts = gridDim.y * 4, part = blockIdx.y * 4 + w;
+    const int parts = gridDim.y * WAVES, part = blockIdx.y * WAVES + w;
     const int ks0 = (int)((long long)part * KS / parts), ks1 = (int)((long long)(part + 1) * KS / parts);
-    const u32x4* Wt = reinterpret_cast<const u32x4*>(a.Wt);
-    const T* X = reinterpret_cast<const T*>(a.X);
+    const u32x4* Wt = reinterpret_cast<const u32x4*>(a.Wt) + ((size_t)nt0 * KS + ks0) * 64 + lane;
+    // padding rows (>= R) feed columns of D that are never stored: let them re-read row 0 instead of
+    // touching more cache lines
+    const T* Xr[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int row = m * 16 + r;
+        Xr[m] = reinterpret_cast<const T*>(a.X) + (size_t)(row < a.R ? row : 0) * a.ldx + (size_t)ks0 * KSTEP + g * KF;
+    }
 
     f32x4 acc[NT][MT];
 #pragma unroll
@@ -208,21 +237,25 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[t][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    int ks = ks0;
-    for (; ks + U <= ks1; ks += U) {
-        Frag fa[U][NT], fb[U][MT][SPL];
+    // Two register buffers of U k-steps each; the loads of the next buffer are always issued (index
+    // clamped to the last chunk) before the current one is consumed, so the loop body is branch-free
+    // around the loads and the hardware keeps one buffer's worth of weight tiles in flight.
+    Frag fa[2][U][NT], fb[2][U][MT][SPL];
+    auto load = [&](int buf, int chunk) {
+        const size_t k = (size_t)chunk * U;
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                fa[u][t].u = __builtin_nontemporal_load(Wt + ((size_t)(nt0 + t) * KS + ks + u) * 64 + lane);
+            for (int t = 0; t < NT; ++t) fa[buf][u][t].u = __builtin_nontemporal_load(Wt + ((size_t)t * KS + k + u) * 64);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int sp = 0; sp < SPL; ++sp)
-                    fb[u][m][sp].u = *reinterpret_cast<const u32x4*>(X + sp * a.xplane + (size_t)(m * 16 + r) * a.ldx + (size_t)(ks + u) * KSTEP + g * KF);
+                    fb[buf][u][m][sp].u = *reinterpret_cast<const u32x4*>(Xr[m] + sp * a.xplane + (k + u) * KSTEP);
+    };
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -230,23 +263,32 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
 #pragma unroll
-                    for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(fa[u][t], fb[u][m][sp], acc[t][m]);
+                    for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(fa[buf][u][t], fb[buf][u][m][sp], acc[t][m]);
+    };
+    const int nchunk = (ks1 - ks0) / U;
+    if (nchunk > 0) {
+        load(0, 0);
+        for (int c = 0; c < nchunk; c += 2) {
+            load(1, min(c + 1, nchunk - 1));
+            compute(0);
+            load(0, min(c + 2, nchunk - 1));
+            if (c + 1 < nchunk) compute(1);
+        }
     }
-    for (; ks < ks1; ++ks) {
-        Frag fa[NT], fb[MT][SPL];
+    for (int ks = nchunk * U; ks < ks1 - ks0; ++ks) {          // remainder k-steps
+        Frag ta[NT], tb[MT][SPL];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) fa[t].u = __builtin_nontemporal_load(Wt + ((size_t)(nt0 + t) * KS + ks) * 64 + lane);
+        for (int t = 0; t < NT; ++t) ta[t].u = __builtin_nontemporal_load(Wt + ((size_t)t * KS + ks) * 64);
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
-            for (int sp = 0; sp < SPL; ++sp)
-                fb[m][sp].u = *reinterpret_cast<const u32x4*>(X + sp * a.xplane + (size_t)(m * 16 + r) * a.ldx + (size_t)ks * KSTEP + g * KF);
+            for (int sp = 0; sp < SPL; ++sp) tb[m][sp].u = *reinterpret_cast<const u32x4*>(Xr[m] + sp * a.xplane + (size_t)ks * KSTEP);
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
-                for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(fa[t], fb[m][sp], acc[t][m]);
+                for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(ta[t], tb[m][sp], acc[t][m]);
     }
 
     // D[n = 4g+i][row = r]  ->  red[w][tile][row*16 + n]
@@ -258,6 +300,9 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
             for (int i = 0; i < 4; ++i) red[w][t * MT + m][r * 16 + 4 * g + i] = acc[t][m][i];
     __syncthreads();
 
+    // the first 256 threads own one (row, column) position of every tile; partial sums are added in
+    // wave order
+    if (threadIdx.x >= 256) return;
     const int tid = threadIdx.x;
     const int er = tid >> 4, en = tid & 15;
 #pragma unroll
@@ -265,8 +310,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
         const int row = m * 16 + er;
         float v[NT];
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-            v[t] = ((red[0][t * MT + m][tid] + red[1][t * MT + m][tid]) + red[2][t * MT + m][tid]) + red[3][t * MT + m][tid];
+        for (int t = 0; t < NT; ++t) {
+            float sum = red[0][t * MT + m][tid];
+#pragma unroll
+            for (int ww = 1; ww < WAVES; ++ww) sum += red[ww][t * MT + m][tid];
+            v[t] = sum;
+        }
         if constexpr (EPI == EPI_PARTIAL) {
             if (row < a.R) {
 #pragma unroll
@@ -274,11 +323,15 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
                     a.out[((size_t)blockIdx.y * a.R + row) * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
             }
         } else if constexpr (EPI == EPI_SWIGLU) {
-            static_assert(EPI != EPI_SWIGLU || NT == 2, "gate/up pairs");
+            static_assert(EPI != EPI_SWIGLU || NT % 2 == 0, "gate/up tiles come in adjacent pairs");
             if (row < a.R) {
-                const float gate = v[0], up = v[NT - 1];
-                const float y = gate / (1.0f + expf(-gate)) * up;
-                Traits<T>::store_split(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)blockIdx.x * 16 + en, a.actplane, y);
+#pragma unroll
+                for (int p = 0; p < NT / 2; ++p) {
+                    const float gate = v[2 * p], up = v[2 * p + 1];
+                    const float y = gate / (1.0f + expf(-gate)) * up;
+                    Traits<T>::store_split(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) +
+                                               ((size_t)blockIdx.x * (NT / 2) + p) * 16 + en, a.actplane, y);
+                }
             }
         } else {
             // logits + this workgroup's softmax partial for the row (16 lanes share a row)
@@ -315,7 +368,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 // the cache at position len + j (v transposed).  A row whose position would fall outside the
 // sequence's capacity writes nothing (the host refuses such calls before launching).
 template <typename T>
-__global__ __launch_bounds__(256) void rope_append_kernel(const StepParams* __restrict__ sp, ModelDims md,
+__global__ __launch_bounds__(512) void rope_append_kernel(const StepParams* __restrict__ sp, ModelDims md,
                                                           const float* __restrict__ part, int nparts, int R,
                                                           const float* __restrict__ cs, T* __restrict__ qbuf,
                                                           size_t qplane, int Mpad, KvView<T> kv, int layer) {
@@ -333,12 +386,13 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const StepParams* __re
     const float* csr = cs + (size_t)r * half * 2;
     auto val = [&](int col) {
         float v = 0.f;
+#pragma unroll 4
         for (int s = 0; s < nparts; ++s) v += part[((size_t)s * R + r) * N + col];
         return v;
     };
     // q and k: pairs (i, i + half) of every head
     const int npairs = (md.Hq + md.Hkv) * half;
-    for (int p = threadIdx.x; p < npairs; p += 256) {
+    for (int p = threadIdx.x; p < npairs; p += 512) {
         const int head = p / half, i = p % half;
         const float c = csr[2 * i], s = csr[2 * i + 1];
         const int col = head * hd + i;                     // q heads then k heads are contiguous in N
@@ -357,7 +411,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const StepParams* __re
         }
     }
     if (in_cap) {
-        for (int e = threadIdx.x; e < Nk; e += 256) {
+        for (int e = threadIdx.x; e < Nk; e += 512) {
             const int kvh = e / hd, dcol = e % hd;
             Traits<T>::store(Vb + ((size_t)kvh * hd + dcol) * cap + pos, val(Nq + Nk + e));
         }
@@ -515,14 +569,32 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(const StepParams* __rest
     const int kv_end = min(len[b] + rps, capv[b]);
     const int nch = (kv_end + chunk_keys - 1) / chunk_keys;
     const size_t pbase = ((size_t)bi * md.Hkv + kvh) * nchunk_max;
+    // chunk statistics first (independent loads), then the weighted sum in chunk order
+    constexpr int CH = 8;
     float mx = -INFINITY;
-    for (int c = 0; c < nch; ++c) mx = fmaxf(mx, mlpart[(pbase + c) * Mpad + m].x);
+    for (int c0 = 0; c0 < nch; c0 += CH) {
+        float t[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) t[i] = (c0 + i < nch) ? mlpart[(pbase + c0 + i) * Mpad + m].x : -INFINITY;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) mx = fmaxf(mx, t[i]);
+    }
     float den = 0.f, num = 0.f;
-    for (int c = 0; c < nch; ++c) {
-        const float2 ml = mlpart[(pbase + c) * Mpad + m];
-        const float wgt = (ml.x == -INFINITY) ? 0.f : expf(ml.x - mx);
-        den += wgt * ml.y;
-        if (wgt != 0.f) num += wgt * opart[((pbase + c) * Mpad + m) * HD + threadIdx.x];
+    for (int c0 = 0; c0 < nch; c0 += CH) {
+        float2 ml[CH];
+        float o[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool in = c0 + i < nch;
+            ml[i] = in ? mlpart[(pbase + c0 + i) * Mpad + m] : float2{-INFINITY, 0.f};
+            o[i] = in ? opart[((pbase + c0 + i) * Mpad + m) * HD + threadIdx.x] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const float wgt = (ml[i].x == -INFINITY) ? 0.f : expf(ml[i].x - mx);
+            den += wgt * ml[i].y;
+            if (wgt != 0.f) num += wgt * o[i];
+        }
     }
     const int gi = m / rps, j = m % rps;
     const int qh = kvh * md.G + gi;

@@ -86,6 +86,10 @@ struct sj_kv {
     hipEvent_t rewind_done = nullptr;
     bool rewind_pending = false;
     // optional timing of one kernel class (eager launches only)
+    // captured launch graphs of the full step, keyed by (gamma, planes)
+    std::map<int, hipGraphExec_t> graphs;
+    hipStream_t cap_stream = nullptr;
+    bool use_graph = true;
     int timing_class = 0;
     std::vector<hipEvent_t> tev;          // start/stop pairs
     size_t tev_used = 0;
@@ -119,14 +123,15 @@ static int check_config(const sj_config* c) {
     if (!c) return fail(SJ_EINVAL, "config is null");
     if (c->dtype != SJ_DTYPE_FP32 && c->dtype != SJ_DTYPE_BF16) return fail(SJ_EINVAL, "dtype must be 0 (fp32) or 1 (bf16)");
     if (c->n_layers < 0 || c->d_model <= 0 || c->vocab <= 0) return fail(SJ_EINVAL, "non-positive model dimension");
-    if (c->d_model % 32 || c->vocab % 32) return fail(SJ_EINVAL, "d_model and vocab must be multiples of 32");
+    if (c->d_model % 64 || c->vocab % 128) return fail(SJ_EINVAL, "d_model must be a multiple of 64 and vocab of 128");
+    if (c->d_model > 16384) return fail(SJ_EINVAL, "d_model above 16384 is not supported");
     if (c->max_gamma < 1 || c->max_gamma > 63) return fail(SJ_EINVAL, "max_gamma must be in 1..63");
     if (!(c->temperature >= 0.f)) return fail(SJ_EINVAL, "temperature must be >= 0");
     if (c->n_layers > 0) {
         if (c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->d_ffn <= 0) return fail(SJ_EINVAL, "non-positive model dimension");
         if (c->head_dim != 64 && c->head_dim != 128) return fail(SJ_EINVAL, "head_dim must be 64 or 128");
         if (c->n_q_heads % c->n_kv_heads) return fail(SJ_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
-        if (c->d_ffn % 32) return fail(SJ_EINVAL, "d_ffn must be a multiple of 32");
+        if (c->d_ffn % 64) return fail(SJ_EINVAL, "d_ffn must be a multiple of 64");
         if (!(c->rope_base > 1.f) || !(c->rms_eps >= 0.f)) return fail(SJ_EINVAL, "bad rope_base / rms_eps");
     }
     return SJ_OK;
@@ -257,9 +262,11 @@ extern "C" int64_t sj_model_weight_bytes(const sj_model* m) { return m ? m->weig
 // ------------------------------------------------------------------------------------------------
 // kv / workspace
 
+// K-slices across workgroups for the projections whose output is summed by the consumer: enough
+// workgroups to cover the chip, every wave keeping at least 8 k-steps
 static int choose_split(int groups, int ksteps) {
-    int s = (768 + groups - 1) / groups;
-    s = std::min(s, std::max(1, ksteps / 16));
+    int s = (384 + groups - 1) / groups;
+    s = std::min(s, std::max(1, ksteps / 32));
     return std::max(1, std::min(s, 8));
 }
 
@@ -272,6 +279,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     if (!kv) return fail(SJ_ENOMEM, "host allocation failed");
     kv->m = m;
     kv->batch = batch;
+    if (const char* e = std::getenv("SJ_NO_GRAPH")) kv->use_graph = !(e[0] == '1');
     kv->cap.assign(batch, 64);
     kv->len_upper.assign(batch, 0);
     kv->seq_off.assign(batch, 0);
@@ -325,9 +333,9 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         const int hd = c.head_dim, Nq = c.n_q_heads * hd, Nk = c.n_kv_heads * hd, F = c.d_ffn;
         const int G = c.n_q_heads / c.n_kv_heads;
         const int kstep = (c.dtype == SJ_DTYPE_FP32) ? 16 : 32;
-        kv->split_qkv = choose_split((Nq + 2 * Nk) / 32, d / kstep);
-        kv->split_o = choose_split(d / 32, Nq / kstep);
-        kv->split_d = choose_split(d / 32, F / kstep);
+        kv->split_qkv = choose_split((Nq + 2 * Nk) / 64, d / kstep);
+        kv->split_o = choose_split(d / 64, Nq / kstep);
+        kv->split_d = choose_split(d / 64, F / kstep);
         size_t part_elems = std::max({(size_t)kv->split_qkv * R * (Nq + 2 * Nk), (size_t)kv->split_o * R * d,
                                       (size_t)kv->split_d * R * d});
         kv->mpad = (G * (c.max_gamma + 1) + 63) / 64 * 64;   // whole groups of 4 MFMA tiles
@@ -365,6 +373,8 @@ extern "C" int sj_kv_free(sj_kv* kv) {
     if (kv->pinned_state) (void)hipHostFree(kv->pinned_state);
     if (kv->rewind_done) (void)hipEventDestroy(kv->rewind_done);
     for (hipEvent_t e : kv->tev) (void)hipEventDestroy(e);
+    for (auto& g : kv->graphs) (void)hipGraphExecDestroy(g.second);
+    if (kv->cap_stream) (void)hipStreamDestroy(kv->cap_stream);
     free_all(kv->allocs);
     delete kv;
     return SJ_OK;
@@ -552,12 +562,16 @@ extern "C" int sj_kv_state(const sj_kv* kv, int32_t* len_host, int32_t* pending_
 // ------------------------------------------------------------------------------------------------
 // kernel sequence
 
-template <typename T, int NT, int EPI, int SPL>
+template <typename T, int NT, int EPI, int SPL, int WAVES>
 static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) {
+    // more than one row tile multiplies the accumulators and the reduction scratch: use at most
+    // 4 n-tiles and 4 waves there (the grid is scaled to match)
+    constexpr int NT2 = NT > 4 ? 4 : NT, W2 = WAVES > 4 ? 4 : WAVES;
+    dim3 g2(grid.x * (NT / NT2), grid.y);
     switch (mt) {
-        case 1: gemm_skinny_kernel<T, NT, 1, EPI, SPL><<<grid, 256, 0, st>>>(a); break;
-        case 2: gemm_skinny_kernel<T, NT, 2, EPI, SPL><<<grid, 256, 0, st>>>(a); break;
-        case 3: gemm_skinny_kernel<T, NT, 3, EPI, SPL><<<grid, 256, 0, st>>>(a); break;
+        case 1: gemm_skinny_kernel<T, NT, 1, EPI, SPL, WAVES><<<grid, WAVES * 64, 0, st>>>(a); break;
+        case 2: gemm_skinny_kernel<T, NT2, 2, EPI, SPL, W2><<<g2, W2 * 64, 0, st>>>(a); break;
+        case 3: gemm_skinny_kernel<T, NT2, 3, EPI, SPL, W2><<<g2, W2 * 64, 0, st>>>(a); break;
         default: return fail(SJ_EINVAL, "internal: unsupported m-tile count %d", mt);
     }
     LAUNCHCHK("gemm_skinny");
@@ -565,8 +579,9 @@ static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) 
 }
 
 // Y = X W^T for all `rows` rows; rows are processed in groups of at most 48 (3 MFMA tiles).
-// X has SPL planes `xplane` elements apart; act (EPI_SWIGLU) gets the same plane distance.
-template <typename T, int NT, int EPI, int SPL>
+// X has SPL planes `xplane` elements apart; act (EPI_SWIGLU) planes are `actplane` apart.
+// NT n-tiles per workgroup (N/16 must be a multiple of NT), WAVES waves split the K-slice.
+template <typename T, int NT, int EPI, int SPL, int WAVES>
 static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
                 float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
     const int ngroups = N / 16 / NT;
@@ -584,7 +599,7 @@ static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, in
         if (EPI == EPI_PARTIAL) a.out = out + (size_t)row0 * N;            // [split][rows][N], split = 1 if grouped
         else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ngroups; }
         else a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
-        int rc = launch_gemm_mt<T, NT, EPI, SPL>((nr + 15) / 16, dim3(ngroups, split), st, a);
+        int rc = launch_gemm_mt<T, NT, EPI, SPL, WAVES>((nr + 15) / 16, dim3(ngroups, split), st, a);
         if (rc) return rc;
     }
     return SJ_OK;
@@ -607,7 +622,7 @@ struct Runner {
     size_t qplane() const { return (size_t)kv->batch * m->md.Hkv * kv->mpad * m->md.hd; }
 
     int partial_gemm(const void* W, const void* X, int ldx, int K, int N, int split) {
-        return gemm<T, 2, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, split, kv->part, nullptr, 0, nullptr, 0.f);
+        return gemm<T, 4, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, split, kv->part, nullptr, 0, nullptr, 0.f);
     }
     int nparts(int split) const { return R > 48 ? 1 : split; }
 
@@ -651,31 +666,31 @@ struct Runner {
         int rc;
         for (int l = 0; l < c.n_layers; ++l) {
             const LayerW& L = m->layers[l];
-            add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)L.attn_norm,
+            add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)L.attn_norm,
                                                       (T*)kv->xn, plane(d), nullptr);
             LAUNCHCHK("add_rmsnorm");
             if ((rc = time_mark(kv, 1, st))) return rc;
             if ((rc = partial_gemm(L.wqkv, kv->xn, d, d, Nqkv, kv->split_qkv))) return rc;
             if ((rc = time_mark(kv, 1, st))) return rc;
-            rope_append_kernel<T><<<R, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->split_qkv), R, kv->cs,
+            rope_append_kernel<T><<<R, 512, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->split_qkv), R, kv->cs,
                                                       (T*)kv->qbuf, qplane(), kv->mpad, view(), l);
             LAUNCHCHK("rope_append");
             if ((rc = attention(l))) return rc;
             if ((rc = time_mark(kv, 2, st))) return rc;
             if ((rc = partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->split_o))) return rc;
             if ((rc = time_mark(kv, 2, st))) return rc;
-            add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, nparts(kv->split_o), (const T*)L.ffn_norm,
+            add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, nparts(kv->split_o), (const T*)L.ffn_norm,
                                                       (T*)kv->xn, plane(d), nullptr);
             LAUNCHCHK("add_rmsnorm");
             if ((rc = time_mark(kv, 3, st))) return rc;
-            if ((rc = gemm<T, 2, EPI_SWIGLU, SPL>(st, L.wgu, kv->xn, plane(d), d, d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f))) return rc;
+            if ((rc = gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, L.wgu, kv->xn, plane(d), d, d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f))) return rc;
             if ((rc = time_mark(kv, 3, st))) return rc;
             if ((rc = time_mark(kv, 4, st))) return rc;
             if ((rc = partial_gemm(L.wd, kv->act, md.F, md.F, d, kv->split_d))) return rc;
             if ((rc = time_mark(kv, 4, st))) return rc;
             pending_parts = nparts(kv->split_d);
         }
-        add_rmsnorm_kernel<T><<<R, 256, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)m->final_norm,
+        add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)m->final_norm,
                                                   (T*)kv->xn, plane(d), kv->hn32);
         LAUNCHCHK("add_rmsnorm");
         return SJ_OK;
@@ -683,13 +698,14 @@ struct Runner {
 
     // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max))
     int lm_head(bool exact_operand) {
+        constexpr int LMNT = 4;          // same tile grouping for every row-tile count (statistics layout)
         const ModelDims& md = m->md;
         // hidden states handed in by the caller are already in the storage dtype: one plane suffices
         int rc = exact_operand
-            ? gemm<T, 2, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
-            : gemm<T, 2, EPI_LOGITS, SPL>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
+            ? gemm<T, LMNT, EPI_LOGITS, 1, 4>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
+            : gemm<T, LMNT, EPI_LOGITS, SPL, 4>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
         if (rc) return rc;
-        const int nblk = md.V / 32;
+        const int nblk = md.V / 16 / LMNT;
         softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, md.inv_temp, kv->rowstat);
         LAUNCHCHK("softmax_merge");
         return SJ_OK;
@@ -726,10 +742,8 @@ static int set_params(sj_kv* kv, hipStream_t st, const StepParams& p) {
 }
 
 template <typename T, int SPL>
-static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,
-                            const void* hidden) {
-    int rc = set_params(kv, st, p);
-    if (rc) return rc;
+static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool head_only, const void* hidden) {
+    int rc;
     Runner<T, SPL> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
     if (head_only) {
         const size_t n = (size_t)run.R * m->md.d;
@@ -741,6 +755,39 @@ static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams&
     }
     if ((rc = run.lm_head(head_only))) return rc;
     return run.tail(gamma);
+}
+
+// The full step is ~200 dependent launches of a few microseconds each: it is captured once per
+// (gamma, planes) into a launch graph and replayed; only the per-call parameter block, written by a
+// tiny kernel in front of the replay, changes between calls.
+template <typename T, int SPL>
+static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,
+                            const void* hidden) {
+    int rc;
+    const bool graph = kv->use_graph && !head_only && kv->timing_class == 0;
+    if (!graph) {
+        if ((rc = set_params(kv, st, p))) return rc;
+        return enqueue_step<T, SPL>(m, kv, gamma, st, head_only, hidden);
+    }
+    const int key = gamma * 4 + SPL;
+    auto it = kv->graphs.find(key);
+    if (it == kv->graphs.end()) {
+        if (!kv->cap_stream) HIPCHK(hipStreamCreateWithFlags(&kv->cap_stream, hipStreamNonBlocking));
+        HIPCHK(hipStreamBeginCapture(kv->cap_stream, hipStreamCaptureModeRelaxed));
+        rc = enqueue_step<T, SPL>(m, kv, gamma, kv->cap_stream, false, nullptr);
+        hipGraph_t g = nullptr;
+        hipError_t e = hipStreamEndCapture(kv->cap_stream, &g);
+        if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+        if (e != hipSuccess) return fail(SJ_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+        hipGraphExec_t ex = nullptr;
+        e = hipGraphInstantiate(&ex, g, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(g);
+        if (e != hipSuccess) return fail(SJ_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+        it = kv->graphs.emplace(key, ex).first;
+    }
+    if ((rc = set_params(kv, st, p))) return rc;
+    HIPCHK(hipGraphLaunch(it->second, st));
+    return SJ_OK;
 }
 
 static int dispatch_step(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,

@@ -71,7 +71,7 @@ def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label):
     return out, ref, stats
 
 
-SMALL = synth.ModelShape("small_bf16", "bf16", 3, 512, 8, 2, 128, 1408, 5024, 500000.0,
+SMALL = synth.ModelShape("small_bf16", "bf16", 3, 512, 8, 2, 128, 1408, 4992, 500000.0,
                          batch=3, gamma=5, weight_std=0.05)
 
 
