@@ -46,8 +46,9 @@ template <typename T> struct KvView {
 // ---------------------------------------------------------------------------------------------
 // Weight re-tiling (model load).  Row-major W[N][K] -> tiles [N/16][K/KSTEP][64 lanes][16 bytes]
 // in MFMA A-operand order, so that one wave-wide 16-byte load reads 1 KB of contiguous memory.
-// interleave = 1: destination tile 2p comes from source tile p, tile 2p+1 from source tile
-// N/32 + p (gate and up projections of the same FFN columns end up adjacent).
+// interleave = 1 (stacked [gate; up] source, N = 2F): destination tile t holds gate rows
+// 8t..8t+7 in its rows 0-7 and up rows 8t..8t+7 in its rows 8-15, so every tile carries both
+// projections of 8 FFN columns and SwiGLU can be applied inside the tile's own epilogue.
 template <typename T>
 __global__ void retile_kernel(const T* __restrict__ src, T* __restrict__ dst, int N, int K, int interleave) {
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
@@ -59,9 +60,9 @@ __global__ void retile_kernel(const T* __restrict__ src, T* __restrict__ dst, in
         const size_t tile = idx >> 6;
         const int ks = (int)(tile % KS);
         const int nt = (int)(tile / KS);
-        const int snt = interleave ? ((nt & 1) * (N / 32) + (nt >> 1)) : nt;
         const int r = lane & 15, g = lane >> 4;
-        const u32x4* s = reinterpret_cast<const u32x4*>(src + (size_t)(snt * 16 + r) * K + ks * KSTEP + g * KF);
+        const int srow = interleave ? ((r >> 3) * (N / 2) + nt * 8 + (r & 7)) : nt * 16 + r;
+        const u32x4* s = reinterpret_cast<const u32x4*>(src + (size_t)srow * K + ks * KSTEP + g * KF);
         reinterpret_cast<u32x4*>(dst)[idx] = *s;
     }
 }
@@ -323,14 +324,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
                     a.out[((size_t)blockIdx.y * a.R + row) * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
             }
         } else if constexpr (EPI == EPI_SWIGLU) {
-            static_assert(EPI != EPI_SWIGLU || NT % 2 == 0, "gate/up tiles come in adjacent pairs");
-            if (row < a.R) {
+            // tile column en < 8 is gate of FFN column 8*tile + en, column en + 8 its up projection
 #pragma unroll
-                for (int p = 0; p < NT / 2; ++p) {
-                    const float gate = v[2 * p], up = v[2 * p + 1];
+            for (int t = 0; t < NT; ++t) {
+                const float up = __shfl_down(v[t], 8, 64);
+                if (row < a.R && en < 8) {
+                    const float gate = v[t];
                     const float y = gate / (1.0f + expf(-gate)) * up;
-                    Traits<T>::store_split(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) +
-                                               ((size_t)blockIdx.x * (NT / 2) + p) * 16 + en, a.actplane, y);
+                    Traits<T>::store_split(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)(nt0 + t) * 8 + en,
+                                           a.actplane, y);
                 }
             }
         } else {
@@ -646,17 +648,20 @@ __global__ __launch_bounds__(256) void softmax_merge_kernel(const float4* __rest
 // d_{j+1}, i.e. block row j + 1.
 template <typename T>
 __global__ __launch_bounds__(256) void judge_kernel(const StepParams* __restrict__ sp, int d,
-                                                    const float* __restrict__ hn32, const T* __restrict__ w,
-                                                    const T* __restrict__ bias, float* __restrict__ scores) {
+                                                    const float* __restrict__ hn32, const float* __restrict__ row_scale,
+                                                    const T* __restrict__ w, const T* __restrict__ bias,
+                                                    float* __restrict__ scores) {
     __shared__ float red[4];
     const int gamma = sp->gamma;
     const int bi = blockIdx.x / gamma, j = blockIdx.x % gamma;
-    const float* h = hn32 + ((size_t)bi * (gamma + 1) + j + 1) * d;
+    const int row = bi * (gamma + 1) + j + 1;
+    const float* h = hn32 + (size_t)row * d;
     float acc = 0.f;
     for (int c = threadIdx.x; c < d; c += 256) acc += h[c] * Traits<T>::load(w + c);
     acc = block_sum_256(acc, red);
     if (threadIdx.x == 0) {
-        const float z = acc + Traits<T>::load(bias);
+        // row_scale: the hidden state was stored without its 1/rms factor (applied here)
+        const float z = acc * (row_scale ? row_scale[row] : 1.0f) + Traits<T>::load(bias);
         scores[blockIdx.x] = 1.0f / (1.0f + expf(-z));
     }
 }

@@ -2,6 +2,7 @@
 // upload / re-tiling, and the kernel sequence of one verification step.
 #include "../../include/sj.h"
 #include "sj_kernels.h"
+#include "sj_mega.h"
 
 #include <algorithm>
 #include <cmath>
@@ -58,6 +59,9 @@ struct sj_model {
     std::vector<void*> allocs;
     int64_t weight_bytes = 0;
     int device = 0;
+    MegaLayer* mega_layers = nullptr;     // device table for the persistent forward kernel (bf16 only)
+    int num_cus = 0;
+    bool coop = false;
 };
 
 struct sj_kv {
@@ -90,6 +94,13 @@ struct sj_kv {
     std::map<int, hipGraphExec_t> graphs;
     hipStream_t cap_stream = nullptr;
     bool use_graph = true;
+    // persistent forward kernel (small row counts)
+    bool use_mega = true;
+    bf16_t *Bx = nullptr, *Battn = nullptr, *Bact = nullptr;
+    float *ssq = nullptr, *row_scale = nullptr;
+    MegaBar* bar = nullptr;
+    unsigned mega_epoch = 0;
+    size_t mega_lds = 0;
     int timing_class = 0;
     std::vector<hipEvent_t> tev;          // start/stop pairs
     size_t tev_used = 0;
@@ -245,6 +256,22 @@ extern "C" int sj_model_load(const sj_config* cfg, sj_tensor_fn provider, void* 
     if ((rc = ld.tiled(&lm_id, &lm_n, 1, -1, d, 0, &m->lm_head))) return cleanup(rc);
     if ((rc = ld.plain(SJ_T_JUDGE_W, -1, d, &m->judge_w))) return cleanup(rc);
     if ((rc = ld.plain(SJ_T_JUDGE_B, -1, 1, &m->judge_b))) return cleanup(rc);
+    if (cfg->dtype == SJ_DTYPE_BF16 && cfg->n_layers > 0) {
+        std::vector<MegaLayer> tab(cfg->n_layers);
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            const LayerW& L = m->layers[l];
+            tab[l] = MegaLayer{(const u32x4*)L.wqkv, (const u32x4*)L.wo, (const u32x4*)L.wgu, (const u32x4*)L.wd,
+                               (const bf16_t*)L.attn_norm, (const bf16_t*)L.ffn_norm};
+        }
+        if ((rc = dev_alloc(m->allocs, &m->mega_layers, sizeof(MegaLayer) * tab.size(), false))) return cleanup(rc);
+        if (hipMemcpy(m->mega_layers, tab.data(), sizeof(MegaLayer) * tab.size(), hipMemcpyHostToDevice) != hipSuccess)
+            return cleanup(fail(SJ_EHIP, "hipMemcpy of the layer table failed"));
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, m->device) == hipSuccess) {
+            m->num_cus = prop.multiProcessorCount;
+            m->coop = prop.cooperativeLaunch != 0;
+        }
+    }
     cleanup(0);
     *out = m;
     return SJ_OK;
@@ -280,6 +307,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     kv->m = m;
     kv->batch = batch;
     if (const char* e = std::getenv("SJ_NO_GRAPH")) kv->use_graph = !(e[0] == '1');
+    if (const char* e = std::getenv("SJ_NO_MEGA")) kv->use_mega = !(e[0] == '1');
     kv->cap.assign(batch, 64);
     kv->len_upper.assign(batch, 0);
     kv->seq_off.assign(batch, 0);
@@ -358,6 +386,15 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         ALLOC(kv->act, (size_t)3 * kv->rpad * F * m->esz);
         ALLOC(kv->cs, (size_t)R * hd * 4);
         ALLOC(kv->prefill_tok, (size_t)R * 4);
+        if (c.dtype == SJ_DTYPE_BF16) {
+            ALLOC(kv->Bx, (size_t)d * 32);                 // packed operands: K/32 tiles of 1 KB
+            ALLOC(kv->Battn, (size_t)Nq * 32);
+            ALLOC(kv->Bact, (size_t)F * 32);
+            ALLOC(kv->ssq, (size_t)MEGA_MAXR * (d / 16) * 4);
+            ALLOC(kv->row_scale, (size_t)std::max(R, MEGA_MAXR) * 4);
+            ALLOC(kv->bar, sizeof(MegaBar));
+            kv->mega_lds = offsetof(MegaShared, red) + std::max(sizeof(AttnShared), sizeof(float) * 2 * MEGA_WAVES * 256);
+        }
     }
 #undef ALLOC
     if (hipMemcpy(kv->seq_off_dev, kv->seq_off.data(), sizeof(int64_t) * batch, hipMemcpyHostToDevice) != hipSuccess ||
@@ -712,9 +749,9 @@ struct Runner {
     }
 
     // Eq. 3, Eq. 5, scan, extra token, state commit
-    int tail(int gamma) {
+    int tail(int gamma, const float* row_scale = nullptr) {
         const ModelDims& md = m->md;
-        judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores);
+        judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, row_scale, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores);
         LAUNCHCHK("judge");
         accept_scan_kernel<<<nseq, 64, 0, st>>>(kv->sp_dev, md.V, md.inv_temp, kv->logits, kv->rowstat, kv->scores, kv->p_at_d,
                                                  kv->bits, kv->nacc);
@@ -760,10 +797,63 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
 // The full step is ~200 dependent launches of a few microseconds each: it is captured once per
 // (gamma, planes) into a launch graph and replayed; only the per-call parameter block, written by a
 // tiny kernel in front of the replay, changes between calls.
+// The persistent forward kernel serves bf16 models when the whole batch fits 8 query rows.
+static bool mega_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl) {
+    const sj_config& c = m->cfg;
+    if (!kv->use_mega || !m->coop || m->num_cus < 1 || c.dtype != SJ_DTYPE_BF16 || spl != 2 || kv->timing_class) return false;
+    const int R = kv->batch * (gamma + 1), G = c.n_q_heads / c.n_kv_heads;
+    if (R > MEGA_MAXR || G * (gamma + 1) > 32 || c.head_dim != 128) return false;
+    const int Nq = c.n_q_heads * c.head_dim;
+    auto ok = [](int K, int D) { return K % (32 * MEGA_WAVES) == 0 && (K / 32 / MEGA_WAVES) % D == 0; };
+    return ok(c.d_model, MEGA_D) && ok(Nq, MEGA_D) && ok(c.d_ffn, MEGA_D / 2) && m->num_cus <= 1024;
+}
+
+static int launch_mega(sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
+    MegaArgs a{};
+    a.layers = m->mega_layers;
+    a.lm_head = (const u32x4*)m->lm_head;
+    a.final_gain = (const bf16_t*)m->final_norm;
+    a.embed = (const bf16_t*)m->embed;
+    a.NL = m->cfg.n_layers;
+    a.md = m->md;
+    a.sp = kv->sp_dev;
+    a.kv.K = (bf16_t*)kv->K; a.kv.V = (bf16_t*)kv->V; a.kv.seq_off = kv->seq_off_dev; a.kv.cap = kv->cap_dev;
+    a.kv.len = kv->len_dev; a.kv.pending = kv->pending_dev; a.kv.layer_stride = kv->layer_stride;
+    a.x = kv->x; a.qkv = kv->part; a.Bx = kv->Bx; a.Battn = kv->Battn; a.Bact = kv->Bact; a.ssq = kv->ssq;
+    a.hn32 = kv->hn32; a.row_scale = kv->row_scale; a.logits = kv->logits; a.stats = kv->stats; a.cs = kv->cs;
+    a.bar = kv->bar;
+    const unsigned nbar = 1u + 5u * (unsigned)m->cfg.n_layers;
+    if (kv->mega_epoch > 0xF0000000u) {                       // epochs are monotonic: restart well before wrap-around
+        HIPCHK(hipStreamSynchronize(st));
+        HIPCHK(hipMemset(kv->bar, 0, sizeof(MegaBar)));
+        kv->mega_epoch = 0;
+    }
+    a.epoch0 = kv->mega_epoch;
+    a.log_base = std::log((double)m->cfg.rope_base);
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIPCHK(hipFuncSetAttribute((const void*)mega_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv->mega_lds));
+        attr_set = true;
+    }
+    void* args[] = {&a};
+    HIPCHK(hipLaunchCooperativeKernel((const void*)mega_forward_kernel, dim3(m->num_cus), dim3(MEGA_THREADS), args,
+                                      kv->mega_lds, st));
+    kv->mega_epoch += nbar;
+    return SJ_OK;
+}
+
 template <typename T, int SPL>
 static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,
                             const void* hidden) {
     int rc;
+    if (!head_only && mega_eligible(m, kv, gamma, SPL)) {
+        if ((rc = set_params(kv, st, p))) return rc;
+        if ((rc = launch_mega(m, kv, gamma, st))) return rc;
+        Runner<T, SPL> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
+        softmax_merge_kernel<<<run.R, 256, 0, st>>>(kv->stats, m->md.V / 16, m->md.inv_temp, kv->rowstat);
+        LAUNCHCHK("softmax_merge");
+        return run.tail(gamma);
+    }
     const bool graph = kv->use_graph && !head_only && kv->timing_class == 0;
     if (!graph) {
         if ((rc = set_params(kv, st, p))) return rc;
