@@ -95,12 +95,13 @@ struct sj_kv {
     hipStream_t cap_stream = nullptr;
     bool use_graph = true;
     // persistent forward kernel (small row counts)
-    bool use_mega = true;
+    bool use_mega = false;     // slower than the launch-graph path so far: opt-in with SJ_MEGA=1
     bf16_t *Bx = nullptr, *Battn = nullptr, *Bact = nullptr;
     float *ssq = nullptr, *row_scale = nullptr;
     MegaBar* bar = nullptr;
     unsigned mega_epoch = 0;
     size_t mega_lds = 0;
+    unsigned long long* prof = nullptr;   // stage timestamps of the persistent kernel (timing class 9)
     int timing_class = 0;
     std::vector<hipEvent_t> tev;          // start/stop pairs
     size_t tev_used = 0;
@@ -307,7 +308,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     kv->m = m;
     kv->batch = batch;
     if (const char* e = std::getenv("SJ_NO_GRAPH")) kv->use_graph = !(e[0] == '1');
-    if (const char* e = std::getenv("SJ_NO_MEGA")) kv->use_mega = !(e[0] == '1');
+    if (const char* e = std::getenv("SJ_MEGA")) kv->use_mega = (e[0] == '1');
     kv->cap.assign(batch, 64);
     kv->len_upper.assign(batch, 0);
     kv->seq_off.assign(batch, 0);
@@ -393,6 +394,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
             ALLOC(kv->ssq, (size_t)MEGA_MAXR * (d / 16) * 4);
             ALLOC(kv->row_scale, (size_t)std::max(R, MEGA_MAXR) * 4);
             ALLOC(kv->bar, sizeof(MegaBar));
+            ALLOC(kv->prof, sizeof(unsigned long long) * 4096);
             kv->mega_lds = offsetof(MegaShared, red) + std::max(sizeof(AttnShared), sizeof(float) * 2 * MEGA_WAVES * 256);
         }
     }
@@ -448,7 +450,7 @@ extern "C" int sj_kv_rewind(sj_kv* kv, const int32_t* len_host, const int32_t* p
 
 extern "C" int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class) {
     if (!kv) return fail(SJ_EINVAL, "kv is null");
-    if (kernel_class < 0 || kernel_class > 4) return fail(SJ_EINVAL, "kernel_class must be 0..4");
+    if ((kernel_class < 0 || kernel_class > 4) && kernel_class != 9) return fail(SJ_EINVAL, "kernel_class must be 0..4 or 9");
     kv->timing_class = kernel_class;
     kv->tev_used = 0;
     return SJ_OK;
@@ -800,7 +802,9 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
 // The persistent forward kernel serves bf16 models when the whole batch fits 8 query rows.
 static bool mega_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl) {
     const sj_config& c = m->cfg;
-    if (!kv->use_mega || !m->coop || m->num_cus < 1 || c.dtype != SJ_DTYPE_BF16 || spl != 2 || kv->timing_class) return false;
+    if (!kv->use_mega || !m->coop || m->num_cus < 1 || c.dtype != SJ_DTYPE_BF16 || spl != 2) return false;
+    if (kv->timing_class != 0 && kv->timing_class != 9) return false;
+    if (c.n_layers * 10 + 8 > 4096) return false;
     const int R = kv->batch * (gamma + 1), G = c.n_q_heads / c.n_kv_heads;
     if (R > MEGA_MAXR || G * (gamma + 1) > 32 || c.head_dim != 128) return false;
     const int Nq = c.n_q_heads * c.head_dim;
@@ -822,6 +826,7 @@ static int launch_mega(sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
     a.x = kv->x; a.qkv = kv->part; a.Bx = kv->Bx; a.Battn = kv->Battn; a.Bact = kv->Bact; a.ssq = kv->ssq;
     a.hn32 = kv->hn32; a.row_scale = kv->row_scale; a.logits = kv->logits; a.stats = kv->stats; a.cs = kv->cs;
     a.bar = kv->bar;
+    a.prof = (kv->timing_class == 9) ? kv->prof : nullptr;
     const unsigned nbar = 1u + 5u * (unsigned)m->cfg.n_layers;
     if (kv->mega_epoch > 0xF0000000u) {                       // epochs are monotonic: restart well before wrap-around
         HIPCHK(hipStreamSynchronize(st));
@@ -1005,6 +1010,21 @@ extern "C" int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, siz
         case SJ_DBG_JUDGE_SCORES: src = kv->scores; want = (size_t)kv->batch * gamma * 4; break;
         case SJ_DBG_P_AT_DRAFT: src = kv->p_at_d; want = (size_t)kv->batch * gamma * 4; break;
         case SJ_DBG_ACCEPT_BITS: src = kv->bits; want = (size_t)kv->batch * gamma * 4; break;
+        case SJ_DBG_STAGE_TIMES: {
+            if (!kv->prof || kv->timing_class != 9) return fail(SJ_EINVAL, "stage times need timing class 9 and a step of the persistent kernel");
+            if (nbytes != 11 * sizeof(float)) return fail(SJ_EINVAL, "nbytes must be 44");
+            const int NL = kv->m->cfg.n_layers, n = 4 + 10 * NL;
+            std::vector<unsigned long long> t(n);
+            HIPCHK(hipDeviceSynchronize());
+            HIPCHK(hipMemcpy(t.data(), kv->prof, sizeof(unsigned long long) * n, hipMemcpyDeviceToHost));
+            double acc[11] = {0};
+            for (int l = 0; l < NL; ++l)
+                for (int i = 0; i < 10; ++i) acc[i] += (double)(t[3 + 10 * l + i] - t[2 + 10 * l + i]);
+            float* o = (float*)dst_host;
+            for (int i = 0; i < 10; ++i) o[i] = (float)(acc[i] / NL * 0.01);      // 100 MHz ticks -> microseconds
+            o[10] = (float)((double)(t[3 + 10 * NL] - t[2 + 10 * NL]) * 0.01);
+            return SJ_OK;
+        }
         default: return fail(SJ_EINVAL, "unknown debug item %d", what);
     }
     if (want == 0) return fail(SJ_EINVAL, "item not produced by the last call");

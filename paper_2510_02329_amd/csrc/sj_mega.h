@@ -68,6 +68,7 @@ struct MegaArgs {
     float* cs;                        // rotary table [R][hd/2][2]
     MegaBar* bar;
     unsigned epoch0;                  // barrier epochs of this launch start above this value
+    unsigned long long* prof;         // optional: timestamps (100 MHz) of workgroup 0 at every stage boundary
     double log_base;
 };
 
@@ -421,6 +422,9 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
     GridSync gs{a.bar, a.epoch0};
     Frag rw[MEGA_D], rb[MEGA_D];
     Stream st;
+    int prof_i = 0;
+    auto stamp = [&]() { if (a.prof && blockIdx.x == 0 && tid == 0) a.prof[prof_i] = wall_clock64(); ++prof_i; };
+    stamp();
 
     // stage 0: embedding rows -> residual, packed operand of the first QKV, sums of squares, rotary table
     {
@@ -457,10 +461,11 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
         }
     }
     st.init(a.layers[0].wqkv, Nqkv / 16, d / 32);
-    gs.arrive();
+    stamp(); gs.arrive();
     if (!lead) prefetch<MEGA_D>(st, rw);
     if (!gs.wait(sm)) return;
     if (lead) prefetch<MEGA_D>(st, rw);
+    stamp();
 
     for (int l = 0; l < a.NL; ++l) {
         const MegaLayer& Lw = a.layers[l];
@@ -470,24 +475,24 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
             if (valid) st_coh(&a.qkv[(size_t)r * Nqkv + tile * 16 + n], v * sm.inv_rms[r]);
         });
         st.init(Lw.wo, d / 16, Nq / 32);
-        gs.arrive();
+        stamp(); gs.arrive();
         // ---- attention (+ rotary, cache append) by the first nseq * Hkv workgroups.  The two kinds of
         // workgroup take separate paths so that the weight ring is not live across the attention code.
         const int n_attn = sp->nseq * md.Hkv;
         if ((int)blockIdx.x < n_attn) {
-            if (!gs.wait(sm)) return;
+            if (!gs.wait(sm)) return; stamp();
             for (int item = blockIdx.x; item < n_attn; item += gridDim.x)
                 attention_wg(a, (size_t)l * a.kv.layer_stride, item, as);
-            gs.arrive();
+            stamp(); gs.arrive();
             if (!lead) prefetch<MEGA_D>(st, rw);
-            if (!gs.wait(sm)) return;
+            if (!gs.wait(sm)) return; stamp();
             if (lead) prefetch<MEGA_D>(st, rw);
         } else {
             if (!lead) prefetch<MEGA_D>(st, rw);
-            if (!gs.wait(sm)) return;
+            if (!gs.wait(sm)) return; stamp();
             if (lead) prefetch<MEGA_D>(st, rw);
-            gs.arrive();
-            if (!gs.wait(sm)) return;
+            stamp(); gs.arrive();
+            if (!gs.wait(sm)) return; stamp();
         }
         // ---- O projection + residual; operand and sums of squares for the FFN norm
         gemm_stage<MEGA_D>(st, a.Battn, R, rw, rb, sm, [&](int tile, int r, int n, float v, bool valid) {
@@ -504,9 +509,9 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
             if (valid && n == 0) st_coh(&a.ssq[(size_t)r * ntx + tile], ss);
         });
         st.init(Lw.wgu, 2 * md.F / 16, d / 32);
-        gs.arrive();
+        stamp(); gs.arrive();
         if (!lead) prefetch<MEGA_D>(st, rw);
-        if (!gs.wait(sm)) return;
+        if (!gs.wait(sm)) return; stamp();
         if (lead) prefetch<MEGA_D>(st, rw);
         // ---- gate / up projection + SwiGLU -> operand of the down projection
         compute_inv_rms(a.ssq, ntx, R, d, md.eps, sm);
@@ -518,9 +523,9 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
             }
         });
         st.init(Lw.wd, d / 16, md.F / 32);
-        gs.arrive();
+        stamp(); gs.arrive();
         if (!lead) prefetch<MEGA_D / 2>(st, rw);
-        if (!gs.wait(sm)) return;
+        if (!gs.wait(sm)) return; stamp();
         if (lead) prefetch<MEGA_D / 2>(st, rw);
         // ---- down projection + residual; operand and sums of squares for the next norm
         const bool last = (l + 1 == a.NL);
@@ -542,9 +547,9 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
         });
         if (last) st.init(a.lm_head, md.V / 16, d / 32);
         else st.init(a.layers[l + 1].wqkv, Nqkv / 16, d / 32);
-        gs.arrive();
+        stamp(); gs.arrive();
         if (!lead) prefetch<MEGA_D>(st, rw);
-        if (!gs.wait(sm)) return;
+        if (!gs.wait(sm)) return; stamp();
         if (lead) prefetch<MEGA_D>(st, rw);
     }
     // ---- LM head: logits and per-tile softmax partials (Eq. 2's p, merged by the tail kernels)
@@ -578,6 +583,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
             if (n == 0) a.stats[(size_t)r * ntv + tile] = float4{mx, se, __int_as_float(arg), 0.f};
         }
     });
+    stamp();
 }
 
 }  // namespace sj

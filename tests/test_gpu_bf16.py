@@ -131,8 +131,7 @@ def test_persistent_kernel_matches_oracle_and_multikernel_path(batch, gamma, len
     W = helpers.oracle_weights(src, cache_items=0)
     outs = {}
     for mode in ("mega", "multi"):
-        if mode == "multi":
-            monkeypatch.setenv("SJ_NO_MEGA", "1")
+        monkeypatch.setenv("SJ_MEGA", "1" if mode == "mega" else "0")
         gpu = G.Gpu(shape, src, cap)
         try:
             caches = _fill_caches(shape, gpu, cfg, lens, seed=4, capacity=cap)
