@@ -395,7 +395,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
             ALLOC(kv->row_scale, (size_t)std::max(R, MEGA_MAXR) * 4);
             ALLOC(kv->bar, sizeof(MegaBar));
             ALLOC(kv->prof, sizeof(unsigned long long) * 4096);
-            kv->mega_lds = offsetof(MegaShared, red) + std::max(sizeof(AttnShared), sizeof(float) * 2 * MEGA_WAVES * 256);
+            kv->mega_lds = sizeof(MegaShared) + 1024;      // + slack for the 1 KB alignment of the staging area
         }
     }
 #undef ALLOC
@@ -808,8 +808,10 @@ static bool mega_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl
     const int R = kv->batch * (gamma + 1), G = c.n_q_heads / c.n_kv_heads;
     if (R > MEGA_MAXR || G * (gamma + 1) > 32 || c.head_dim != 128) return false;
     const int Nq = c.n_q_heads * c.head_dim;
-    auto ok = [](int K, int D) { return K % (32 * MEGA_WAVES) == 0 && (K / 32 / MEGA_WAVES) % D == 0; };
-    return ok(c.d_model, MEGA_D) && ok(Nq, MEGA_D) && ok(c.d_ffn, MEGA_D / 2) && m->num_cus <= 1024;
+    auto ok = [](int K, int D) { return K % (32 * MEGA_SW) == 0 && (K / 32 / MEGA_SW) % D == 0; };
+    // K of the LDS-staged operands is bounded by the staging area (1 KB per k-step)
+    return ok(c.d_model, MEGA_D) && ok(Nq, MEGA_D) && ok(c.d_ffn, 8) && c.d_model / 32 * 1024 <= MEGA_BIG &&
+           Nq / 32 * 1024 <= MEGA_BIG && m->num_cus <= 1024;
 }
 
 static int launch_mega(sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
