@@ -117,6 +117,9 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalid as a result)")
     ap.add_argument("--planes", type=int, default=0, help="bf16 operand planes (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     ap.add_argument("--theta", type=float, default=0.5)
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
@@ -169,6 +172,12 @@ def main() -> int:
         sj.sj_kv_rewind(kv, lens.tolist(), pend.tolist(), stream)
         sj.sj_verify_step(model, kv, gamma, dt, dp, un, args.theta, acc, nxt, stream)
 
+    if args.calibrate_copy:
+        src_c = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst_c = torch.empty_like(src_c)
+        torch.mul(src_c, 1.0, out=dst_c)           # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src_c, dst_c
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()

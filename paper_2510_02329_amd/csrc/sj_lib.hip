@@ -805,8 +805,8 @@ static bool mega_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl
     if (!kv->use_mega || !m->coop || m->num_cus < 1 || c.dtype != SJ_DTYPE_BF16 || spl != 2) return false;
     if (kv->timing_class != 0 && kv->timing_class != 9) return false;
     if (c.n_layers * 10 + 8 > 4096) return false;
-    const int R = kv->batch * (gamma + 1), G = c.n_q_heads / c.n_kv_heads;
-    if (R > MEGA_MAXR || G * (gamma + 1) > 32 || c.head_dim != 128) return false;
+    const int R = kv->batch * (gamma + 1);
+    if (R > MEGA_MAXR || c.head_dim != 128) return false;
     const int Nq = c.n_q_heads * c.head_dim;
     auto ok = [](int K, int D) { return K % (32 * MEGA_SW) == 0 && (K / 32 / MEGA_SW) % D == 0; };
     // K of the LDS-staged operands is bounded by the staging area (1 KB per k-step)

@@ -110,8 +110,10 @@ __device__ __forceinline__ void store_packed_row16(bf16_t* B, int r, int k, int 
 }
 
 struct AttnShared {
-    bf16_t q[2][32][128];             // rotated queries, hi / lo planes, row m = head * rps + j
-    float o[MEGA_SW][16][128];        // per-wave unnormalised outputs of its 16 query rows
+    bf16_t q[2][16][128];             // rotated queries of one head, hi / lo planes, row = block row j
+    bf16_t knew[32][128];             // rotated keys of the block's own rows, as the cache stores them
+    bf16_t vnewT[128][32];            // values of the block's own rows, transposed
+    float o[MEGA_SW][16][128];        // per-wave unnormalised outputs
     float2 ml[MEGA_SW][16];           // per-wave running max and sum
 };
 
@@ -294,83 +296,83 @@ __device__ __forceinline__ void compute_inv_rms(const float* __restrict__ ssq, i
     }
 }
 
-// ---- attention of one (sequence, kv head) by the 8 streaming waves of one workgroup ---------------
-// Wave w owns query tile w % MT (16 rows of M = G * rps, MT = 1 or 2) and every (8 / MT)-th step of
-// 32 keys.  The service wave only takes part in the three workgroup barriers.
-__device__ __forceinline__ void attention_wg(const MegaArgs& a, size_t layer_off, int item, AttnShared& as) {
+// ---- attention of one (sequence, query head) by the 8 streaming waves of one workgroup -------------
+// The rps block rows of the head are one MFMA query tile.  Cached keys 0..L-1 are read from the cache in
+// steps of 32, wave w taking steps w, w+8, ...; the block's own keys (positions L..L+rps-1) are rotated
+// here, kept in LDS in the cache's storage format and handled as one more step, so that no workgroup
+// has to wait for another one's cache append.  The workgroup of a kv head's first query head also
+// writes the new K / V rows to the cache.  The service wave only takes part in the barriers.
+__device__ __noinline__ void attention_wg(const MegaArgs& a, size_t layer_off, int item, AttnShared& as) {
     constexpr int HD = 128, KSTEP = 32, KF = 8, KK = HD / KSTEP, HT = HD / 16;
     const ModelDims& md = a.md;
     const StepParams* sp = a.sp;
     const int rps = sp->rps;
-    const int bi = item / md.Hkv, kvh = item % md.Hkv;
+    const int bi = item / md.Hq, qh = item % md.Hq, kvh = qh / md.G;
+    const bool writer = (qh % md.G) == 0;
     const int b = sp->seq_base + bi;
     const int L = a.kv.len[b], cap = a.kv.cap[b];
-    const int M = md.G * rps, MT = (M + 15) / 16, NSL = MEGA_SW / MT;
     const int Nq = md.Hq * HD, Nk = md.Hkv * HD, Nqkv = Nq + 2 * Nk;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 15, g = lane >> 4;
     constexpr int NT = MEGA_SW * 64;
     bf16_t* Kb = a.kv.K + layer_off + a.kv.seq_off[b] + (size_t)kvh * cap * HD;
     bf16_t* Vb = a.kv.V + layer_off + a.kv.seq_off[b] + (size_t)kvh * HD * cap;
 
-    // rotary on q (G heads) and k (this kv head) of every block row; q -> LDS planes, k / v -> cache
-    for (int p = tid; p < 2 * 32 * 128 / 2; p += NT) reinterpret_cast<uint32_t*>(&as.q[0][0][0])[p] = 0u;
+    // zero the padding of the LDS operands (q, knew, vnewT are contiguous: 24 KB)
+    for (int p = tid; p < (int)((sizeof(as.q) + sizeof(as.knew) + sizeof(as.vnewT)) / 4); p += NT)
+        reinterpret_cast<uint32_t*>(&as.q[0][0][0])[p] = 0u;
     lds_barrier();
     const int half = HD / 2;
-    for (int p = tid; p < (md.G + 1) * rps * half; p += NT) {
-        const int i = p % half, j = (p / half) % rps, hh = p / (half * rps);
-        const int row = bi * rps + j;
-        const float c = a.cs[((size_t)row * half + i) * 2], s = a.cs[((size_t)row * half + i) * 2 + 1];
-        const int col = (hh < md.G) ? (kvh * md.G + hh) * HD + i : Nq + kvh * HD + i;
-        const float lo = a.qkv[(size_t)row * Nqkv + col], hi = a.qkv[(size_t)row * Nqkv + col + half];
-        const float olo = lo * c - hi * s, ohi = hi * c + lo * s;
-        if (hh < md.G) {
-            const int m = hh * rps + j;
+    // rotary pairs of q (work items 0 .. rps*64-1) and k (rps*64 .. 2*rps*64-1), then the values
+    for (int p = tid; p < 2 * rps * half + rps * HD; p += NT) {
+        if (p < 2 * rps * half) {
+            const int i = p % half, j = (p / half) % rps, isk = p / (half * rps);
+            const int row = bi * rps + j;
+            const float c = a.cs[((size_t)row * half + i) * 2], s = a.cs[((size_t)row * half + i) * 2 + 1];
+            const int col = isk ? Nq + kvh * HD + i : qh * HD + i;
+            const float lo = a.qkv[(size_t)row * Nqkv + col], hi = a.qkv[(size_t)row * Nqkv + col + half];
+            const float olo = lo * c - hi * s, ohi = hi * c + lo * s;
             const bf16_t h0 = f32_to_bf16(olo), h1 = f32_to_bf16(ohi);
-            as.q[0][m][i] = h0; as.q[0][m][i + half] = h1;
-            as.q[1][m][i] = f32_to_bf16(olo - bf16_to_f32(h0));
-            as.q[1][m][i + half] = f32_to_bf16(ohi - bf16_to_f32(h1));
-        } else if (L + j < cap) {
-            bf16_t* k = Kb + (size_t)(L + j) * HD;
-            k[i] = f32_to_bf16(olo);
-            k[i + half] = f32_to_bf16(ohi);
+            if (!isk) {
+                as.q[0][j][i] = h0; as.q[0][j][i + half] = h1;
+                as.q[1][j][i] = f32_to_bf16(olo - bf16_to_f32(h0));
+                as.q[1][j][i + half] = f32_to_bf16(ohi - bf16_to_f32(h1));
+            } else {
+                as.knew[j][i] = h0; as.knew[j][i + half] = h1;
+                if (writer && L + j < cap) {
+                    bf16_t* k = Kb + (size_t)(L + j) * HD;
+                    k[i] = h0; k[i + half] = h1;
+                }
+            }
+        } else {
+            const int e = p - 2 * rps * half, j = e / HD, dcol = e % HD;
+            const bf16_t v = f32_to_bf16(a.qkv[(size_t)(bi * rps + j) * Nqkv + Nq + Nk + kvh * HD + dcol]);
+            as.vnewT[dcol][j] = v;
+            if (writer && L + j < cap) Vb[(size_t)dcol * cap + L + j] = v;
         }
     }
-    for (int e = tid; e < rps * HD; e += NT) {
-        const int j = e / HD, dcol = e % HD;
-        if (L + j < cap) Vb[(size_t)dcol * cap + L + j] = f32_to_bf16(a.qkv[(size_t)(bi * rps + j) * Nqkv + Nq + Nk + kvh * HD + dcol]);
-    }
-    wait_vm0();
-    lds_barrier();        // the new rows are stored; this workgroup's own loads below will see them
+    lds_barrier();
 
-    const int kv_end = min(L + rps, cap);
-    const int mq = w % MT, slice = w / MT;
     f32x4 o[HT];
     float m_run = -INFINITY, l_run = 0.f;
-    const int mrow = mq * 16 + r;
-    const int limit = (mrow < M) ? L + (mrow % rps) : -1;
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) o[ht] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int key0 = slice * KSTEP; key0 < kv_end; key0 += NSL * KSTEP) {
+    const int nsteps = (L + KSTEP - 1) / KSTEP;                  // steps over the cached keys
+    // one step: K rows (two S^T tiles), V^T rows, online softmax, PV.  `limit` = last visible key index
+    // relative to key0 semantics below; cached steps see keys < L, the block step sees jj <= j.
+    auto step = [&](const Frag (&kf)[2][KK], const Frag (&vf)[HT], int key0, int limit) {
         f32x4 s[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const int krow = key0 + KF * (r >> 2) + 4 * t + (r & 3);
-            Frag kf[KK];
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) kf[kk].u = *reinterpret_cast<const u32x4*>(Kb + (size_t)krow * HD + kk * KSTEP + g * KF);
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
                 for (int pl = 0; pl < 2; ++pl) {
                     Frag qf;
-                    qf.u = *reinterpret_cast<const u32x4*>(&as.q[pl][mrow][kk * KSTEP + g * KF]);
-                    s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk].h, qf.h, s[t], 0, 0, 0);
+                    qf.u = *reinterpret_cast<const u32x4*>(&as.q[pl][r][kk * KSTEP + g * KF]);
+                    s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][kk].h, qf.h, s[t], 0, 0, 0);
                 }
         }
-        Frag vf[HT];
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht) vf[ht].u = *reinterpret_cast<const u32x4*>(Vb + (size_t)(ht * 16 + r) * cap + key0 + g * KF);
         Frag pf[2];
         float mx = -INFINITY;
 #pragma unroll
@@ -404,6 +406,32 @@ __device__ __forceinline__ void attention_wg(const MegaArgs& a, size_t layer_off
 #pragma unroll
             for (int pl = 0; pl < 2; ++pl) o[ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[ht].h, pf[pl].h, o[ht], 0, 0, 0);
         }
+    };
+    for (int st = w; st < nsteps; st += MEGA_SW) {
+        const int key0 = st * KSTEP;
+        Frag kf[2][KK], vf[HT];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int krow = key0 + KF * (r >> 2) + 4 * t + (r & 3);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *reinterpret_cast<const u32x4*>(Kb + (size_t)krow * HD + kk * KSTEP + g * KF);
+        }
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) vf[ht].u = *reinterpret_cast<const u32x4*>(Vb + (size_t)(ht * 16 + r) * cap + key0 + g * KF);
+        step(kf, vf, key0, (r < rps) ? L - 1 : -1);
+    }
+    if (w == nsteps % MEGA_SW) {
+        // the block's own keys: key index jj = 0..31 (rows >= rps are zero padding), row j sees jj <= j
+        Frag kf[2][KK], vf[HT];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int krow = KF * (r >> 2) + 4 * t + (r & 3);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *reinterpret_cast<const u32x4*>(&as.knew[krow][kk * KSTEP + g * KF]);
+        }
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) vf[ht].u = *reinterpret_cast<const u32x4*>(&as.vnewT[ht * 16 + r][g * KF]);
+        step(kf, vf, 0, (r < rps) ? r : -1);
     }
     {
         float l = l_run;
@@ -416,24 +444,23 @@ __device__ __forceinline__ void attention_wg(const MegaArgs& a, size_t layer_off
             for (int i = 0; i < 4; ++i) as.o[w][r][ht * 16 + 4 * g + i] = o[ht][i];
     }
     lds_barrier();
-    // merge the key slices (fixed order) and write the O-projection operand; each 16-lane group holds
-    // 16 neighbouring columns of one row
-    for (int e = tid; e < MT * 16 * HD; e += NT) {
-        const int m = e / HD, dcol = e % HD;
-        const int tq = m / 16, rr = m % 16;
+    // merge the waves (fixed order) and write this head's columns of the O-projection operand; each
+    // 16-lane group holds 16 neighbouring columns of one row
+    for (int e = tid; e < 16 * HD; e += NT) {
+        const int j = e / HD, dcol = e % HD;
         float mx = -INFINITY;
-        for (int sl = 0; sl < NSL; ++sl) mx = fmaxf(mx, as.ml[sl * MT + tq][rr].x);
+#pragma unroll
+        for (int ww = 0; ww < MEGA_SW; ++ww) mx = fmaxf(mx, as.ml[ww][j].x);
         float den = 0.f, num = 0.f;
-        for (int sl = 0; sl < NSL; ++sl) {
-            const float2 ml = as.ml[sl * MT + tq][rr];
+#pragma unroll
+        for (int ww = 0; ww < MEGA_SW; ++ww) {
+            const float2 ml = as.ml[ww][j];
             const float wgt = (ml.x == -INFINITY) ? 0.f : expf(ml.x - mx);
             den += wgt * ml.y;
-            if (wgt != 0.f) num += wgt * as.o[sl * MT + tq][rr][dcol];
+            if (wgt != 0.f) num += wgt * as.o[ww][j][dcol];
         }
-        const bool valid = m < M;
-        const int mm = valid ? m : 0;
-        const int gi = mm / rps, j = mm % rps;
-        store_packed_row16(a.Battn, bi * rps + j, (kvh * md.G + gi) * HD + dcol, dcol & 15, valid ? num / den : 0.f, valid);
+        const bool valid = j < rps;
+        store_packed_row16(a.Battn, valid ? bi * rps + j : 0, qh * HD + dcol, dcol & 15, valid ? num / den : 0.f, valid);
     }
     wait_vm0();
 }
@@ -450,7 +477,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
     const int Nq = md.Hq * md.hd, Nk = md.Hkv * md.hd, Nqkv = Nq + 2 * Nk;
     const int ntx = d / 16, ntv = md.V / 16;
     const bool service = tid >= MEGA_SW * 64;
-    const int n_attn = sp->nseq * md.Hkv;
+    const int n_attn = sp->nseq * md.Hq;                  // one workgroup per (sequence, query head)
     const bool has_attn = (int)blockIdx.x < n_attn;
     const int KWd = md.F / 32 / MEGA_SW;                  // k-steps per wave of the down projection
 
@@ -516,7 +543,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void mega_forward_kernel(MegaArgs a) 
             stamp();
             if (!gs.sync()) { leave(); return; }
             stamp();
-            // ---- attention: the streaming waves of the first nseq * Hkv workgroups
+            // ---- attention: the streaming waves of the first nseq * Hq workgroups
             if (has_attn) {
                 for (int item = blockIdx.x; item < n_attn; item += gridDim.x) {
                     // release + the three barriers inside the attention + its end

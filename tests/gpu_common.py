@@ -21,7 +21,11 @@ def sj_config(shape: synth.ModelShape, max_gamma: int | None = None) -> sj.SJCon
 
 
 def load_model(shape: synth.ModelShape, src: synth.WeightSource, max_gamma: int | None = None) -> int:
-    return sj.sj_model_load(sj_config(shape, max_gamma), lambda name, layer: src.tensor(name, layer))
+    def provider(name, layer):
+        if name == "wq" and layer % 8 == 0 and shape.n_layers > 40:
+            print(f"  loading layer {layer}/{shape.n_layers}", flush=True)       # long loads must show progress
+        return src.tensor(name, layer)
+    return sj.sj_model_load(sj_config(shape, max_gamma), provider)
 
 
 class Gpu:
@@ -109,3 +113,46 @@ def replay_matches(shape, gpu_out, draft, theta, mode="two_stage"):
         if not ok:
             bad.append((b, res["accepted_len"], int(gpu_out["accepted_len"][b]), res["next_token"], int(gpu_out["next_token"][b])))
     return bad, excused
+
+
+class ForcedRows(np.ndarray):
+    """Cache array of the oracle whose appended rows take the DEVICE's storage-rounding decision.
+
+    Rounding a new K/V row to bf16 is a quantisation decision taken on a value the two sides know to
+    ~1e-6 relative; near a rounding boundary they pick different neighbours, and an 80-layer random
+    decoder amplifies each such one-ulp difference into the logit tolerance.  Per the decision-margin
+    rule both sides must take the decision on the same value: the oracle computes its own rounded row,
+    the test checks that the device's stored row is the same or the adjacent representable value, and
+    the device's row is what the oracle stores.  Everything downstream is then compared as usual."""
+    forced = None      # [n_kv_heads, n_rows, hd] float64 rows read back from the device
+    first = 0          # cache position of forced[:, 0]
+    stats = None       # shared dict: {"rows": n, "flips": n}
+
+    def __setitem__(self, key, value):
+        if self.forced is not None and isinstance(key, tuple) and len(key) == 3 and isinstance(key[1], (int, np.integer)):
+            pos = int(key[1])
+            dev = self.forced[:, pos - self.first, :]
+            mine = np.asarray(value, np.float64)
+            # the device's stored value must be the oracle's value up to one storage ulp plus the
+            # numeric tolerance of the quantity itself (small elements of a row differ by more than
+            # their own ulp once upstream rounding differs)
+            a_tol, r_tol = TOL["bf16"]
+            bound = np.maximum(np.abs(mine), np.abs(dev)) * 2.0 ** -7 + 0.1 * (a_tol + r_tol * np.abs(mine))
+            assert (np.abs(dev - mine) <= bound).all(), "stored K/V row is not the oracle's row within a storage ulp"
+            if self.stats is not None:
+                self.stats["rows"] += mine.size
+                self.stats["flips"] += int((dev != mine).sum())
+            value = dev
+        super().__setitem__(key, value)
+
+
+def force_device_rounding(gpu, caches, gamma, stats):
+    """After a device step: make the oracle caches adopt the device's stored rows of the block."""
+    shape = gpu.shape
+    for b, c in enumerate(caches):
+        for l in range(shape.n_layers):
+            k, v = gpu.kv_rows(b, l, c.length, gamma + 1)
+            for arr_list, dev in ((c.k, k), (c.v, v)):
+                fr = arr_list[l].view(ForcedRows)
+                fr.forced, fr.first, fr.stats = dev, c.length, stats
+                arr_list[l] = fr

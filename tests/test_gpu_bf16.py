@@ -28,11 +28,17 @@ def _fill_caches(shape, gpu, cfg, lens, seed, capacity):
     return caches
 
 
-def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label):
+def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label, force_rounding=False):
     B, gamma = draft["tokens"].shape
     L0 = [c.length for c in caches]
     out = gpu.step(draft, theta, gamma)
+    flips = {"rows": 0, "flips": 0}
+    if force_rounding:
+        G.force_device_rounding(gpu, caches, gamma, flips)
     ref = orc.verify_step(cfg, W, caches, draft["tokens"], draft["probs"], draft["uniforms"], theta)
+    if force_rounding:
+        print(f"{label}: {flips['flips']} of {flips['rows']} stored K/V elements took the other bf16 neighbour", flush=True)
+        assert flips["flips"] < 0.10 * flips["rows"]
     stats = {}
     for b in range(B):
         stats["logits"] = G.close_enough(out["logits"][b], ref[b]["logits"], shape.dtype, f"{label} logits seq {b}")
