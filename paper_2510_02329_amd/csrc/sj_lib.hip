@@ -1014,6 +1014,15 @@ extern "C" int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, siz
         case SJ_DBG_ACCEPT_BITS: src = kv->bits; want = (size_t)kv->batch * gamma * 4; break;
         case SJ_DBG_STAGE_TIMES: {
             if (!kv->prof || kv->timing_class != 9) return fail(SJ_EINVAL, "stage times need timing class 9 and a step of the persistent kernel");
+            if (nbytes == 8 * sizeof(float)) {           // inner stamps of the attention stage (workgroup 0, last layer)
+                unsigned long long t8[8];
+                HIPCHK(hipDeviceSynchronize());
+                HIPCHK(hipMemcpy(t8, kv->prof + 3000, sizeof t8, hipMemcpyDeviceToHost));
+                float* o8 = (float*)dst_host;
+                o8[0] = 0.f;
+                for (int i = 1; i < 8; ++i) o8[i] = (float)((double)(t8[i] - t8[0]) * 0.01);
+                return SJ_OK;
+            }
             if (nbytes != 11 * sizeof(float)) return fail(SJ_EINVAL, "nbytes must be 44");
             const int NL = kv->m->cfg.n_layers, n = 4 + 10 * NL;
             std::vector<unsigned long long> t(n);

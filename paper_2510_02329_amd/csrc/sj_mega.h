@@ -317,6 +317,8 @@ __device__ __noinline__ void attention_wg(const MegaArgs& a, size_t layer_off, i
     bf16_t* Kb = a.kv.K + layer_off + a.kv.seq_off[b] + (size_t)kvh * cap * HD;
     bf16_t* Vb = a.kv.V + layer_off + a.kv.seq_off[b] + (size_t)kvh * HD * cap;
 
+    auto astamp = [&](int i) { if (a.prof && blockIdx.x == 0 && tid == 0) a.prof[3000 + i] = wall_clock64(); };
+    astamp(0);
     // zero the padding of the LDS operands (q, knew, vnewT are contiguous: 24 KB)
     for (int p = tid; p < (int)((sizeof(as.q) + sizeof(as.knew) + sizeof(as.vnewT)) / 4); p += NT)
         reinterpret_cast<uint32_t*>(&as.q[0][0][0])[p] = 0u;
@@ -350,7 +352,9 @@ __device__ __noinline__ void attention_wg(const MegaArgs& a, size_t layer_off, i
             if (writer && L + j < cap) Vb[(size_t)dcol * cap + L + j] = v;
         }
     }
+    astamp(1);
     lds_barrier();
+    astamp(2);
 
     f32x4 o[HT];
     float m_run = -INFINITY, l_run = 0.f;
@@ -420,6 +424,7 @@ __device__ __noinline__ void attention_wg(const MegaArgs& a, size_t layer_off, i
         for (int ht = 0; ht < HT; ++ht) vf[ht].u = *reinterpret_cast<const u32x4*>(Vb + (size_t)(ht * 16 + r) * cap + key0 + g * KF);
         step(kf, vf, key0, (r < rps) ? L - 1 : -1);
     }
+    astamp(3);
     if (w == nsteps % MEGA_SW) {
         // the block's own keys: key index jj = 0..31 (rows >= rps are zero padding), row j sees jj <= j
         Frag kf[2][KK], vf[HT];
@@ -443,10 +448,12 @@ __device__ __noinline__ void attention_wg(const MegaArgs& a, size_t layer_off, i
 #pragma unroll
             for (int i = 0; i < 4; ++i) as.o[w][r][ht * 16 + 4 * g + i] = o[ht][i];
     }
+    astamp(4);
     lds_barrier();
+    astamp(5);
     // merge the waves (fixed order) and write this head's columns of the O-projection operand; each
     // 16-lane group holds 16 neighbouring columns of one row
-    for (int e = tid; e < 16 * HD; e += NT) {
+    for (int e = tid; e < rps * HD; e += NT) {
         const int j = e / HD, dcol = e % HD;
         float mx = -INFINITY;
 #pragma unroll
@@ -462,7 +469,9 @@ __device__ __noinline__ void attention_wg(const MegaArgs& a, size_t layer_off, i
         const bool valid = j < rps;
         store_packed_row16(a.Battn, valid ? bi * rps + j : 0, qh * HD + dcol, dcol & 15, valid ? num / den : 0.f, valid);
     }
+    astamp(6);
     wait_vm0();
+    astamp(7);
 }
 
 // ---- the kernel -----------------------------------------------------------------------------------
