@@ -166,6 +166,10 @@ int sj_kv_rewind(sj_kv* kv, const int32_t* len_host, const int32_t* pending_host
  * persistent kernel record stage timestamps (read with SJ_DBG_STAGE_TIMES).  sj_get_kernel_timing synchronises, returns
  * the summed duration and launch count since the last call, and clears them.  0 switches it off. */
 int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class);
+/* Launches the projection kernel of class 1..4 `launches` times back to back on `stream`, cycling through
+ * the layers' weights (so nothing is re-read from cache) with the operands left by the last step, and
+ * returns the elapsed time between two HIP events around the whole series.  Synchronises `stream`. */
+int sj_time_kernel_class(sj_model* m, sj_kv* kv, int32_t kernel_class, int32_t launches, void* stream, double* total_ms);
 int sj_get_kernel_timing(sj_kv* kv, double* total_ms, int64_t* launches);
 
 /* bf16 models only: how many bf16 planes carry the fp32 activations (the few-row operand of every

@@ -70,6 +70,7 @@ def load_library() -> C.CDLL:
         "sj_kv_rewind": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
         "sj_set_kernel_timing": (C.c_int, [vp, i32]),
         "sj_get_kernel_timing": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+        "sj_time_kernel_class": (C.c_int, [vp, vp, i32, i32, vp, C.POINTER(C.c_double)]),
         "sj_debug_fetch": (C.c_int, [vp, i32, vp, sz]),
         "sj_last_error": (C.c_char_p, []),
         "sj_version": (C.c_char_p, []),
@@ -218,6 +219,12 @@ def sj_get_kernel_timing(kv: int):
     ms, n = C.c_double(), C.c_int64()
     _check(load_library().sj_get_kernel_timing(kv, C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def sj_time_kernel_class(model: int, kv: int, kernel_class: int, launches: int, stream=None) -> float:
+    ms = C.c_double()
+    _check(load_library().sj_time_kernel_class(model, kv, kernel_class, launches, _stream(stream), C.byref(ms)))
+    return ms.value
 
 
 def sj_set_operand_planes(kv: int, planes: int) -> None:

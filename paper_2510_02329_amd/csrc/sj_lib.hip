@@ -736,8 +736,8 @@ struct Runner {
     }
 
     // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max))
-    int lm_head(bool exact_operand) {
-        constexpr int LMNT = 4;          // same tile grouping for every row-tile count (statistics layout)
+    template <int LMNT>
+    int lm_head_nt(bool exact_operand) {
         const ModelDims& md = m->md;
         // hidden states handed in by the caller are already in the storage dtype: one plane suffices
         int rc = exact_operand
@@ -749,6 +749,9 @@ struct Runner {
         LAUNCHCHK("softmax_merge");
         return SJ_OK;
     }
+    // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max)).  One row
+    // tile: 8 n-tiles per workgroup; more rows: 4 (the statistics layout must be the same for every row group)
+    int lm_head(bool exact_operand) { return R <= 16 ? lm_head_nt<8>(exact_operand) : lm_head_nt<4>(exact_operand); }
 
     // Eq. 3, Eq. 5, scan, extra token, state commit
     int tail(int gamma, const float* row_scale = nullptr) {
@@ -895,6 +898,50 @@ static int dispatch_step(sj_model* m, sj_kv* kv, int gamma, const StepParams& p,
         case 3: return verify_step_impl<bf16_t, 3>(m, kv, gamma, p, st, head_only, hidden);
         default: return verify_step_impl<bf16_t, 2>(m, kv, gamma, p, st, head_only, hidden);
     }
+}
+
+template <typename T, int SPL>
+static int time_kernel_impl(sj_model* m, sj_kv* kv, int cls, int launches, int gamma, hipStream_t st, double* total_ms) {
+    Runner<T, SPL> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
+    const ModelDims& md = m->md;
+    const int d = md.d, Nq = md.Hq * md.hd, Nk = md.Hkv * md.hd;
+    hipEvent_t e0, e1;
+    HIPCHK(hipEventCreate(&e0));
+    HIPCHK(hipEventCreate(&e1));
+    int rc = SJ_OK;
+    HIPCHK(hipEventRecord(e0, st));
+    for (int i = 0; i < launches && !rc; ++i) {
+        const LayerW& L = m->layers[i % m->cfg.n_layers];        // a different layer each time: no cache reuse
+        switch (cls) {
+            case 1: rc = run.partial_gemm(L.wqkv, kv->xn, d, d, Nq + 2 * Nk, kv->split_qkv); break;
+            case 2: rc = run.partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->split_o); break;
+            case 3: rc = gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, L.wgu, kv->xn, run.plane(d), d, d, 2 * md.F, run.R, 1, nullptr, kv->act,
+                                                        run.plane(md.F), nullptr, 0.f); break;
+            default: rc = run.partial_gemm(L.wd, kv->act, md.F, md.F, d, kv->split_d); break;
+        }
+    }
+    hipError_t e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    if (e != hipSuccess) return fail(SJ_EHIP, "kernel timing failed: %s", hipGetErrorString(e));
+    *total_ms = ms;
+    return SJ_OK;
+}
+
+extern "C" int sj_time_kernel_class(sj_model* m, sj_kv* kv, int32_t kernel_class, int32_t launches, void* stream, double* total_ms) {
+    if (!m || !kv || !total_ms) return fail(SJ_EINVAL, "null argument");
+    if (kv->m != m || m->cfg.n_layers == 0) return fail(SJ_EINVAL, "needs a decoder model and its kv");
+    if (kernel_class < 1 || kernel_class > 4 || launches < 1) return fail(SJ_EINVAL, "kernel_class must be 1..4, launches >= 1");
+    if (kv->last_gamma < 1) return fail(SJ_EINVAL, "run a verification step first (the operands of the last step are reused)");
+    hipStream_t st = (hipStream_t)stream;
+    if (m->cfg.dtype == SJ_DTYPE_FP32) return time_kernel_impl<float, 1>(m, kv, kernel_class, launches, kv->last_gamma, st, total_ms);
+    if (kv->planes == 1) return time_kernel_impl<bf16_t, 1>(m, kv, kernel_class, launches, kv->last_gamma, st, total_ms);
+    if (kv->planes == 3) return time_kernel_impl<bf16_t, 3>(m, kv, kernel_class, launches, kv->last_gamma, st, total_ms);
+    return time_kernel_impl<bf16_t, 2>(m, kv, kernel_class, launches, kv->last_gamma, st, total_ms);
 }
 
 static int check_step_args(sj_model* m, sj_kv* kv, int gamma, const void* a, const void* b, const void* c, const void* d,
