@@ -57,6 +57,10 @@ template <> struct Traits<float> {
     static __device__ __forceinline__ void pack(Frag& f, int j, float v) { f.f[j] = v; }
     template <int SPL> static __device__ __forceinline__ void pack_split(Frag* f, int j, float v) { f[0].f[j] = v; }
     static __device__ __forceinline__ void store_split(float* p, size_t, float v) { *p = v; }
+    // four neighbouring values (p 16-byte aligned)
+    static __device__ __forceinline__ void store_split4(float* p, size_t, const float (&v)[4]) {
+        *reinterpret_cast<float4*>(p) = float4{v[0], v[1], v[2], v[3]};
+    }
 };
 
 template <> struct Traits<bf16_t> {
@@ -87,6 +91,21 @@ template <> struct Traits<bf16_t> {
         p[0] = h;
         p[plane] = m;
         p[2 * plane] = f32_to_bf16(r1 - bf16_to_f32(m));
+    }
+    // four neighbouring values (p 8-byte aligned): one 8-byte store per plane
+    static __device__ __forceinline__ void store_split4(bf16_t* p, size_t plane, const float (&v)[4]) {
+        bf16_t h[4], m[4], l[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            h[i] = f32_to_bf16(v[i]);
+            const float r1 = v[i] - bf16_to_f32(h[i]);
+            m[i] = f32_to_bf16(r1);
+            l[i] = f32_to_bf16(r1 - bf16_to_f32(m[i]));
+        }
+        auto pack = [](const bf16_t (&x)[4]) { return uint2{(uint32_t)x[0] | ((uint32_t)x[1] << 16), (uint32_t)x[2] | ((uint32_t)x[3] << 16)}; };
+        *reinterpret_cast<uint2*>(p) = pack(h);
+        *reinterpret_cast<uint2*>(p + plane) = pack(m);
+        *reinterpret_cast<uint2*>(p + 2 * plane) = pack(l);
     }
 };
 
@@ -123,5 +142,14 @@ __device__ __forceinline__ double block_sum_256(double v, double* lds4) {
     __syncthreads();
     return (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
 }
+
+// ---- coherent accessors (agent scope: write-through / cache-bypassing single accesses) ----------
+__device__ __forceinline__ void st_coh(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_coh(unsigned* p, unsigned v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_coh(unsigned long long* p, unsigned long long v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ unsigned ld_coh(const unsigned* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_coh(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+__device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 }  // namespace sj

@@ -365,246 +365,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Rotary + KV append (one workgroup per query row).  Sums the QKV partials, rotates q and k to the
-// row's position, writes q for attention as [seq][kv head][m = gi*rps + j][hd] and appends k / v to
-// the cache at position len + j (v transposed).  A row whose position would fall outside the
-// sequence's capacity writes nothing (the host refuses such calls before launching).
-template <typename T>
-__global__ __launch_bounds__(512) void rope_append_kernel(const StepParams* __restrict__ sp, ModelDims md,
-                                                          const float* __restrict__ part, int nparts, int R,
-                                                          const float* __restrict__ cs, T* __restrict__ qbuf,
-                                                          size_t qplane, int Mpad, KvView<T> kv, int layer) {
-    const int r = blockIdx.x;
-    const int rps = sp->rps;
-    const int bi = r / rps, j = r % rps;
-    const int b = sp->seq_base + bi;
-    const int hd = md.hd, half = hd >> 1;
-    const int Nq = md.Hq * hd, Nk = md.Hkv * hd, N = Nq + 2 * Nk;
-    const int cap = kv.cap[b];
-    const int pos = kv.len[b] + j;
-    const bool in_cap = pos < cap;
-    T* Kb = kv.K + (size_t)layer * kv.layer_stride + kv.seq_off[b];
-    T* Vb = kv.V + (size_t)layer * kv.layer_stride + kv.seq_off[b];
-    const float* csr = cs + (size_t)r * half * 2;
-    auto val = [&](int col) {
-        float v = 0.f;
-#pragma unroll 4
-        for (int s = 0; s < nparts; ++s) v += part[((size_t)s * R + r) * N + col];
-        return v;
-    };
-    // q and k: pairs (i, i + half) of every head
-    const int npairs = (md.Hq + md.Hkv) * half;
-    for (int p = threadIdx.x; p < npairs; p += 512) {
-        const int head = p / half, i = p % half;
-        const float c = csr[2 * i], s = csr[2 * i + 1];
-        const int col = head * hd + i;                     // q heads then k heads are contiguous in N
-        const float lo = val(col), hi = val(col + half);
-        const float olo = lo * c - hi * s, ohi = hi * c + lo * s;
-        if (head < md.Hq) {
-            const int kvh = head / md.G, gi = head % md.G;
-            T* q = qbuf + (((size_t)bi * md.Hkv + kvh) * Mpad + (size_t)gi * rps + j) * hd;
-            Traits<T>::store_split(q + i, qplane, olo);
-            Traits<T>::store_split(q + i + half, qplane, ohi);
-        } else if (in_cap) {
-            const int kvh = head - md.Hq;
-            T* k = Kb + ((size_t)kvh * cap + pos) * hd;
-            Traits<T>::store(k + i, olo);
-            Traits<T>::store(k + i + half, ohi);
-        }
-    }
-    if (in_cap) {
-        for (int e = threadIdx.x; e < Nk; e += 512) {
-            const int kvh = e / hd, dcol = e % hd;
-            Traits<T>::store(Vb + ((size_t)kvh * hd + dcol) * cap + pos, val(Nq + Nk + e));
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Multi-query causal decode attention, split over the keys (one wave per (chunk, kv head, q-tile
-// group, sequence)).  The M = G*rps query rows that share a kv head are the MFMA "columns":
-//   S^T[key][m]  = K[key][:] . Q[m][:]           (A = K rows,   B = Q rows)
-//   O^T[hd][m]  += V^T[hd][keys] . P^T[keys][m]  (A = V^T rows, B = the S^T accumulators, re-packed)
-// The key order inside a 4*KF-key step is permuted (S tile t, A row a <-> key KF*(a/4) + 4t + a%4)
-// so that a lane's S^T accumulators are exactly its B-operand elements of the second product:
-// no LDS transpose, no cross-lane traffic except the running-max reduction over the 4 lane groups.
-// Row m = gi*rps + j sees keys 0 .. len + j.  Writes the chunk's unnormalised O, running max and sum.
-template <typename T, int HD, int MQ, int SPL>
-__global__ __launch_bounds__(64) void attn_partial_kernel(const StepParams* __restrict__ sp, ModelDims md,
-                                                          const T* __restrict__ qbuf, size_t qplane, int Mpad, KvView<T> kv, int layer,
-                                                          int chunk_keys, int nchunk_max, float* __restrict__ opart,
-                                                          float2* __restrict__ mlpart) {
-    constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
-    constexpr int NS = KF / 4;       // S^T tiles per step of KSTEP keys
-    static_assert(SPL <= Traits<T>::NS, "more planes than the storage type has");
-    constexpr int KK = HD / KSTEP;   // contraction steps over the head dimension
-    constexpr int HT = HD / 16;
-    const int chunk = blockIdx.x, kvh = blockIdx.y % md.Hkv, qg = blockIdx.y / md.Hkv, bi = blockIdx.z;
-    const int b = sp->seq_base + bi;
-    const int rps = sp->rps;
-    const int M = md.G * rps;
-    const int L = kv.len[b], cap = kv.cap[b];
-    const int kv_end = min(L + rps, cap);
-    const int key_lo = chunk * chunk_keys;
-    if (key_lo >= kv_end) return;
-    const int key_hi = min(key_lo + chunk_keys, kv_end);
-    const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
-    const T* Kb = kv.K + (size_t)layer * kv.layer_stride + kv.seq_off[b] + (size_t)kvh * cap * HD;
-    const T* Vb = kv.V + (size_t)layer * kv.layer_stride + kv.seq_off[b] + (size_t)kvh * HD * cap;
-    const T* Q = qbuf + (((size_t)bi * md.Hkv + kvh) * Mpad + (size_t)qg * MQ * 16) * HD;
-
-    Frag qf[MQ][KK][SPL];
-#pragma unroll
-    for (int mq = 0; mq < MQ; ++mq)
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-#pragma unroll
-            for (int sp = 0; sp < SPL; ++sp)
-                qf[mq][kk][sp].u = *reinterpret_cast<const u32x4*>(Q + sp * qplane + (size_t)(mq * 16 + r) * HD + kk * KSTEP + g * KF);
-
-    f32x4 o[HT][MQ];
-    float m_run[MQ], l_run[MQ];
-    int limit[MQ];
-#pragma unroll
-    for (int mq = 0; mq < MQ; ++mq) {
-        m_run[mq] = -INFINITY;
-        l_run[mq] = 0.f;
-        const int m = (qg * MQ + mq) * 16 + r;
-        limit[mq] = (m < M) ? L + (m % rps) : -1;      // last visible key; padding rows see nothing
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht) o[ht][mq] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    for (int key0 = key_lo; key0 < key_hi; key0 += KSTEP) {
-        f32x4 s[NS][MQ];
-#pragma unroll
-        for (int t = 0; t < NS; ++t) {
-#pragma unroll
-            for (int mq = 0; mq < MQ; ++mq) s[t][mq] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const int krow = key0 + KF * (r >> 2) + 4 * t + (r & 3);
-            Frag kf[KK];
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk)
-                kf[kk].u = *reinterpret_cast<const u32x4*>(Kb + (size_t)krow * HD + kk * KSTEP + g * KF);
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk)
-#pragma unroll
-                for (int mq = 0; mq < MQ; ++mq)
-#pragma unroll
-                    for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(kf[kk], qf[mq][kk][sp], s[t][mq]);
-        }
-        Frag vf[HT];
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht)
-            vf[ht].u = *reinterpret_cast<const u32x4*>(Vb + (size_t)(ht * 16 + r) * cap + key0 + g * KF);
-
-        Frag pf[MQ][SPL];
-#pragma unroll
-        for (int mq = 0; mq < MQ; ++mq) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < NS; ++t)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int key = key0 + KF * g + 4 * t + i;
-                    const float v = (key <= limit[mq]) ? s[t][mq][i] * md.scale : -INFINITY;
-                    s[t][mq][i] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[mq], mx);
-            const bool dead = (m_new == -INFINITY);
-            const float alpha = dead ? 1.f : expf(m_run[mq] - m_new);
-            float psum = 0.f;
-#pragma unroll
-            for (int t = 0; t < NS; ++t)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float p = dead ? 0.f : expf(s[t][mq][i] - m_new);
-                    psum += p;
-                    Traits<T>::template pack_split<SPL>(pf[mq], 4 * t + i, p);
-                }
-            l_run[mq] = l_run[mq] * alpha + psum;
-            m_run[mq] = m_new;
-#pragma unroll
-            for (int ht = 0; ht < HT; ++ht) o[ht][mq] *= alpha;
-        }
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-            for (int mq = 0; mq < MQ; ++mq)
-#pragma unroll
-                for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(vf[ht], pf[mq][sp], o[ht][mq]);
-    }
-
-    const size_t pbase = (((size_t)bi * md.Hkv + kvh) * nchunk_max + chunk) * Mpad;
-#pragma unroll
-    for (int mq = 0; mq < MQ; ++mq) {
-        float l = l_run[mq];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
-        const int m = (qg * MQ + mq) * 16 + r;
-        if (m < M) {
-            if (g == 0) mlpart[pbase + m] = float2{m_run[mq], l};
-#pragma unroll
-            for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) opart[(pbase + m) * HD + ht * 16 + 4 * g + i] = o[ht][mq][i];
-        }
-    }
-}
-
-// Merge of the key chunks (log-sum-exp weights, chunk order fixed) -> attention output rows in the
-// storage dtype, laid out [row][q head][hd] as the O-projection's operand.  One workgroup of HD
-// threads per (m, kv head, sequence).
-template <typename T, int HD>
-__global__ __launch_bounds__(HD) void attn_merge_kernel(const StepParams* __restrict__ sp, ModelDims md, int Mpad,
-                                                        const int32_t* __restrict__ len, const int32_t* __restrict__ capv,
-                                                        int chunk_keys, int nchunk_max, const float* __restrict__ opart,
-                                                        const float2* __restrict__ mlpart, T* __restrict__ attn_out,
-                                                        size_t aplane) {
-    const int m = blockIdx.x, kvh = blockIdx.y, bi = blockIdx.z;
-    const int rps = sp->rps;
-    if (m >= md.G * rps) return;
-    const int b = sp->seq_base + bi;
-    const int kv_end = min(len[b] + rps, capv[b]);
-    const int nch = (kv_end + chunk_keys - 1) / chunk_keys;
-    const size_t pbase = ((size_t)bi * md.Hkv + kvh) * nchunk_max;
-    // chunk statistics first (independent loads), then the weighted sum in chunk order
-    constexpr int CH = 8;
-    float mx = -INFINITY;
-    for (int c0 = 0; c0 < nch; c0 += CH) {
-        float t[CH];
-#pragma unroll
-        for (int i = 0; i < CH; ++i) t[i] = (c0 + i < nch) ? mlpart[(pbase + c0 + i) * Mpad + m].x : -INFINITY;
-#pragma unroll
-        for (int i = 0; i < CH; ++i) mx = fmaxf(mx, t[i]);
-    }
-    float den = 0.f, num = 0.f;
-    for (int c0 = 0; c0 < nch; c0 += CH) {
-        float2 ml[CH];
-        float o[CH];
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const bool in = c0 + i < nch;
-            ml[i] = in ? mlpart[(pbase + c0 + i) * Mpad + m] : float2{-INFINITY, 0.f};
-            o[i] = in ? opart[((pbase + c0 + i) * Mpad + m) * HD + threadIdx.x] : 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const float wgt = (ml[i].x == -INFINITY) ? 0.f : expf(ml[i].x - mx);
-            den += wgt * ml[i].y;
-            if (wgt != 0.f) num += wgt * o[i];
-        }
-    }
-    const int gi = m / rps, j = m % rps;
-    const int qh = kvh * md.G + gi;
-    const size_t row = (size_t)bi * rps + j;
-    Traits<T>::store_split(attn_out + (row * md.Hq + qh) * HD + threadIdx.x, aplane, num / den);
-}
-
-// ---------------------------------------------------------------------------------------------
 // Vocabulary softmax statistics of each row from the LM-head workgroups' partials:
 // row max, Z = sum exp((l - max)/T), lowest-index arg-max.  One workgroup per row.
 __global__ __launch_bounds__(256) void softmax_merge_kernel(const float4* __restrict__ stats, int nblk, float inv_temp,

@@ -2,7 +2,9 @@
 // upload / re-tiling, and the kernel sequence of one verification step.
 #include "../../include/sj.h"
 #include "sj_kernels.h"
+#include "sj_attn.h"
 #include "sj_mega.h"
+#include "sj_stream.h"
 
 #include <algorithm>
 #include <cmath>
@@ -77,8 +79,8 @@ struct sj_kv {
     StepParams* sp_dev = nullptr;
     float *x = nullptr, *hn32 = nullptr, *part = nullptr, *opart = nullptr, *cs = nullptr, *logits = nullptr;
     float *scores = nullptr, *p_at_d = nullptr;
-    void *xn = nullptr, *qbuf = nullptr, *attn_out = nullptr, *act = nullptr;
-    float2* mlpart = nullptr;
+    void *xn = nullptr, *attn_out = nullptr, *act = nullptr;
+    unsigned* tickets = nullptr;
     float4 *stats = nullptr, *rowstat = nullptr;
     int32_t *row_tok = nullptr, *bits = nullptr, *nacc = nullptr, *prefill_tok = nullptr;
     double *epart = nullptr, *wpart = nullptr;
@@ -95,7 +97,8 @@ struct sj_kv {
     hipStream_t cap_stream = nullptr;
     bool use_graph = true;
     // persistent forward kernel (small row counts)
-    bool use_mega = false;     // slower than the launch-graph path so far: opt-in with SJ_MEGA=1
+    bool use_mega = false;     // slower than the launch-graph paths so far: opt-in with SJ_MEGA=1
+    bool use_stream = false;   // stage-per-kernel variant of the persistent kernel: slower than the default path, opt-in with SJ_STREAM=1
     bf16_t *Bx = nullptr, *Battn = nullptr, *Bact = nullptr;
     float *ssq = nullptr, *row_scale = nullptr;
     MegaBar* bar = nullptr;
@@ -309,6 +312,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     kv->batch = batch;
     if (const char* e = std::getenv("SJ_NO_GRAPH")) kv->use_graph = !(e[0] == '1');
     if (const char* e = std::getenv("SJ_MEGA")) kv->use_mega = (e[0] == '1');
+    if (const char* e = std::getenv("SJ_STREAM")) kv->use_stream = (e[0] == '1');
     kv->cap.assign(batch, 64);
     kv->len_upper.assign(batch, 0);
     kv->seq_off.assign(batch, 0);
@@ -368,21 +372,22 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         size_t part_elems = std::max({(size_t)kv->split_qkv * R * (Nq + 2 * Nk), (size_t)kv->split_o * R * d,
                                       (size_t)kv->split_d * R * d});
         kv->mpad = (G * (c.max_gamma + 1) + 63) / 64 * 64;   // whole groups of 4 MFMA tiles
-        // key chunks: enough waves to fill the chip, at least 64 keys each
+        // key ranges of attention: one wave takes chunk_keys keys (at least one 32-key step, more when the
+        // total context would otherwise need more than 4096 waves), a workgroup 4 waves' worth
         {
             const int64_t total_keys = off / ((int64_t)c.n_kv_heads * hd);
-            int ck = 64;
+            int ck = 32;
             while (ck < 1024 && total_keys * c.n_kv_heads / ck > 4096) ck *= 2;
             kv->chunk_keys = ck;
-            kv->nchunk_max = (cap_max + ck - 1) / ck;
+            kv->nchunk_max = (cap_max + 4 * ck - 1) / (4 * ck);
         }
         ALLOC(kv->K, (size_t)kv->layer_stride * c.n_layers * m->esz);
         ALLOC(kv->V, (size_t)kv->layer_stride * c.n_layers * m->esz);
         ALLOC(kv->x, (size_t)R * d * 4);
         ALLOC(kv->part, part_elems * 4);
-        ALLOC(kv->qbuf, (size_t)3 * batch * c.n_kv_heads * kv->mpad * hd * m->esz);
-        ALLOC(kv->opart, (size_t)batch * c.n_kv_heads * kv->nchunk_max * kv->mpad * hd * 4);
-        ALLOC(kv->mlpart, (size_t)batch * c.n_kv_heads * kv->nchunk_max * kv->mpad * sizeof(float2));
+        // per (sequence, kv head, key range): mpad rows of hd accumulators + (max, sum) in lane order
+        ALLOC(kv->opart, (size_t)batch * c.n_kv_heads * kv->nchunk_max * kv->mpad * (hd + 8) * 4);
+        ALLOC(kv->tickets, (size_t)batch * c.n_kv_heads * (kv->mpad / 16) * 4);
         ALLOC(kv->attn_out, (size_t)3 * kv->rpad * Nq * m->esz);
         ALLOC(kv->act, (size_t)3 * kv->rpad * F * m->esz);
         ALLOC(kv->cs, (size_t)R * hd * 4);
@@ -658,13 +663,12 @@ struct Runner {
         return v;
     }
     size_t plane(int ld) const { return (size_t)kv->rpad * ld; }
-    size_t qplane() const { return (size_t)kv->batch * m->md.Hkv * kv->mpad * m->md.hd; }
-
     int partial_gemm(const void* W, const void* X, int ldx, int K, int N, int split) {
         return gemm<T, 4, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, split, kv->part, nullptr, 0, nullptr, 0.f);
     }
     int nparts(int split) const { return R > 48 ? 1 : split; }
 
+    // rotary + cache append + attention of one layer from the QKV partials in kv->part
     int attention(int layer) {
         const ModelDims& md = m->md;
         const int M = md.G * rps;
@@ -672,24 +676,17 @@ struct Runner {
         const int mq = std::min(mtiles, 4);
         const int qgroups = (mtiles + mq - 1) / mq;
         dim3 grid(kv->nchunk_max, md.Hkv * qgroups, nseq);
-#define ATTN(HD, MQ)                                                                                          \
-    attn_partial_kernel<T, HD, MQ, SPL><<<grid, 64, 0, st>>>(kv->sp_dev, md, (const T*)kv->qbuf, qplane(), kv->mpad, view(), layer, \
-                                                        kv->chunk_keys, kv->nchunk_max, kv->opart, kv->mlpart)
+#define ATTN(HD, MQ)                                                                                                   \
+    attn_fused_kernel<T, HD, MQ, SPL><<<grid, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->split_qkv), R, kv->cs, view(), \
+                                                            layer, kv->chunk_keys, kv->nchunk_max, kv->opart, kv->tickets,      \
+                                                            (T*)kv->attn_out, plane(md.Hq * md.hd))
         if (md.hd == 128) {
             switch (mq) { case 1: ATTN(128, 1); break; case 2: ATTN(128, 2); break; case 3: ATTN(128, 3); break; default: ATTN(128, 4); }
         } else {
             switch (mq) { case 1: ATTN(64, 1); break; case 2: ATTN(64, 2); break; case 3: ATTN(64, 3); break; default: ATTN(64, 4); }
         }
 #undef ATTN
-        LAUNCHCHK("attn_partial");
-        dim3 mg(M, md.Hkv, nseq);
-        if (md.hd == 128)
-            attn_merge_kernel<T, 128><<<mg, 128, 0, st>>>(kv->sp_dev, md, kv->mpad, kv->len_dev, kv->cap_dev, kv->chunk_keys,
-                                                           kv->nchunk_max, kv->opart, kv->mlpart, (T*)kv->attn_out, plane(md.Hq * md.hd));
-        else
-            attn_merge_kernel<T, 64><<<mg, 64, 0, st>>>(kv->sp_dev, md, kv->mpad, kv->len_dev, kv->cap_dev, kv->chunk_keys,
-                                                         kv->nchunk_max, kv->opart, kv->mlpart, (T*)kv->attn_out, plane(md.Hq * md.hd));
-        LAUNCHCHK("attn_merge");
+        LAUNCHCHK("attn_fused");
         return SJ_OK;
     }
 
@@ -711,9 +708,6 @@ struct Runner {
             if ((rc = time_mark(kv, 1, st))) return rc;
             if ((rc = partial_gemm(L.wqkv, kv->xn, d, d, Nqkv, kv->split_qkv))) return rc;
             if ((rc = time_mark(kv, 1, st))) return rc;
-            rope_append_kernel<T><<<R, 512, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->split_qkv), R, kv->cs,
-                                                      (T*)kv->qbuf, qplane(), kv->mpad, view(), l);
-            LAUNCHCHK("rope_append");
             if ((rc = attention(l))) return rc;
             if ((rc = time_mark(kv, 2, st))) return rc;
             if ((rc = partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->split_o))) return rc;
@@ -783,6 +777,9 @@ static int set_params(sj_kv* kv, hipStream_t st, const StepParams& p) {
     return SJ_OK;
 }
 
+static bool stream_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl);
+static int stream_forward(const sj_model* m, sj_kv* kv, int gamma, hipStream_t st);
+
 template <typename T, int SPL>
 static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool head_only, const void* hidden) {
     int rc;
@@ -792,6 +789,9 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
         HIPCHK(hipMemcpyAsync(kv->xn, hidden, n * sizeof(T), hipMemcpyDeviceToDevice, st));
         to_f32_kernel<T><<<1024, 256, 0, st>>>((const T*)hidden, kv->hn32, n);
         LAUNCHCHK("to_f32");
+    } else if (stream_eligible(m, kv, gamma, SPL)) {
+        if ((rc = stream_forward(m, kv, gamma, st))) return rc;       // includes the LM head and its softmax merge
+        return run.tail(gamma);
     } else {
         if ((rc = run.layers())) return rc;
     }
@@ -803,11 +803,23 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
 // (gamma, planes) into a launch graph and replayed; only the per-call parameter block, written by a
 // tiny kernel in front of the replay, changes between calls.
 // The persistent forward kernel serves bf16 models when the whole batch fits 8 query rows.
+// shapes the stream kernels (and the persistent kernel built from the same parts) serve
+static bool stream_shape_ok(const sj_model* m, const sj_kv* kv, int gamma, int spl);
+
 static bool mega_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl) {
-    const sj_config& c = m->cfg;
-    if (!kv->use_mega || !m->coop || m->num_cus < 1 || c.dtype != SJ_DTYPE_BF16 || spl != 2) return false;
+    if (!kv->use_mega || !m->coop) return false;
     if (kv->timing_class != 0 && kv->timing_class != 9) return false;
-    if (c.n_layers * 10 + 8 > 4096) return false;
+    if (m->cfg.n_layers * 10 + 8 > 4096) return false;
+    return stream_shape_ok(m, kv, gamma, spl);
+}
+
+static bool stream_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl) {
+    return kv->use_stream && kv->timing_class == 0 && stream_shape_ok(m, kv, gamma, spl);
+}
+
+static bool stream_shape_ok(const sj_model* m, const sj_kv* kv, int gamma, int spl) {
+    const sj_config& c = m->cfg;
+    if (m->num_cus < 1 || c.dtype != SJ_DTYPE_BF16 || spl != 2 || c.n_layers < 1) return false;
     const int R = kv->batch * (gamma + 1);
     if (R > MEGA_MAXR || c.head_dim != 128) return false;
     const int Nq = c.n_q_heads * c.head_dim;
@@ -817,7 +829,7 @@ static bool mega_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl
            Nq / 32 * 1024 <= MEGA_BIG && m->num_cus <= 1024;
 }
 
-static int launch_mega(sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
+static MegaArgs mega_args(const sj_model* m, const sj_kv* kv) {
     MegaArgs a{};
     a.layers = m->mega_layers;
     a.lm_head = (const u32x4*)m->lm_head;
@@ -831,6 +843,69 @@ static int launch_mega(sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
     a.x = kv->x; a.qkv = kv->part; a.Bx = kv->Bx; a.Battn = kv->Battn; a.Bact = kv->Bact; a.ssq = kv->ssq;
     a.hn32 = kv->hn32; a.row_scale = kv->row_scale; a.logits = kv->logits; a.stats = kv->stats; a.cs = kv->cs;
     a.bar = kv->bar;
+    a.prof = nullptr;
+    a.log_base = std::log((double)m->cfg.rope_base);
+    return a;
+}
+
+// The stages of the forward as separate stream kernels (sj_stream.h), for a launch graph to chain.
+template <int EPI, int D, bool BLDS>
+static int launch_stream_gemm(const sj_model* m, const sj_kv* kv, hipStream_t st, const MegaArgs& a, const StreamStage& sg) {
+    static bool attr_set = false;
+    auto fn = stream_gemm_kernel<EPI, D, BLDS>;
+    if (!attr_set) {
+        HIPCHK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv->mega_lds));
+        attr_set = true;
+    }
+    fn<<<m->num_cus, MEGA_THREADS, kv->mega_lds, st>>>(a, sg);
+    LAUNCHCHK("stream_gemm");
+    return SJ_OK;
+}
+
+static int stream_forward(const sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
+    const sj_config& c = m->cfg;
+    const MegaArgs a = mega_args(m, kv);
+    const int d = c.d_model, Nq = c.n_q_heads * c.head_dim, Nk = c.n_kv_heads * c.head_dim, Nqkv = Nq + 2 * Nk;
+    const int ntx = d / 16, R = kv->batch * (gamma + 1);
+    int rc;
+    stream_embed_kernel<<<std::max(ntx, R), 64, 0, st>>>(a);
+    LAUNCHCHK("stream_embed");
+    static bool attn_attr = false;
+    if (!attn_attr) {
+        HIPCHK(hipFuncSetAttribute((const void*)stream_attn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(AttnShared) + 1024));
+        attn_attr = true;
+    }
+    std::vector<MegaLayer> dummy;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const LayerW& L = m->layers[l];
+        StreamStage sg{};
+        sg.W = (const u32x4*)L.wqkv; sg.ntiles = Nqkv / 16; sg.KS = d / 32; sg.B = kv->Bx;
+        if ((rc = launch_stream_gemm<SEPI_QKV, MEGA_D, true>(m, kv, st, a, sg))) return rc;
+        stream_attn_kernel<<<kv->batch * c.n_q_heads, MEGA_SW * 64, sizeof(AttnShared) + 1024, st>>>(a, (size_t)l * kv->layer_stride);
+        LAUNCHCHK("stream_attn");
+        sg = StreamStage{};
+        sg.W = (const u32x4*)L.wo; sg.ntiles = ntx; sg.KS = Nq / 32; sg.B = kv->Battn; sg.gain_next = (const bf16_t*)L.ffn_norm;
+        if ((rc = launch_stream_gemm<SEPI_RESID, MEGA_D, true>(m, kv, st, a, sg))) return rc;
+        sg = StreamStage{};
+        sg.W = (const u32x4*)L.wgu; sg.ntiles = 2 * c.d_ffn / 16; sg.KS = d / 32; sg.B = kv->Bx;
+        if ((rc = launch_stream_gemm<SEPI_SWIGLU, MEGA_D, true>(m, kv, st, a, sg))) return rc;
+        const bool last = (l + 1 == c.n_layers);
+        sg = StreamStage{};
+        sg.W = (const u32x4*)L.wd; sg.ntiles = ntx; sg.KS = c.d_ffn / 32; sg.B = kv->Bact;
+        sg.gain_next = (const bf16_t*)(last ? m->final_norm : m->layers[l + 1].attn_norm);
+        sg.last = last ? 1 : 0;
+        if ((rc = launch_stream_gemm<SEPI_RESID, MEGA_DD, false>(m, kv, st, a, sg))) return rc;
+    }
+    StreamStage sg{};
+    sg.W = (const u32x4*)m->lm_head; sg.ntiles = c.vocab / 16; sg.KS = d / 32; sg.B = kv->Bx;
+    if ((rc = launch_stream_gemm<SEPI_LOGITS, MEGA_D, true>(m, kv, st, a, sg))) return rc;
+    softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, c.vocab / 16, m->md.inv_temp, kv->rowstat);
+    LAUNCHCHK("softmax_merge");
+    return SJ_OK;
+}
+
+static int launch_mega(sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
+    MegaArgs a = mega_args(m, kv);
     a.prof = (kv->timing_class == 9) ? kv->prof : nullptr;
     const unsigned nbar = 1u + 5u * (unsigned)m->cfg.n_layers;
     if (kv->mega_epoch > 0xF0000000u) {                       // epochs are monotonic: restart well before wrap-around
@@ -839,7 +914,6 @@ static int launch_mega(sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
         kv->mega_epoch = 0;
     }
     a.epoch0 = kv->mega_epoch;
-    a.log_base = std::log((double)m->cfg.rope_base);
     static bool attr_set = false;
     if (!attr_set) {
         HIPCHK(hipFuncSetAttribute((const void*)mega_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv->mega_lds));

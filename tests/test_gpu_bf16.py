@@ -129,15 +129,16 @@ MEGA = synth.ModelShape("mega_bf16", "bf16", 2, 4096, 32, 8, 128, 2048, 4096, 50
 
 
 @pytest.mark.parametrize("batch,gamma,lens", [(1, 5, [200]), (1, 7, [1024]), (2, 3, [77, 513])])
-def test_persistent_kernel_matches_oracle_and_multikernel_path(batch, gamma, lens, monkeypatch):
+def test_stream_and_persistent_kernels_match_oracle_and_multikernel_path(batch, gamma, lens, monkeypatch):
     shape = MEGA.scaled(batch=batch, gamma=gamma)
     src = synth.WeightSource(shape, seed=3, norm_jitter=0.1, judge_bias=0.2)
     cap = [l + 64 for l in lens]
     cfg = helpers.oracle_config(shape)
     W = helpers.oracle_weights(src, cache_items=0)
     outs = {}
-    for mode in ("mega", "multi"):
+    for mode in ("stream", "mega", "multi"):
         monkeypatch.setenv("SJ_MEGA", "1" if mode == "mega" else "0")
+        monkeypatch.setenv("SJ_STREAM", "1" if mode == "stream" else "0")
         gpu = G.Gpu(shape, src, cap)
         try:
             caches = _fill_caches(shape, gpu, cfg, lens, seed=4, capacity=cap)
@@ -152,6 +153,7 @@ def test_persistent_kernel_matches_oracle_and_multikernel_path(batch, gamma, len
         finally:
             gpu.close()
     for step in range(2):
-        a, b = outs[("mega", step)], outs[("multi", step)]
-        assert np.abs(a["logits"] - b["logits"]).max() < 5e-3
-        assert (a["accepted_len"] == b["accepted_len"]).all() and (a["next_token"] == b["next_token"]).all()
+        for other in ("stream", "mega"):
+            a, b = outs[(other, step)], outs[("multi", step)]
+            assert np.abs(a["logits"] - b["logits"]).max() < 5e-3
+            assert (a["accepted_len"] == b["accepted_len"]).all() and (a["next_token"] == b["next_token"]).all()
