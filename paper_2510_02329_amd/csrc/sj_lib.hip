@@ -66,6 +66,13 @@ struct sj_model {
     bool coop = false;
 };
 
+// Shape of a split-K projection launch: NT n-tiles and `waves` waves per workgroup, `split` K-slices
+// across workgroups (summed by the consumer).  The chip has 256 CUs and these kernels are a single
+// wave of workgroups long, so a launch whose workgroup count is not a multiple of 256 leaves CUs idle
+// for its whole duration: among the tile groupings the kernel is instantiated for, take the one that
+// wastes the fewest workgroup slots, every wave keeping at least 8 k-steps.
+struct GemmPlan { int nt = 4, waves = 4, split = 1; };
+
 struct sj_kv {
     const sj_model* m = nullptr;
     int batch = 0, max_rows = 0, rpad = 0, mpad = 0;
@@ -85,7 +92,8 @@ struct sj_kv {
     int32_t *row_tok = nullptr, *bits = nullptr, *nacc = nullptr, *prefill_tok = nullptr;
     double *epart = nullptr, *wpart = nullptr;
     int chunk_keys = 64, nchunk_max = 1, nslab = 0, slab_len = 0;
-    int split_qkv = 1, split_o = 1, split_d = 1, lm_nt = 2;
+    GemmPlan plan_qkv[2], plan_o[2], plan_d[2];   // [0]: at most 16 rows, [1]: more
+    int lm_nt = 2;
     int mode = SJ_MODE_TWO_STAGE;
     int planes = 2;            // bf16 planes of the activation operand (fp32 storage: always 1)
     int32_t* pinned_state = nullptr;      // [2*batch] staging of sj_kv_rewind
@@ -293,12 +301,20 @@ extern "C" int64_t sj_model_weight_bytes(const sj_model* m) { return m ? m->weig
 // ------------------------------------------------------------------------------------------------
 // kv / workspace
 
-// K-slices across workgroups for the projections whose output is summed by the consumer: enough
-// workgroups to cover the chip, every wave keeping at least 8 k-steps
-static int choose_split(int groups, int ksteps) {
-    int s = (384 + groups - 1) / groups;
-    s = std::min(s, std::max(1, ksteps / 32));
-    return std::max(1, std::min(s, 8));
+static GemmPlan plan_partial(int ntiles, int ksteps, bool one_row_tile) {
+    static const int cand[3][2] = {{4, 4}, {3, 8}, {6, 4}};
+    GemmPlan best;
+    double best_waste = 1e30;
+    for (const auto& c : cand) {
+        if (ntiles % c[0]) continue;
+        int split = 1;
+        while (split < 8 && ksteps / (c[1] * split * 2) >= 8) split *= 2;
+        const int wgs = ntiles / c[0] * split;
+        const double waste = (double)((wgs + 255) / 256 * 256) / wgs;
+        if (waste < best_waste - 1e-9) { best.nt = c[0]; best.waves = c[1]; best.split = split; best_waste = waste; }
+        if (!one_row_tile) break;          // more row tiles: only the 4 x 4 shape is instantiated
+    }
+    return best;
 }
 
 extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* capacity, sj_kv** out) {
@@ -366,11 +382,14 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         const int hd = c.head_dim, Nq = c.n_q_heads * hd, Nk = c.n_kv_heads * hd, F = c.d_ffn;
         const int G = c.n_q_heads / c.n_kv_heads;
         const int kstep = (c.dtype == SJ_DTYPE_FP32) ? 16 : 32;
-        kv->split_qkv = choose_split((Nq + 2 * Nk) / 64, d / kstep);
-        kv->split_o = choose_split(d / 64, Nq / kstep);
-        kv->split_d = choose_split(d / 64, F / kstep);
-        size_t part_elems = std::max({(size_t)kv->split_qkv * R * (Nq + 2 * Nk), (size_t)kv->split_o * R * d,
-                                      (size_t)kv->split_d * R * d});
+        size_t part_elems = 0;
+        for (int i = 0; i < 2; ++i) {
+            kv->plan_qkv[i] = plan_partial((Nq + 2 * Nk) / 16, d / kstep, i == 0);
+            kv->plan_o[i] = plan_partial(d / 16, Nq / kstep, i == 0);
+            kv->plan_d[i] = plan_partial(d / 16, F / kstep, i == 0);
+            part_elems = std::max({part_elems, (size_t)kv->plan_qkv[i].split * R * (Nq + 2 * Nk),
+                                   (size_t)kv->plan_o[i].split * R * d, (size_t)kv->plan_d[i].split * R * d});
+        }
         kv->mpad = (G * (c.max_gamma + 1) + 63) / 64 * 64;   // whole groups of 4 MFMA tiles
         // key ranges of attention: one wave takes chunk_keys keys (at least one 32-key step, more when the
         // total context would otherwise need more than 4096 waves), a workgroup 4 waves' worth
@@ -611,6 +630,7 @@ static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) 
     // more than one row tile multiplies the accumulators and the reduction scratch: use at most
     // 4 n-tiles and 4 waves there (the grid is scaled to match)
     constexpr int NT2 = NT > 4 ? 4 : NT, W2 = WAVES > 4 ? 4 : WAVES;
+    if (mt > 1 && NT % NT2 != 0) return fail(SJ_EINVAL, "internal: %d n-tiles per workgroup with %d row tiles", NT, mt);
     dim3 g2(grid.x * (NT / NT2), grid.y);
     switch (mt) {
         case 1: gemm_skinny_kernel<T, NT, 1, EPI, SPL, WAVES><<<grid, WAVES * 64, 0, st>>>(a); break;
@@ -663,10 +683,23 @@ struct Runner {
         return v;
     }
     size_t plane(int ld) const { return (size_t)kv->rpad * ld; }
-    int partial_gemm(const void* W, const void* X, int ldx, int K, int N, int split) {
-        return gemm<T, 4, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, split, kv->part, nullptr, 0, nullptr, 0.f);
+    int partial_gemm(const void* W, const void* X, int ldx, int K, int N, const GemmPlan (&pl)[2]) {
+        const GemmPlan& p = pl[R <= 16 ? 0 : 1];
+        if (p.nt == 3 && p.waves == 8)
+            return gemm<T, 3, EPI_PARTIAL, SPL, 8>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
+        if (p.nt == 6 && p.waves == 4)
+            return gemm<T, 6, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
+        return gemm<T, 4, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
     }
-    int nparts(int split) const { return R > 48 ? 1 : split; }
+    int nparts(const GemmPlan (&pl)[2]) const { return R > 48 ? 1 : pl[R <= 16 ? 0 : 1].split; }
+    // gate / up projection with the SwiGLU epilogue: 7 n-tiles per workgroup when that gives a whole
+    // number of workgroups per CU (2F/16 = 1792 tiles -> 256 workgroups), else 8
+    int gate_up(const void* W) {
+        const ModelDims& md = m->md;
+        if (R <= 16 && (2 * md.F / 16) % 7 == 0)
+            return gemm<T, 7, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
+        return gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
+    }
 
     // rotary + cache append + attention of one layer from the QKV partials in kv->part
     int attention(int layer) {
@@ -677,7 +710,7 @@ struct Runner {
         const int qgroups = (mtiles + mq - 1) / mq;
         dim3 grid(kv->nchunk_max, md.Hkv * qgroups, nseq);
 #define ATTN(HD, MQ)                                                                                                   \
-    attn_fused_kernel<T, HD, MQ, SPL><<<grid, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->split_qkv), R, kv->cs, view(), \
+    attn_fused_kernel<T, HD, MQ, SPL><<<grid, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->plan_qkv), R, kv->cs, view(), \
                                                             layer, kv->chunk_keys, kv->nchunk_max, kv->opart, kv->tickets,      \
                                                             (T*)kv->attn_out, plane(md.Hq * md.hd))
         if (md.hd == 128) {
@@ -706,22 +739,22 @@ struct Runner {
                                                       (T*)kv->xn, plane(d), nullptr);
             LAUNCHCHK("add_rmsnorm");
             if ((rc = time_mark(kv, 1, st))) return rc;
-            if ((rc = partial_gemm(L.wqkv, kv->xn, d, d, Nqkv, kv->split_qkv))) return rc;
+            if ((rc = partial_gemm(L.wqkv, kv->xn, d, d, Nqkv, kv->plan_qkv))) return rc;
             if ((rc = time_mark(kv, 1, st))) return rc;
             if ((rc = attention(l))) return rc;
             if ((rc = time_mark(kv, 2, st))) return rc;
-            if ((rc = partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->split_o))) return rc;
+            if ((rc = partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->plan_o))) return rc;
             if ((rc = time_mark(kv, 2, st))) return rc;
-            add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, nparts(kv->split_o), (const T*)L.ffn_norm,
+            add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, nparts(kv->plan_o), (const T*)L.ffn_norm,
                                                       (T*)kv->xn, plane(d), nullptr);
             LAUNCHCHK("add_rmsnorm");
             if ((rc = time_mark(kv, 3, st))) return rc;
-            if ((rc = gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, L.wgu, kv->xn, plane(d), d, d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f))) return rc;
+            if ((rc = gate_up(L.wgu))) return rc;
             if ((rc = time_mark(kv, 3, st))) return rc;
             if ((rc = time_mark(kv, 4, st))) return rc;
-            if ((rc = partial_gemm(L.wd, kv->act, md.F, md.F, d, kv->split_d))) return rc;
+            if ((rc = partial_gemm(L.wd, kv->act, md.F, md.F, d, kv->plan_d))) return rc;
             if ((rc = time_mark(kv, 4, st))) return rc;
-            pending_parts = nparts(kv->split_d);
+            pending_parts = nparts(kv->plan_d);
         }
         add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)m->final_norm,
                                                   (T*)kv->xn, plane(d), kv->hn32);
@@ -987,11 +1020,10 @@ static int time_kernel_impl(sj_model* m, sj_kv* kv, int cls, int launches, int g
     for (int i = 0; i < launches && !rc; ++i) {
         const LayerW& L = m->layers[i % m->cfg.n_layers];        // a different layer each time: no cache reuse
         switch (cls) {
-            case 1: rc = run.partial_gemm(L.wqkv, kv->xn, d, d, Nq + 2 * Nk, kv->split_qkv); break;
-            case 2: rc = run.partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->split_o); break;
-            case 3: rc = gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, L.wgu, kv->xn, run.plane(d), d, d, 2 * md.F, run.R, 1, nullptr, kv->act,
-                                                        run.plane(md.F), nullptr, 0.f); break;
-            default: rc = run.partial_gemm(L.wd, kv->act, md.F, md.F, d, kv->split_d); break;
+            case 1: rc = run.partial_gemm(L.wqkv, kv->xn, d, d, Nq + 2 * Nk, kv->plan_qkv); break;
+            case 2: rc = run.partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->plan_o); break;
+            case 3: rc = run.gate_up(L.wgu); break;
+            default: rc = run.partial_gemm(L.wd, kv->act, md.F, md.F, d, kv->plan_d); break;
         }
     }
     hipError_t e = hipEventRecord(e1, st);
