@@ -165,7 +165,16 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(int R, int d, float e
         v[p] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (c < d) {
             v[p] = *reinterpret_cast<const f32x4*>(xr + c);
-            for (int s = 0; s < nparts; ++s) v[p] += *reinterpret_cast<const f32x4*>(part + ((size_t)s * R + r) * d + c);
+            // partials in batches of 8 independent loads (index clamped, surplus ignored), added in order
+            for (int s0 = 0; s0 < nparts; s0 += 8) {
+                f32x4 t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    t[u] = *reinterpret_cast<const f32x4*>(part + ((size_t)min(s0 + u, nparts - 1) * R + r) * d + c);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < nparts) v[p] += t[u];
+            }
             if (nparts) *reinterpret_cast<f32x4*>(xr + c) = v[p];
             ss += v[p][0] * v[p][0] + v[p][1] * v[p][1] + v[p][2] * v[p][2] + v[p][3] * v[p][3];
         }
@@ -181,12 +190,11 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(int R, int d, float e
     for (int p = 0; p < MAXP; ++p) {
         const int c = (p * 1024 + threadIdx.x) * 4;
         if (c < d) {
+            float y[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float y = v[p][i] * inv * Traits<T>::load(gain + c + i);
-                Traits<T>::store_split(xn + (size_t)r * d + c + i, xplane, y);
-                if (xn32) xn32[(size_t)r * d + c + i] = y;
-            }
+            for (int i = 0; i < 4; ++i) y[i] = v[p][i] * inv * Traits<T>::load(gain + c + i);
+            Traits<T>::store_split4(xn + (size_t)r * d + c, xplane, y);
+            if (xn32) *reinterpret_cast<f32x4*>(xn32 + (size_t)r * d + c) = f32x4{y[0], y[1], y[2], y[3]};
         }
     }
 }
