@@ -38,6 +38,14 @@ __device__ unsigned long long attn_prof[4096 * 16];
 #define ATTN_STAMP(k) do { } while (0)
 #endif
 
+// m / d for 0 <= m < 2^20, 0 < d: reciprocal estimate + one correction step either way
+__device__ __forceinline__ int small_div(int m, int d) {
+    int q = (int)((float)m * __frcp_rn((float)d));
+    q -= (q * d > m);
+    q += ((q + 1) * d <= m);
+    return q;
+}
+
 template <typename T, int HD, int MQ, int SPL>
 struct AttnSmem {
     static constexpr int HT = HD / 16, KK = HD / Traits<T>::KSTEP;
@@ -115,7 +123,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
         const int mq = gq / (KK / 2);
         const int m = (qg * MQ + mq) * 16 + r;
         valid = m < M;                                 // padding rows read row 0 (valid memory), masked later
-        const int gi = valid ? m / rps : 0, j = valid ? m - gi * rps : 0;
+        const int gi = valid ? small_div(m, rps) : 0, j = valid ? m - gi * rps : 0;
         row = bi * rps + j;
         head = kvh * md.G + gi;
     };
@@ -123,9 +131,10 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
         int row, head; bool valid;
         q_row(gq, row, head, valid);
         const int i0 = (gq % (KK / 2)) * KSTEP + g * KF;
+        const int off0 = row * N + head * HD + i0;     // the partials hold fewer than 2^31 elements
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float* pl = part + ((size_t)min(s0 + u, nparts - 1) * R + row) * N + head * HD + i0;
+            const float* pl = part + (off0 + min(s0 + u, nparts - 1) * R * N);
 #pragma unroll
             for (int e = 0; e < KF / 4; ++e) {
                 qa[u][e] = *reinterpret_cast<const float4*>(pl + 4 * e);
@@ -152,14 +161,15 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
             int j, i; bool isv;
             nr_item(min(base + u * 256 + tid, nr_total - 1), j, i, isv);
             const int row = bi * rps + j, col = (isv ? Nq + Nk : Nq) + kvh * HD + i;
+            const int off0 = row * N + col;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float* pl = part + ((size_t)min(s0 + v, nparts - 1) * R + row) * N + col;
+                const float* pl = part + (off0 + min(s0 + v, nparts - 1) * R * N);
                 nlo[u][v] = pl[0];
                 nhi[u][v] = pl[HALF];
             }
-            ncs[u][0] = cs[((size_t)row * HALF + i) * 2];
-            ncs[u][1] = cs[((size_t)row * HALF + i) * 2 + 1];
+            ncs[u][0] = cs[(row * HALF + i) * 2];
+            ncs[u][1] = cs[(row * HALF + i) * 2 + 1];
         }
     };
     nr_issue(0, 0);
@@ -185,7 +195,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
         int row, head; bool valid;
         q_row(gq, row, head, valid);
         const int mq = gq / (KK / 2), kk = gq % (KK / 2), i0 = kk * KSTEP + g * KF;
-        const float* csr = cs + ((size_t)row * HALF + i0) * 2;
+        const float* csr = cs + (row * HALF + i0) * 2;
         Frag f0[SPL], f1[SPL];
 #pragma unroll
         for (int e = 0; e < KF; ++e) {
@@ -263,7 +273,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
     for (int mq = 0; mq < MQ; ++mq) {
         const int m = (qg * MQ + mq) * 16 + r;
         rowvalid[mq] = m < M;
-        girow[mq] = rowvalid[mq] ? m / rps : 0;
+        girow[mq] = rowvalid[mq] ? small_div(m, rps) : 0;
         jrow[mq] = rowvalid[mq] ? m - girow[mq] * rps : 0;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)

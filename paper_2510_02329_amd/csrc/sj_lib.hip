@@ -403,6 +403,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         ALLOC(kv->K, (size_t)kv->layer_stride * c.n_layers * m->esz);
         ALLOC(kv->V, (size_t)kv->layer_stride * c.n_layers * m->esz);
         ALLOC(kv->x, (size_t)R * d * 4);
+        if (part_elems >= ((size_t)1 << 31)) return bail(fail(SJ_EINVAL, "batch * (max_gamma + 1) rows need a projection workspace beyond 2^31 elements"));
         ALLOC(kv->part, part_elems * 4);
         // per (sequence, kv head, key range): mpad rows of hd accumulators + (max, sum) in lane order
         ALLOC(kv->opart, (size_t)batch * c.n_kv_heads * kv->nchunk_max * kv->mpad * (hd + 8) * 4);
@@ -706,7 +707,10 @@ struct Runner {
         const ModelDims& md = m->md;
         const int M = md.G * rps;
         const int mtiles = (M + 15) / 16;
-        const int mq = std::min(mtiles, 4);
+        // one query tile per workgroup while the launch stays small (shortest dependent chain per wave;
+        // K / V are then read once per tile), up to 4 tiles per workgroup for large batches
+        const bool small = (long long)nseq * md.Hkv * kv->nchunk_max * mtiles <= 512;
+        const int mq = small ? 1 : std::min(mtiles, 4);
         const int qgroups = (mtiles + mq - 1) / mq;
         dim3 grid(kv->nchunk_max, md.Hkv * qgroups, nseq);
 #define ATTN(HD, MQ)                                                                                                   \
