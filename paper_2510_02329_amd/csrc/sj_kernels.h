@@ -218,11 +218,16 @@ struct GemmArgs {
     float inv_temp;     // 1/T, 0 when T = 0
 };
 
-template <typename T, int NT, int MT, int EPI, int SPL, int WAVES>
+#ifdef SJ_GEMM_PROF
+__device__ unsigned long long gemm_prof[8192 * 8];
+#define GEMM_STAMP(k) do { if ((threadIdx.x & 63) == 0) gemm_prof[(((blockIdx.y * gridDim.x + blockIdx.x) * WAVES + (threadIdx.x >> 6)) & 8191) * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define GEMM_STAMP(k) do { } while (0)
+#endif
+
+template <typename T, int NT, int MT, int EPI, int SPL, int WAVES, int D = 2>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
-    constexpr int UU = 12 / (NT + MT * SPL);
-    constexpr int U = UU < 1 ? 1 : (UU > 4 ? 4 : UU);         // k-steps per register buffer
     __shared__ float red[WAVES][NT * MT][256];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
@@ -246,60 +251,44 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[t][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Two register buffers of U k-steps each; the loads of the next buffer are always issued (index
-    // clamped to the last chunk) before the current one is consumed, so the loop body is branch-free
-    // around the loads and the hardware keeps one buffer's worth of weight tiles in flight.
-    Frag fa[2][U][NT], fb[2][U][MT][SPL];
-    auto load = [&](int buf, int chunk) {
-        const size_t k = (size_t)chunk * U;
+    // Ring of D single-k-step register buffers.  The load of step i + D - 1 is always issued (index
+    // clamped to the last step) before step i is consumed, so the loop body is branch-free around the
+    // loads - a load under a branch makes the compiler wait for everything outstanding - and the wave
+    // keeps D - 1 k-steps of weight tiles in flight, waited for one step at a time.
+    Frag fa[D][NT], fb[D][MT][SPL];
+    auto load = [&](int buf, int ks) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) fa[buf][u][t].u = __builtin_nontemporal_load(Wt + ((size_t)t * KS + k + u) * 64);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int m = 0; m < MT; ++m)
-#pragma unroll
-                for (int sp = 0; sp < SPL; ++sp)
-                    fb[buf][u][m][sp].u = *reinterpret_cast<const u32x4*>(Xr[m] + sp * a.xplane + (k + u) * KSTEP);
-    };
-    auto compute = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int m = 0; m < MT; ++m)
-#pragma unroll
-                    for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(fa[buf][u][t], fb[buf][u][m][sp], acc[t][m]);
-    };
-    const int nchunk = (ks1 - ks0) / U;
-    if (nchunk > 0) {
-        load(0, 0);
-        for (int c = 0; c < nchunk; c += 2) {
-            load(1, min(c + 1, nchunk - 1));
-            compute(0);
-            load(0, min(c + 2, nchunk - 1));
-            if (c + 1 < nchunk) compute(1);
-        }
-    }
-    for (int ks = nchunk * U; ks < ks1 - ks0; ++ks) {          // remainder k-steps
-        Frag ta[NT], tb[MT][SPL];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) ta[t].u = __builtin_nontemporal_load(Wt + ((size_t)t * KS + ks) * 64);
+        for (int t = 0; t < NT; ++t) fa[buf][t].u = __builtin_nontemporal_load(Wt + ((size_t)t * KS + ks) * 64);
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
-            for (int sp = 0; sp < SPL; ++sp) tb[m][sp].u = *reinterpret_cast<const u32x4*>(Xr[m] + sp * a.xplane + (size_t)ks * KSTEP);
+            for (int sp = 0; sp < SPL; ++sp)
+                fb[buf][m][sp].u = *reinterpret_cast<const u32x4*>(Xr[m] + sp * a.xplane + (size_t)ks * KSTEP);
+    };
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
-                for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(ta[t], tb[m][sp], acc[t][m]);
+                for (int sp = 0; sp < SPL; ++sp) Traits<T>::mma(fa[buf][t], fb[buf][m][sp], acc[t][m]);
+    };
+    const int nks = ks1 - ks0;
+    GEMM_STAMP(0);
+    if (nks > 0) {
+#pragma unroll
+        for (int j = 0; j < D - 1; ++j) load(j, min(j, nks - 1));
+        GEMM_STAMP(1);
+        for (int c = 0; c < nks; c += D) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                load((j + D - 1) % D, min(c + j + D - 1, nks - 1));
+                if (c + j < nks) compute(j);
+            }
+        }
     }
 
+    GEMM_STAMP(2);
     // D[n = 4g+i][row = r]  ->  red[w][tile][row*16 + n]
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -309,6 +298,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
             for (int i = 0; i < 4; ++i) red[w][t * MT + m][r * 16 + 4 * g + i] = acc[t][m][i];
     __syncthreads();
 
+    GEMM_STAMP(3);
     // the first 256 threads own one (row, column) position of every tile; partial sums are added in
     // wave order
     if (threadIdx.x >= 256) return;

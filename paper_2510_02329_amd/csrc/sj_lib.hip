@@ -626,7 +626,7 @@ extern "C" int sj_kv_state(const sj_kv* kv, int32_t* len_host, int32_t* pending_
 // ------------------------------------------------------------------------------------------------
 // kernel sequence
 
-template <typename T, int NT, int EPI, int SPL, int WAVES>
+template <typename T, int NT, int EPI, int SPL, int WAVES, int D>
 static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) {
     // more than one row tile multiplies the accumulators and the reduction scratch: use at most
     // 4 n-tiles and 4 waves there (the grid is scaled to match)
@@ -634,7 +634,7 @@ static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) 
     if (mt > 1 && NT % NT2 != 0) return fail(SJ_EINVAL, "internal: %d n-tiles per workgroup with %d row tiles", NT, mt);
     dim3 g2(grid.x * (NT / NT2), grid.y);
     switch (mt) {
-        case 1: gemm_skinny_kernel<T, NT, 1, EPI, SPL, WAVES><<<grid, WAVES * 64, 0, st>>>(a); break;
+        case 1: gemm_skinny_kernel<T, NT, 1, EPI, SPL, WAVES, D><<<grid, WAVES * 64, 0, st>>>(a); break;
         case 2: gemm_skinny_kernel<T, NT2, 2, EPI, SPL, W2><<<g2, W2 * 64, 0, st>>>(a); break;
         case 3: gemm_skinny_kernel<T, NT2, 3, EPI, SPL, W2><<<g2, W2 * 64, 0, st>>>(a); break;
         default: return fail(SJ_EINVAL, "internal: unsupported m-tile count %d", mt);
@@ -646,7 +646,7 @@ static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) 
 // Y = X W^T for all `rows` rows; rows are processed in groups of at most 48 (3 MFMA tiles).
 // X has SPL planes `xplane` elements apart; act (EPI_SWIGLU) planes are `actplane` apart.
 // NT n-tiles per workgroup (N/16 must be a multiple of NT), WAVES waves split the K-slice.
-template <typename T, int NT, int EPI, int SPL, int WAVES>
+template <typename T, int NT, int EPI, int SPL, int WAVES, int D = 2>
 static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
                 float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
     const int ngroups = N / 16 / NT;
@@ -664,7 +664,7 @@ static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, in
         if (EPI == EPI_PARTIAL) a.out = out + (size_t)row0 * N;            // [split][rows][N], split = 1 if grouped
         else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ngroups; }
         else a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
-        int rc = launch_gemm_mt<T, NT, EPI, SPL, WAVES>((nr + 15) / 16, dim3(ngroups, split), st, a);
+        int rc = launch_gemm_mt<T, NT, EPI, SPL, WAVES, D>((nr + 15) / 16, dim3(ngroups, split), st, a);
         if (rc) return rc;
     }
     return SJ_OK;
@@ -690,6 +690,9 @@ struct Runner {
             return gemm<T, 3, EPI_PARTIAL, SPL, 8>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
         if (p.nt == 6 && p.waves == 4)
             return gemm<T, 6, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
+        // short K-slices (at most 8 k-steps per wave): a deeper register ring puts the whole slice in flight
+        if (R <= 16 && K / Traits<T>::KSTEP / (p.split * 4) <= 8)
+            return gemm<T, 4, EPI_PARTIAL, SPL, 4, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
         return gemm<T, 4, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
     }
     int nparts(const GemmPlan (&pl)[2]) const { return R > 48 ? 1 : pl[R <= 16 ? 0 : 1].split; }
