@@ -1,0 +1,170 @@
+// Weight-streaming GEMM for more than one row tile (batched verification: R = batch * (gamma + 1)
+// rows, up to 144 per launch): Y[R][N] = X[R][K] * W[N][K]^T with W in the re-tiled layout.
+// Paper reference: the projections of the target forward, Eq. 2 / Eq. 4.
+//
+// With many rows the few-row kernel's scheme (every wave fetches its own operand fragments) turns the
+// operand into the dominant traffic.  Here a workgroup is 8 waves that share ONE K-slice and own one
+// n-tile each: the operand fragments of a stage (KB k-steps, all row tiles, all planes) are staged
+// once per workgroup in LDS in MFMA fragment order and read by all 8 waves, while every wave streams
+// its own weight tile through registers.  Each weight byte is read once per launch; the row tiles
+// live in the accumulators (9 tiles x 4 registers).  No cross-wave reduction is needed, so the
+// epilogue runs straight from the accumulators.  Split-K across workgroups (gridDim.y slices,
+// partials summed by the consumer in slice order) keeps the short projections on all CUs.
+//
+// MFMA convention as in the few-row kernel: A = weight fragment (rows = n), B = operand fragment
+// (rows = m), lane 16g + r then holds D[n = 4g + i][m = r].
+#pragma once
+#include "sj_kernels.h"
+
+namespace sj {
+
+constexpr int ROWS_MT = 9;         // row tiles per launch (144 rows)
+constexpr int ROWS_WAVES = 8;      // waves = n-tiles per workgroup
+
+template <typename T, int SPL> constexpr int rows_kb() { return (SPL >= 3) ? 2 : 4; }   // k-steps per stage
+
+template <typename T, int EPI, int SPL>
+__global__ __launch_bounds__(ROWS_WAVES * 64) void gemm_rows_kernel(GemmArgs a, int mt) {
+    constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
+    constexpr int KB = rows_kb<T, SPL>();
+    constexpr int NTHR = ROWS_WAVES * 64;
+    constexpr int XR = (SPL * ROWS_MT * 16 * KB * 4 + NTHR - 1) / NTHR;    // staged 16-byte granules per thread
+    __shared__ u32x4 Bs[2][SPL][ROWS_MT][KB][64];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int KS = a.K / KSTEP, ntiles = a.N / 16;
+    const int nt = blockIdx.x * ROWS_WAVES + w;
+    const bool live = nt < ntiles;                     // a trailing workgroup may own fewer tiles
+    const int ks0 = (int)((long long)blockIdx.y * KS / gridDim.y), ks1 = (int)((long long)(blockIdx.y + 1) * KS / gridDim.y);
+    const int nks = ks1 - ks0, nstage = (nks + KB - 1) / KB;
+    const u32x4* Wt = reinterpret_cast<const u32x4*>(a.Wt) + ((size_t)(live ? nt : 0) * KS + ks0) * 64 + lane;
+    const int rows = mt * 16;
+    const int ngran = SPL * rows * KB * 4;             // granules of one stage
+
+    f32x4 acc[ROWS_MT];
+#pragma unroll
+    for (int m = 0; m < ROWS_MT; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // stage s covers k-steps [s*KB, s*KB + KB) of the slice; indices past the slice are clamped to its
+    // last k-step (loaded twice, multiplied never), so all loads are branch-free
+    Frag wq[2][KB];
+    u32x4 xq[XR];
+    // a thread stages the same granules (plane, row, k-step of the stage, 16-byte column) every stage:
+    // source offset without the stage's k offset, k-step inside the stage, LDS slot (-1: none)
+    size_t xsrc[XR];
+    int xkb[XR], xdst[XR];
+#pragma unroll
+    for (int i = 0; i < XR; ++i) {
+        const int raw = i * NTHR + tid, idx = min(raw, ngran - 1);
+        const int gq = idx & 3, kb = (idx >> 2) % KB, row = (idx / (4 * KB)) % rows, sp = idx / (4 * KB * rows);
+        xsrc[i] = sp * a.xplane + (size_t)(row < a.R ? row : 0) * a.ldx + (size_t)ks0 * KSTEP + gq * KF;
+        xkb[i] = kb;
+        xdst[i] = (raw < ngran) ? (((sp * ROWS_MT + (row >> 4)) * KB + kb) * 64 + gq * 16 + (row & 15)) : -1;
+    }
+    auto load_w = [&](int buf, int s) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) wq[buf][kb].u = __builtin_nontemporal_load(Wt + (size_t)min(s * KB + kb, nks - 1) * 64);
+    };
+    auto load_x = [&](int s) {
+#pragma unroll
+        for (int i = 0; i < XR; ++i)
+            xq[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(a.X) + xsrc[i] + (size_t)min(s * KB + xkb[i], nks - 1) * KSTEP);
+    };
+    auto store_x = [&](int buf) {
+        u32x4* dst = &Bs[buf][0][0][0][0];
+#pragma unroll
+        for (int i = 0; i < XR; ++i)
+            if (xdst[i] >= 0) dst[xdst[i]] = xq[i];
+    };
+    auto compute = [&](int buf, int wb, int s) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            if (s * KB + kb < nks) {
+#pragma unroll
+                for (int m = 0; m < ROWS_MT; ++m) {
+                    if (m < mt) {
+#pragma unroll
+                        for (int sp = 0; sp < SPL; ++sp) {
+                            Frag b;
+                            b.u = Bs[buf][sp][m][kb][lane];
+                            Traits<T>::mma(wq[wb][kb], b, acc[m]);
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    if (nstage > 0) {
+        load_w(0, 0);
+        load_x(0);
+        store_x(0);
+        __syncthreads();
+        for (int s = 0; s < nstage; s += 2) {
+            // even stage: LDS buffer 0, weight buffer 0; prefetch stage s + 1 into the other buffers
+            load_w(1, min(s + 1, nstage - 1));
+            load_x(min(s + 1, nstage - 1));
+            compute(0, 0, s);
+            store_x(1);
+            __syncthreads();
+            if (s + 1 < nstage) {
+                load_w(0, min(s + 2, nstage - 1));
+                load_x(min(s + 2, nstage - 1));
+                compute(1, 1, s + 1);
+                store_x(0);
+                __syncthreads();
+            }
+        }
+    }
+    if (!live) return;
+
+    // ---- epilogue from the accumulators: lane holds columns nt*16 + 4g .. +3 of row m*16 + r
+#pragma unroll
+    for (int m = 0; m < ROWS_MT; ++m) {
+        if (m >= mt) continue;                         // wave-uniform
+        const int row = m * 16 + r;
+        const bool valid = row < a.R;
+        if constexpr (EPI == EPI_PARTIAL) {
+            if (valid)
+                *reinterpret_cast<f32x4*>(a.out + ((size_t)blockIdx.y * a.slice_rows + row) * a.N + (size_t)nt * 16 + 4 * g) = acc[m];
+        } else if constexpr (EPI == EPI_SWIGLU) {
+            // tile rows 0-7 are gate of FFN columns 8*nt .. 8*nt+7, rows 8-15 their up projections:
+            // the up value of this lane's gate sits two lane groups further
+            float y[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float up = __shfl_down(acc[m][i], 32, 64);
+                const float gate = acc[m][i];
+                y[i] = gate / (1.0f + expf(-gate)) * up;
+            }
+            if (valid && g < 2)
+                Traits<T>::store_split4(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)nt * 8 + 4 * g, a.actplane, y);
+        } else {
+            // logits + this tile's softmax partial of the row (max, sum exp((l - max)/T), lowest arg-max)
+            float mx = acc[m][0];
+            int arg = nt * 16 + 4 * g;
+#pragma unroll
+            for (int i = 1; i < 4; ++i)
+                if (acc[m][i] > mx) { mx = acc[m][i]; arg = nt * 16 + 4 * g + i; }
+#pragma unroll
+            for (int o = 16; o < 64; o <<= 1) {
+                const float omx = __shfl_xor(mx, o, 64);
+                const int oarg = __shfl_xor(arg, o, 64);
+                if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+            }
+            float se = 0.f;
+            if (a.inv_temp > 0.f) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) se += expf((acc[m][i] - mx) * a.inv_temp);
+                se += __shfl_xor(se, 16, 64);
+                se += __shfl_xor(se, 32, 64);
+            }
+            if (valid) {
+                *reinterpret_cast<f32x4*>(a.out + (size_t)row * a.N + (size_t)nt * 16 + 4 * g) = acc[m];
+                if (g == 0) a.stats[(size_t)row * ntiles + nt] = float4{mx, se, __int_as_float(arg), 0.f};
+            }
+        }
+    }
+}
+
+}  // namespace sj

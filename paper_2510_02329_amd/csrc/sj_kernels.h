@@ -212,7 +212,8 @@ struct GemmArgs {
     size_t xplane;      // elements between consecutive planes of X
     size_t actplane;    // same for act
     int32_t ldx, K, N, R;
-    float* out;         // EPI_PARTIAL: [gridDim.y][R][N] fp32;  EPI_LOGITS: [R][N] fp32
+    int32_t slice_rows; // EPI_PARTIAL: rows between consecutive K-slices of out (>= R)
+    float* out;         // EPI_PARTIAL: [gridDim.y][slice_rows][N] fp32;  EPI_LOGITS: [R][N] fp32
     void* act;          // EPI_SWIGLU: [MT*16][N/2] storage dtype = silu(gate) * up
     float4* stats;      // EPI_LOGITS: [R][gridDim.x] (max, sum exp((l-max)/T), argmax as float bits, 0)
     float inv_temp;     // 1/T, 0 when T = 0
@@ -319,7 +320,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
             if (row < a.R) {
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
-                    a.out[((size_t)blockIdx.y * a.R + row) * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
+                    a.out[((size_t)blockIdx.y * a.slice_rows + row) * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
             }
         } else if constexpr (EPI == EPI_SWIGLU) {
             // tile column en < 8 is gate of FFN column 8*tile + en, column en + 8 its up projection

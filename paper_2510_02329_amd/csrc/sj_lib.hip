@@ -3,6 +3,7 @@
 #include "../../include/sj.h"
 #include "sj_kernels.h"
 #include "sj_attn.h"
+#include "sj_gemm_rows.h"
 #include "sj_mega.h"
 #include "sj_stream.h"
 
@@ -304,6 +305,14 @@ extern "C" int64_t sj_model_weight_bytes(const sj_model* m) { return m ? m->weig
 static GemmPlan plan_partial(int ntiles, int ksteps, bool one_row_tile) {
     static const int cand[3][2] = {{4, 4}, {3, 8}, {6, 4}};
     GemmPlan best;
+    if (!one_row_tile) {
+        // LDS-staged kernel: 8 n-tiles per workgroup; K-slices until the chip is covered, every slice
+        // keeping at least two 4-k-step stages
+        const int groups = (ntiles + 7) / 8;
+        best.nt = 8; best.waves = 8; best.split = 1;
+        while (groups * best.split < 256 && best.split < 8 && ksteps / (best.split * 2) >= 8) best.split *= 2;
+        return best;
+    }
     double best_waste = 1e30;
     for (const auto& c : cand) {
         if (ntiles % c[0]) continue;
@@ -312,7 +321,6 @@ static GemmPlan plan_partial(int ntiles, int ksteps, bool one_row_tile) {
         const int wgs = ntiles / c[0] * split;
         const double waste = (double)((wgs + 255) / 256 * 256) / wgs;
         if (waste < best_waste - 1e-9) { best.nt = c[0]; best.waves = c[1]; best.split = split; best_waste = waste; }
-        if (!one_row_tile) break;          // more row tiles: only the 4 x 4 shape is instantiated
     }
     return best;
 }
@@ -626,46 +634,44 @@ extern "C" int sj_kv_state(const sj_kv* kv, int32_t* len_host, int32_t* pending_
 // ------------------------------------------------------------------------------------------------
 // kernel sequence
 
-template <typename T, int NT, int EPI, int SPL, int WAVES, int D>
-static int launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const GemmArgs& a) {
-    // more than one row tile multiplies the accumulators and the reduction scratch: use at most
-    // 4 n-tiles and 4 waves there (the grid is scaled to match)
-    constexpr int NT2 = NT > 4 ? 4 : NT, W2 = WAVES > 4 ? 4 : WAVES;
-    if (mt > 1 && NT % NT2 != 0) return fail(SJ_EINVAL, "internal: %d n-tiles per workgroup with %d row tiles", NT, mt);
-    dim3 g2(grid.x * (NT / NT2), grid.y);
-    switch (mt) {
-        case 1: gemm_skinny_kernel<T, NT, 1, EPI, SPL, WAVES, D><<<grid, WAVES * 64, 0, st>>>(a); break;
-        case 2: gemm_skinny_kernel<T, NT2, 2, EPI, SPL, W2><<<g2, W2 * 64, 0, st>>>(a); break;
-        case 3: gemm_skinny_kernel<T, NT2, 3, EPI, SPL, W2><<<g2, W2 * 64, 0, st>>>(a); break;
-        default: return fail(SJ_EINVAL, "internal: unsupported m-tile count %d", mt);
-    }
+// Few rows (at most 16): Y = X W^T with the few-row kernel.  X has SPL planes `xplane` elements apart;
+// act (EPI_SWIGLU) planes are `actplane` apart.  NT n-tiles per workgroup (N/16 must be a multiple
+// of NT), WAVES waves split the K-slice, D = depth of the register ring.
+template <typename T, int NT, int EPI, int SPL, int WAVES, int D = 2>
+static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
+                float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
+    if (rows > 16) return fail(SJ_EINVAL, "internal: few-row kernel called with %d rows", rows);
+    const int ngroups = N / 16 / NT;
+    GemmArgs a{};
+    a.Wt = Wt; a.X = X; a.xplane = xplane; a.actplane = actplane;
+    a.ldx = ldx; a.K = K; a.N = N; a.R = rows; a.slice_rows = rows;
+    a.inv_temp = inv_temp;
+    a.out = out; a.stats = stats; a.act = act;
+    gemm_skinny_kernel<T, NT, 1, EPI, SPL, WAVES, D><<<dim3(ngroups, split), WAVES * 64, 0, st>>>(a);
     LAUNCHCHK("gemm_skinny");
     return SJ_OK;
 }
 
-// Y = X W^T for all `rows` rows; rows are processed in groups of at most 48 (3 MFMA tiles).
-// X has SPL planes `xplane` elements apart; act (EPI_SWIGLU) planes are `actplane` apart.
-// NT n-tiles per workgroup (N/16 must be a multiple of NT), WAVES waves split the K-slice.
-template <typename T, int NT, int EPI, int SPL, int WAVES, int D = 2>
-static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
-                float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
-    const int ngroups = N / 16 / NT;
-    if (EPI == EPI_PARTIAL && rows > 48) split = 1;     // slice stride below assumes one slice then
-    for (int row0 = 0; row0 < rows; row0 += 48) {
-        const int nr = std::min(48, rows - row0);
+// More rows: groups of at most 144 rows (9 MFMA row tiles) through the LDS-staged kernel; the statistics
+// of EPI_LOGITS are per n-tile there ([rows][N/16]).
+template <typename T, int EPI, int SPL>
+static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
+                     float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
+    const int ntiles = N / 16;
+    for (int row0 = 0; row0 < rows; row0 += ROWS_MT * 16) {
+        const int nr = std::min(ROWS_MT * 16, rows - row0);
         GemmArgs a{};
         a.Wt = Wt;
         a.X = (const char*)X + (size_t)row0 * ldx * sizeof(T);
-        a.xplane = xplane;
-        a.actplane = actplane;
+        a.xplane = xplane; a.actplane = actplane;
         a.ldx = ldx; a.K = K; a.N = N;
-        a.R = nr;
+        a.R = nr; a.slice_rows = rows;
         a.inv_temp = inv_temp;
-        if (EPI == EPI_PARTIAL) a.out = out + (size_t)row0 * N;            // [split][rows][N], split = 1 if grouped
-        else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ngroups; }
+        if (EPI == EPI_PARTIAL) a.out = out + (size_t)row0 * N;            // [split][rows][N]
+        else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ntiles; }
         else a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
-        int rc = launch_gemm_mt<T, NT, EPI, SPL, WAVES, D>((nr + 15) / 16, dim3(ngroups, split), st, a);
-        if (rc) return rc;
+        gemm_rows_kernel<T, EPI, SPL><<<dim3((ntiles + ROWS_WAVES - 1) / ROWS_WAVES, EPI == EPI_PARTIAL ? split : 1), ROWS_WAVES * 64, 0, st>>>(a, (nr + 15) / 16);
+        LAUNCHCHK("gemm_rows");
     }
     return SJ_OK;
 }
@@ -685,22 +691,24 @@ struct Runner {
     }
     size_t plane(int ld) const { return (size_t)kv->rpad * ld; }
     int partial_gemm(const void* W, const void* X, int ldx, int K, int N, const GemmPlan (&pl)[2]) {
-        const GemmPlan& p = pl[R <= 16 ? 0 : 1];
+        if (R > 16) return gemm_rows<T, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, pl[1].split, kv->part, nullptr, 0, nullptr, 0.f);
+        const GemmPlan& p = pl[0];
         if (p.nt == 3 && p.waves == 8)
             return gemm<T, 3, EPI_PARTIAL, SPL, 8>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
         if (p.nt == 6 && p.waves == 4)
             return gemm<T, 6, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
         // short K-slices (at most 8 k-steps per wave): a deeper register ring puts the whole slice in flight
-        if (R <= 16 && K / Traits<T>::KSTEP / (p.split * 4) <= 8)
+        if (K / Traits<T>::KSTEP / (p.split * 4) <= 8)
             return gemm<T, 4, EPI_PARTIAL, SPL, 4, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
         return gemm<T, 4, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
     }
-    int nparts(const GemmPlan (&pl)[2]) const { return R > 48 ? 1 : pl[R <= 16 ? 0 : 1].split; }
+    int nparts(const GemmPlan (&pl)[2]) const { return pl[R <= 16 ? 0 : 1].split; }
     // gate / up projection with the SwiGLU epilogue: 7 n-tiles per workgroup when that gives a whole
     // number of workgroups per CU (2F/16 = 1792 tiles -> 256 workgroups), else 8
     int gate_up(const void* W) {
         const ModelDims& md = m->md;
-        if (R <= 16 && (2 * md.F / 16) % 7 == 0)
+        if (R > 16) return gemm_rows<T, EPI_SWIGLU, SPL>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
+        if ((2 * md.F / 16) % 7 == 0)
             return gemm<T, 7, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
         return gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
     }
@@ -769,23 +777,27 @@ struct Runner {
         return SJ_OK;
     }
 
-    // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max))
-    template <int LMNT>
-    int lm_head_nt(bool exact_operand) {
+    // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max)).
+    // Hidden states handed in by the caller are already in the storage dtype: one plane suffices then.
+    int lm_head(bool exact_operand) {
         const ModelDims& md = m->md;
-        // hidden states handed in by the caller are already in the storage dtype: one plane suffices
-        int rc = exact_operand
-            ? gemm<T, LMNT, EPI_LOGITS, 1, 4>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
-            : gemm<T, LMNT, EPI_LOGITS, SPL, 4>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
+        int rc, nblk;
+        if (R > 16) {
+            rc = exact_operand
+                ? gemm_rows<T, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
+                : gemm_rows<T, EPI_LOGITS, SPL>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
+            nblk = md.V / 16;
+        } else {
+            rc = exact_operand
+                ? gemm<T, 8, EPI_LOGITS, 1, 4>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
+                : gemm<T, 8, EPI_LOGITS, SPL, 4>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
+            nblk = md.V / 16 / 8;
+        }
         if (rc) return rc;
-        const int nblk = md.V / 16 / LMNT;
         softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, md.inv_temp, kv->rowstat);
         LAUNCHCHK("softmax_merge");
         return SJ_OK;
     }
-    // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max)).  One row
-    // tile: 8 n-tiles per workgroup; more rows: 4 (the statistics layout must be the same for every row group)
-    int lm_head(bool exact_operand) { return R <= 16 ? lm_head_nt<8>(exact_operand) : lm_head_nt<4>(exact_operand); }
 
     // Eq. 3, Eq. 5, scan, extra token, state commit
     int tail(int gamma, const float* row_scale = nullptr) {
