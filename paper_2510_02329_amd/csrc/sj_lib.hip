@@ -306,11 +306,11 @@ static GemmPlan plan_partial(int ntiles, int ksteps, bool one_row_tile) {
     static const int cand[3][2] = {{4, 4}, {3, 8}, {6, 4}};
     GemmPlan best;
     if (!one_row_tile) {
-        // LDS-staged kernel: 8 n-tiles per workgroup, two workgroups per CU; K-slices until the chip is
-        // covered twice, every slice keeping at least 8 k-steps
+        // loader-wave kernel: 8 n-tiles per workgroup, one workgroup per CU; K-slices until the chip is
+        // covered, every slice keeping at least 8 k-steps
         const int groups = (ntiles + 7) / 8;
         best.nt = 8; best.waves = 8; best.split = 1;
-        while (groups * best.split < 512 && best.split < 8 && ksteps / (best.split * 2) >= 8) best.split *= 2;
+        while (groups * best.split < 256 && best.split < 8 && ksteps / (best.split * 2) >= 8) best.split *= 2;
         return best;
     }
     double best_waste = 1e30;
@@ -652,7 +652,7 @@ static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, in
     return SJ_OK;
 }
 
-// More rows: groups of at most 144 rows (9 MFMA row tiles) through the LDS-staged kernel; the statistics
+// More rows: groups of at most 144 rows (9 MFMA row tiles) through the loader-wave kernel; the statistics
 // of EPI_LOGITS are per n-tile there ([rows][N/16]).
 template <typename T, int EPI, int SPL>
 static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
@@ -670,7 +670,7 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
         if (EPI == EPI_PARTIAL) a.out = out + (size_t)row0 * N;            // [split][rows][N]
         else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ntiles; }
         else a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
-        gemm_rows_kernel<T, EPI, SPL><<<dim3((ntiles + ROWS_NT - 1) / ROWS_NT, EPI == EPI_PARTIAL ? split : 1), ROWS_WAVES * 64, 0, st>>>(a, (nr + 15) / 16);
+        gemm_rows2_kernel<T, EPI, SPL><<<dim3((ntiles + R2_NT - 1) / R2_NT, EPI == EPI_PARTIAL ? split : 1), (R2_CW + R2_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
         LAUNCHCHK("gemm_rows");
     }
     return SJ_OK;
