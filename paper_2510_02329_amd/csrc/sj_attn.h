@@ -56,7 +56,7 @@ struct AttnSmem {
             u32x4 q[MQ][KK][SPL][64];       // query fragments in lane order
         } in;
         struct {
-            f32x4 o[4][HT * MQ][64];        // the 4 waves' accumulators in lane order
+            f32x4 o[4][4 * MQ][64];         // the 4 waves' accumulators of 4 head tiles, in lane order
             float m[4][MQ][64];
             float l[4][MQ][64];
         } mg;
@@ -102,20 +102,21 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
     // ---------------- round trip 1: all independent loads, branch-free (indices clamped) --------------
     const int key_lo = chunk * wg_keys + wave * wave_keys;
     const int key_hi = min(key_lo + wave_keys, L);
-    Frag kf[NS][KK], vf[HT];
-    auto load_keys = [&](int key0) {
+    // two register sets of one key step each: the next step is requested before the current one is used
+    Frag kf[2][NS][KK], vf[2][HT];
+    auto load_keys = [&](int set, int key0) {
 #pragma unroll
         for (int t = 0; t < NS; ++t) {
             const int krow = key0 + KF * (r >> 2) + 4 * t + (r & 3);
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk)
-                kf[t][kk].u = *reinterpret_cast<const u32x4*>(Kb + (size_t)krow * HD + kk * KSTEP + g * KF);
+                kf[set][t][kk].u = *reinterpret_cast<const u32x4*>(Kb + (size_t)krow * HD + kk * KSTEP + g * KF);
         }
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
-            vf[ht].u = *reinterpret_cast<const u32x4*>(Vb + (size_t)(ht * 16 + r) * cap + key0 + g * KF);
+            vf[set][ht].u = *reinterpret_cast<const u32x4*>(Vb + (size_t)(ht * 16 + r) * cap + key0 + g * KF);
     };
-    load_keys(min(key_lo, cap - KSTEP));               // capacities are multiples of 64: always inside
+    load_keys(0, min(key_lo, cap - KSTEP));            // capacities are multiples of 64: always inside
 
     // query fragment group gq = (q tile mq, head-dim step kk): 4 split-K partials per batch of loads
     float4 qa[4][KF / 4], qc[4][KF / 4];
@@ -293,7 +294,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
 
     // one step of KSTEP keys held in kf / vf; visible(mq, kidx) says whether query row mq of this lane
     // sees the key with in-step index kidx = KF*g + 4t + i
-    auto consume = [&](auto visible) {
+    auto consume = [&](int set, auto visible) {
         f32x4 s[NS][MQ];
 #pragma unroll
         for (int t = 0; t < NS; ++t)
@@ -303,7 +304,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-                    for (int pl = 0; pl < SPL; ++pl) Traits<T>::mma(kf[t][kk], qf[mq][kk][pl], s[t][mq]);
+                    for (int pl = 0; pl < SPL; ++pl) Traits<T>::mma(kf[set][t][kk], qf[mq][kk][pl], s[t][mq]);
             }
         Frag pf[MQ][SPL];
 #pragma unroll
@@ -341,24 +342,34 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
 #pragma unroll
             for (int mq = 0; mq < MQ; ++mq)
 #pragma unroll
-                for (int pl = 0; pl < SPL; ++pl) Traits<T>::mma(vf[ht], pf[mq][pl], o[ht][mq]);
+                for (int pl = 0; pl < SPL; ++pl) Traits<T>::mma(vf[set][ht], pf[mq][pl], o[ht][mq]);
     };
 
     // ---------------- cached keys of this wave ----------------
-    for (int key0 = key_lo; key0 < key_hi; key0 += KSTEP) {
-        if (key0 != key_lo) load_keys(key0);
+    // one step of the cache from register set `set`; columns of V past the context hold whatever the
+    // cache had: zero them so that 0 * value stays 0
+    auto cached_step = [&](int set, int key0) {
         if (key0 + KSTEP > L) {
-            // the step reaches past the context: those V columns hold whatever the cache had; zero them
-            // so that 0 * value stays 0
 #pragma unroll
             for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
                 for (int e = 0; e < KF; ++e)
                     if (key0 + g * KF + e >= L) {
-                        if constexpr (sizeof(T) == 2) vf[ht].s[e] = 0; else vf[ht].f[e] = 0.f;
+                        if constexpr (sizeof(T) == 2) vf[set][ht].s[e] = 0; else vf[set][ht].f[e] = 0.f;
                     }
         }
-        consume([&](int mq, int kidx) { return rowvalid[mq] && key0 + kidx < L; });
+        consume(set, [&](int mq, int kidx) { return rowvalid[mq] && key0 + kidx < L; });
+    };
+    {
+        int key0 = key_lo;                             // set 0 holds this step
+        while (key0 + KSTEP < key_hi) {                // at least two steps left: no branch around the loads
+            load_keys(1, key0 + KSTEP);
+            cached_step(0, key0);
+            load_keys(0, min(key0 + 2 * KSTEP, cap - KSTEP));   // may lie past this wave's range: in bounds, unused then
+            cached_step(1, key0 + KSTEP);
+            key0 += 2 * KSTEP;
+        }
+        if (key0 < key_hi) cached_step(0, key0);
     }
     ATTN_STAMP(4);
     // ---------------- the block's own rows: row j of the block sees new rows 0..j ----------------
@@ -370,12 +381,12 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
                 const int krow = j0 + KF * (r >> 2) + 4 * t + (r & 3);
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk)
-                    kf[t][kk].u = *reinterpret_cast<const u32x4*>(&sm.in.knew[krow][kk * KSTEP + g * KF]);
+                    kf[0][t][kk].u = *reinterpret_cast<const u32x4*>(&sm.in.knew[krow][kk * KSTEP + g * KF]);
             }
 #pragma unroll
             for (int ht = 0; ht < HT; ++ht)
-                vf[ht].u = *reinterpret_cast<const u32x4*>(&sm.in.vnewT[ht * 16 + r][j0 + g * KF]);
-            consume([&](int mq, int kidx) { return rowvalid[mq] && j0 + kidx <= jrow[mq]; });
+                vf[0][ht].u = *reinterpret_cast<const u32x4*>(&sm.in.vnewT[ht * 16 + r][j0 + g * KF]);
+            consume(0, [&](int mq, int kidx) { return rowvalid[mq] && j0 + kidx <= jrow[mq]; });
         }
     }
 #pragma unroll
@@ -387,36 +398,37 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
     }
     ATTN_STAMP(5);
 
-    // ---------------- merge of the 4 waves through LDS: every wave merges its head tiles -------------
+    // ---------------- merge of the 4 waves through LDS, 4 head tiles per round: wave w merges tile 4h + w ----
     __syncthreads();                    // the input area is dead from here on (same LDS as the merge area)
 #pragma unroll
-    for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-        for (int mq = 0; mq < MQ; ++mq) sm.mg.o[wave][ht * MQ + mq][lane] = o[ht][mq];
-#pragma unroll
     for (int mq = 0; mq < MQ; ++mq) { sm.mg.m[wave][mq][lane] = m_run[mq]; sm.mg.l[wave][mq][lane] = l_run[mq]; }
-    __syncthreads();
     float mw[MQ], lw[MQ];               // merged running max and sum of the workgroup
     f32x4 ow[HPW][MQ];                  // merged accumulators of head tiles wave + 4*hh
 #pragma unroll
-    for (int mq = 0; mq < MQ; ++mq) {
-        float mv[4], f[4];
-        float mn = -INFINITY;
+    for (int hh = 0; hh < HPW; ++hh) {
+        if (hh > 0) __syncthreads();    // everyone has read the previous round
 #pragma unroll
-        for (int w = 0; w < 4; ++w) { mv[w] = sm.mg.m[w][mq][lane]; mn = fmaxf(mn, mv[w]); }
-        float l = 0.f;
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            f[w] = (mv[w] == -INFINITY) ? 0.f : __expf(mv[w] - mn);
-            l += f[w] * sm.mg.l[w][mq][lane];
-        }
-        mw[mq] = mn;
-        lw[mq] = l;
+            for (int mq = 0; mq < MQ; ++mq) sm.mg.o[wave][j * MQ + mq][lane] = o[4 * hh + j][mq];
+        __syncthreads();
 #pragma unroll
-        for (int hh = 0; hh < HPW; ++hh) {
+        for (int mq = 0; mq < MQ; ++mq) {
+            float mv[4], f[4];
+            float mn = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { mv[w] = sm.mg.m[w][mq][lane]; mn = fmaxf(mn, mv[w]); }
+            float l = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                f[w] = (mv[w] == -INFINITY) ? 0.f : __expf(mv[w] - mn);
+                l += f[w] * sm.mg.l[w][mq][lane];
+            }
+            mw[mq] = mn;
+            lw[mq] = l;
             f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int w = 0; w < 4; ++w) acc += sm.mg.o[w][(wave + 4 * hh) * MQ + mq][lane] * f[w];
+            for (int w = 0; w < 4; ++w) acc += sm.mg.o[w][wave * MQ + mq][lane] * f[w];
             ow[hh][mq] = acc;
         }
     }
