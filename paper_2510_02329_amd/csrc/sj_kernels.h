@@ -494,7 +494,17 @@ __global__ __launch_bounds__(256) void resample_e_kernel(const StepParams* __res
     const float* l = a.logits + (size_t)row * a.V;
     const int k0 = slab * a.slab_len, k1 = min(a.V, k0 + a.slab_len);
     double s = 0.0;
-    for (int k = k0; k < k1; ++k) s += e_of(l[k], mx, a.inv_temp);
+    if (((a.slab_len | a.V) & 3) == 0) {               // 16-byte loads; same summation order
+        for (int k = k0; k < k1; k += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(l + k);
+            s += e_of(v.x, mx, a.inv_temp);
+            s += e_of(v.y, mx, a.inv_temp);
+            s += e_of(v.z, mx, a.inv_temp);
+            s += e_of(v.w, mx, a.inv_temp);
+        }
+    } else {
+        for (int k = k0; k < k1; ++k) s += e_of(l[k], mx, a.inv_temp);
+    }
     a.epart[(size_t)bi * a.nslab + slab] = s;
 }
 
@@ -517,7 +527,18 @@ __global__ __launch_bounds__(256) void resample_w_kernel(const StepParams* __res
     double s = 0.0;
     if (n < gamma) {
         const float* q = sp->draft_probs + ((size_t)bi * gamma + n) * a.V;
-        for (int k = k0; k < k1; ++k) s += fmax(0.0, e_of(l[k], mx, a.inv_temp) - Z * (double)q[k]);
+        if (((a.slab_len | a.V) & 3) == 0 && (reinterpret_cast<uintptr_t>(q) & 15) == 0) {   // 16-byte loads; same order
+            for (int k = k0; k < k1; k += 4) {
+                const float4 v = *reinterpret_cast<const float4*>(l + k);
+                const float4 u = *reinterpret_cast<const float4*>(q + k);
+                s += fmax(0.0, e_of(v.x, mx, a.inv_temp) - Z * (double)u.x);
+                s += fmax(0.0, e_of(v.y, mx, a.inv_temp) - Z * (double)u.y);
+                s += fmax(0.0, e_of(v.z, mx, a.inv_temp) - Z * (double)u.z);
+                s += fmax(0.0, e_of(v.w, mx, a.inv_temp) - Z * (double)u.w);
+            }
+        } else {
+            for (int k = k0; k < k1; ++k) s += fmax(0.0, e_of(l[k], mx, a.inv_temp) - Z * (double)q[k]);
+        }
     }
     a.wpart[(size_t)bi * a.nslab + slab] = s;
 }
@@ -527,6 +548,7 @@ __global__ __launch_bounds__(256) void resample_pick_kernel(const StepParams* __
     __shared__ double red[4];
     __shared__ double wave_tot[4];
     __shared__ double before_of[257];
+    __shared__ double slab_w[256];
     __shared__ int hit_slab;
     __shared__ double hit_before;
     const int bi = blockIdx.x;
@@ -584,20 +606,26 @@ __global__ __launch_bounds__(256) void resample_pick_kernel(const StepParams* __
             hit_before = hb;
         }
         __syncthreads();
+        const float mx = st.x;
+        const float* l = a.logits + (size_t)row * a.V;
+        const float* q = (n < gamma) ? sp->draft_probs + ((size_t)bi * gamma + n) * a.V : nullptr;
+        auto weight = [&](int k) {
+            const double e = e_of(l[k], mx, a.inv_temp);
+            return use_e ? e : fmax(0.0, e - Z * (double)q[k]);
+        };
+        // the weights of the slab that holds the target, one per thread (slabs of up to 256 entries),
+        // then scanned in vocabulary order by one thread
+        const bool have_slab = (owner != 0x7fffffff && hit_slab >= 0);
+        const int hk0 = have_slab ? hit_slab * a.slab_len : 0, hk1 = have_slab ? min(a.V, hk0 + a.slab_len) : 0;
+        const bool staged = have_slab && a.slab_len <= 256;
+        if (staged && hk0 + (int)threadIdx.x < hk1) slab_w[threadIdx.x] = weight(hk0 + threadIdx.x);
+        __syncthreads();
         if (threadIdx.x == 0) {
-            const float mx = st.x;
-            const float* l = a.logits + (size_t)row * a.V;
-            const float* q = (n < gamma) ? sp->draft_probs + ((size_t)bi * gamma + n) * a.V : nullptr;
-            auto weight = [&](int k) {
-                const double e = e_of(l[k], mx, a.inv_temp);
-                return use_e ? e : fmax(0.0, e - Z * (double)q[k]);
-            };
-            if (owner != 0x7fffffff && hit_slab >= 0) {
-                const int k0 = hit_slab * a.slab_len, k1 = min(a.V, k0 + a.slab_len);
+            if (have_slab) {
                 double c = hit_before;
                 int last_pos = -1;
-                for (int k = k0; k < k1; ++k) {
-                    const double v = weight(k);
+                for (int k = hk0; k < hk1; ++k) {
+                    const double v = staged ? slab_w[k - hk0] : weight(k);
                     if (v > 0.0) last_pos = k;
                     c += v;
                     if (c > target) { next = k; break; }

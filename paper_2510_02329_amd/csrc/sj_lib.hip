@@ -364,8 +364,8 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
 #define ALLOC(ptr, bytes) if ((rc = dev_alloc(A, &(ptr), (bytes)))) return bail(rc)
     ALLOC(kv->seq_off_dev, sizeof(int64_t) * batch);
     ALLOC(kv->cap_dev, sizeof(int32_t) * batch);
-    ALLOC(kv->len_dev, sizeof(int32_t) * batch);
-    ALLOC(kv->pending_dev, sizeof(int32_t) * batch);
+    ALLOC(kv->len_dev, sizeof(int32_t) * 2 * batch);           // lengths, then pending tokens: one copy rewinds both
+    kv->pending_dev = kv->len_dev + batch;
     ALLOC(kv->sp_dev, sizeof(StepParams));
     ALLOC(kv->xn, (size_t)3 * kv->rpad * d * m->esz);          // up to three operand planes
     ALLOC(kv->hn32, (size_t)R * d * 4);
@@ -475,8 +475,7 @@ extern "C" int sj_kv_rewind(sj_kv* kv, const int32_t* len_host, const int32_t* p
     if (kv->rewind_pending) HIPCHK(hipEventSynchronize(kv->rewind_done));   // staging still being read
     std::memcpy(kv->pinned_state, len_host, sizeof(int32_t) * kv->batch);
     std::memcpy(kv->pinned_state + kv->batch, pending_host, sizeof(int32_t) * kv->batch);
-    HIPCHK(hipMemcpyAsync(kv->len_dev, kv->pinned_state, sizeof(int32_t) * kv->batch, hipMemcpyHostToDevice, st));
-    HIPCHK(hipMemcpyAsync(kv->pending_dev, kv->pinned_state + kv->batch, sizeof(int32_t) * kv->batch, hipMemcpyHostToDevice, st));
+    HIPCHK(hipMemcpyAsync(kv->len_dev, kv->pinned_state, sizeof(int32_t) * 2 * kv->batch, hipMemcpyHostToDevice, st));
     HIPCHK(hipEventRecord(kv->rewind_done, st));
     kv->rewind_pending = true;
     for (int b = 0; b < kv->batch; ++b) kv->len_upper[b] = len_host[b];
