@@ -103,6 +103,28 @@ def test_small_gqa_bf16_two_steps(theta):
         gpu.close()
 
 
+@pytest.mark.parametrize("batch,gamma,lens", [
+    (3, 7, [70, 200, 333]),                                        # 24 rows: two row tiles
+    (10, 15, [0, 33, 1500, 64, 129, 700, 31, 32, 255, 1024]),      # 160 rows: two launches of the many-row
+])                                                                 # GEMM; empty, one-step and 12-range contexts
+def test_small_gqa_bf16_many_rows(batch, gamma, lens):
+    """More than 16 query rows (the LDS-staged projections), contexts from empty to many key ranges
+    (several key steps per wave, the ticketed merge in more than one batch)."""
+    import dataclasses
+    shape = dataclasses.replace(SMALL, name=f"small_bf16_b{batch}_g{gamma}", batch=batch, gamma=gamma)
+    src = synth.WeightSource(shape, seed=3, norm_jitter=0.1, judge_bias=0.2)
+    cap = [max(64, l + gamma + 1 + 17) for l in lens]
+    gpu = G.Gpu(shape, src, cap)
+    try:
+        cfg = helpers.oracle_config(shape)
+        W = helpers.oracle_weights(src)
+        caches = _fill_caches(shape, gpu, cfg, lens, seed=4, capacity=cap)
+        draft = synth.make_draft(shape, seed=40)
+        _compare_step(shape, gpu, cfg, W, caches, draft, 0.5, f"rows {batch * (gamma + 1)}")
+    finally:
+        gpu.close()
+
+
 def test_llama8b_batch1_full_size():
     """The benchmark workload: 32 layers, d 4096, 32/8 heads of 128, FFN 14336, vocab 128256, cache 1024,
     gamma 5, in the launch configuration bench.py times.  The oracle runs the whole step in fp64."""
