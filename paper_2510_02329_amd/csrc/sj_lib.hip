@@ -93,7 +93,7 @@ struct sj_kv {
     int32_t *row_tok = nullptr, *bits = nullptr, *nacc = nullptr, *prefill_tok = nullptr;
     double *epart = nullptr, *wpart = nullptr;
     int chunk_keys = 64, nchunk_max = 1, nslab = 0, slab_len = 0;
-    GemmPlan plan_qkv[2], plan_o[2], plan_d[2];   // [0]: at most 16 rows, [1]: more
+    GemmPlan plan_qkv[2], plan_o[2], plan_d[2];   // [0]: few-row kernel (at most 32 rows), [1]: more
     int lm_nt = 2;
     int mode = SJ_MODE_TWO_STAGE;
     int planes = 2;            // bf16 planes of the activation operand (fp32 storage: always 1)
@@ -635,20 +635,25 @@ extern "C" int sj_kv_state(const sj_kv* kv, int32_t* len_host, int32_t* pending_
 // ------------------------------------------------------------------------------------------------
 // kernel sequence
 
-// Few rows (at most 16): Y = X W^T with the few-row kernel.  X has SPL planes `xplane` elements apart;
-// act (EPI_SWIGLU) planes are `actplane` apart.  NT n-tiles per workgroup (N/16 must be a multiple
-// of NT), WAVES waves split the K-slice, D = depth of the register ring.
+// Few rows (at most 32 = two MFMA row tiles): Y = X W^T with the few-row kernel.  X has SPL planes `xplane`
+// elements apart; act (EPI_SWIGLU) planes are `actplane` apart.  NT n-tiles per workgroup (N/16 must be a
+// multiple of NT), WAVES waves split the K-slice, D = depth of the register ring.
+// up to two row tiles the few-row kernel (every wave fetches its own operand fragments) is the faster
+// one (gate/up of the 70B shape at 24 rows: 179 us against 262 us); from three on the loader-wave kernel
+constexpr int FEW_ROWS = 32;
+
 template <typename T, int NT, int EPI, int SPL, int WAVES, int D = 2>
 static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
                 float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
-    if (rows > 16) return fail(SJ_EINVAL, "internal: few-row kernel called with %d rows", rows);
+    if (rows > FEW_ROWS) return fail(SJ_EINVAL, "internal: few-row kernel called with %d rows", rows);
     const int ngroups = N / 16 / NT;
     GemmArgs a{};
     a.Wt = Wt; a.X = X; a.xplane = xplane; a.actplane = actplane;
     a.ldx = ldx; a.K = K; a.N = N; a.R = rows; a.slice_rows = rows;
     a.inv_temp = inv_temp;
     a.out = out; a.stats = stats; a.act = act;
-    gemm_skinny_kernel<T, NT, 1, EPI, SPL, WAVES, D><<<dim3(ngroups, split), WAVES * 64, 0, st>>>(a);
+    if (rows <= 16) gemm_skinny_kernel<T, NT, 1, EPI, SPL, WAVES, D><<<dim3(ngroups, split), WAVES * 64, 0, st>>>(a);
+    else gemm_skinny_kernel<T, NT, 2, EPI, SPL, WAVES, D><<<dim3(ngroups, split), WAVES * 64, 0, st>>>(a);
     LAUNCHCHK("gemm_skinny");
     return SJ_OK;
 }
@@ -692,7 +697,7 @@ struct Runner {
     }
     size_t plane(int ld) const { return (size_t)kv->rpad * ld; }
     int partial_gemm(const void* W, const void* X, int ldx, int K, int N, const GemmPlan (&pl)[2]) {
-        if (R > 16) return gemm_rows<T, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, pl[1].split, kv->part, nullptr, 0, nullptr, 0.f);
+        if (R > FEW_ROWS) return gemm_rows<T, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, pl[1].split, kv->part, nullptr, 0, nullptr, 0.f);
         const GemmPlan& p = pl[0];
         if (p.nt == 3 && p.waves == 8)
             return gemm<T, 3, EPI_PARTIAL, SPL, 8>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
@@ -703,12 +708,12 @@ struct Runner {
             return gemm<T, 4, EPI_PARTIAL, SPL, 4, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
         return gemm<T, 4, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
     }
-    int nparts(const GemmPlan (&pl)[2]) const { return pl[R <= 16 ? 0 : 1].split; }
+    int nparts(const GemmPlan (&pl)[2]) const { return pl[R <= FEW_ROWS ? 0 : 1].split; }
     // gate / up projection with the SwiGLU epilogue: 7 n-tiles per workgroup when that gives a whole
     // number of workgroups per CU (2F/16 = 1792 tiles -> 256 workgroups), else 8
     int gate_up(const void* W) {
         const ModelDims& md = m->md;
-        if (R > 16) return gemm_rows<T, EPI_SWIGLU, SPL>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
+        if (R > FEW_ROWS) return gemm_rows<T, EPI_SWIGLU, SPL>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
         if ((2 * md.F / 16) % 7 == 0)
             return gemm<T, 7, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
         return gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
@@ -783,7 +788,7 @@ struct Runner {
     int lm_head(bool exact_operand) {
         const ModelDims& md = m->md;
         int rc, nblk;
-        if (R > 16) {
+        if (R > FEW_ROWS) {
             rc = exact_operand
                 ? gemm_rows<T, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
                 : gemm_rows<T, EPI_LOGITS, SPL>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
