@@ -138,6 +138,23 @@ int sj_verify_step(sj_model* m, sj_kv* kv, int32_t gamma, const int32_t* draft_t
                    const float* draft_probs, const float* uniforms, float judge_threshold,
                    int32_t* accepted_len, int32_t* next_token, void* stream);
 
+/* Draft proposal (Sec. 2.2, Eq. 1): gamma sequential single-token decodes of a DRAFT model m for every
+ * sequence of the batch, producing exactly what sj_verify_step of the target consumes.  Step j feeds
+ * the sequence's pending token at position len, appends its K/V, forms q_j = softmax(logits / T) of that
+ * row, draws d_{j+1} from q_j by inverse CDF in vocabulary order with uniforms[j][b] (the rule of the
+ * extra token of sj_verify_step), makes it the pending token and advances len by 1.
+ *   uniforms      device float [gamma, batch]        in [0,1), step-major
+ *   feed_last     non-zero: after the last draw the layers (no LM head) also run on d_gamma, so the cache
+ *                 holds a row for every drafted token and any accepted length can be kept by length alone
+ *   draft_tokens  device int32 [batch, gamma]        out
+ *   draft_probs   device float [batch, gamma, vocab] out, fp32 probabilities (one-hot at T = 0)
+ * Effects: len += gamma (+1 with feed_last), pending = d_gamma.  After the target's verification accepted n
+ * tokens and emitted e, the caller sets the draft cache to len0 + 1 + n, pending e (sj_kv_set_state /
+ * sj_kv_rewind): rows beyond the new length are dead.  m is any model with the target's vocabulary.
+ * Errors: SJ_EINVAL (null, gamma outside 1..63, head-only model), SJ_ECAPACITY. */
+int sj_draft_block(sj_model* m, sj_kv* kv, int32_t gamma, const float* uniforms, int32_t feed_last,
+                   int32_t* draft_tokens, float* draft_probs, void* stream);
+
 /* The verification tail alone (LM head, softmax, Eq. 3, Eq. 5, scan, resampling) on given final
  * hidden states: hidden = device [batch*(gamma+1), d_model] in the storage dtype, already
  * RMS-normed, row b*(gamma+1)+j = block row j of sequence b.  No cache is read or written; kv

@@ -18,6 +18,8 @@ and "Judge Verification"):
   * judge test (Eq. 5): accept d_t iff Verifier(h_t) > theta, Verifier = logistic regression.
   * a token is kept if either test approves it (Sec. 3.2, App. D.2); tokens are accepted in
     order until the first rejection (Sec. 3.1).
+  * the draft proposal that feeds the cycle (Eq. 1): gamma sequential single-token decodes of the
+    draft model, each drawing d from its own next-token law q (`draft_block`).
   * one more token is emitted: from the last distribution p_{t+gamma+1} if everything was
     accepted (Sec. 3.1, text after Eq. 2), otherwise from the residual distribution
     norm(max(0, p - q)) of "modified rejection sampling" (Sec. 2.2), which is the choice that
@@ -310,6 +312,33 @@ def verify_step(cfg: OracleConfig, W: WeightFn, caches: Sequence[SeqCache],
         cache.pending = res["next_token"]
         results.append(res)
     return results
+
+
+def draft_block(cfg: OracleConfig, W: WeightFn, caches: Sequence[SeqCache], gamma: int,
+                uniforms: np.ndarray, feed_last: bool = True):
+    """Draft proposal (Sec. 2.2, Eq. 1): the draft model M_q generates gamma tokens one at a time,
+    d_{t+i} ~ q(. | x_<=t, d_{t+1..t+i-1}).  cfg / W / caches are the DRAFT model's.  Step j reads the
+    pending token (R8), takes q_j = softmax(logits / T) of that one row (R6 at T = 0), draws d_{j+1} by
+    the inverse-CDF rule R5 with uniforms[j][b], and the drawn token becomes the pending one.
+    feed_last: the last drafted token is also run through the layers, so the cache ends with a row for
+    every drafted token.  Returns tokens [B, gamma] and probs [B, gamma, V]; commits every cache."""
+    B = len(caches)
+    tokens = np.zeros((B, gamma), dtype=np.int64)
+    probs = np.zeros((B, gamma, cfg.vocab), F64)
+    for j in range(gamma):
+        fw = block_forward(cfg, W, caches, [[c.pending] for c in caches])
+        for b, c in enumerate(caches):
+            q = target_distribution(fw[b]["logits"][0], cfg.temperature)
+            d = draw(q, float(uniforms[j][b]))
+            probs[b, j] = q
+            tokens[b, j] = d
+            c.length += 1
+            c.pending = d
+    if feed_last:
+        block_forward(cfg, W, caches, [[c.pending] for c in caches], want_logits=False)
+        for c in caches:
+            c.length += 1
+    return tokens, probs
 
 
 def prefill(cfg: OracleConfig, W: WeightFn, cache: SeqCache, tokens: Sequence[int]) -> int:

@@ -65,6 +65,7 @@ def load_library() -> C.CDLL:
         "sj_prefill": (C.c_int, [vp, vp, i32, C.POINTER(i32), i32, vp]),
         "sj_verify_step": (C.c_int, [vp, vp, i32, vp, vp, vp, f32, vp, vp, vp]),
         "sj_verify_head": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, f32, vp, vp, vp]),
+        "sj_draft_block": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, vp]),
         "sj_set_mode": (C.c_int, [vp, i32]),
         "sj_set_operand_planes": (C.c_int, [vp, i32]),
         "sj_kv_rewind": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
@@ -199,6 +200,11 @@ def sj_verify_head(model: int, kv: int, gamma: int, hidden, draft_tokens, draft_
     _check(load_library().sj_verify_head(model, kv, gamma, _ptr(hidden), _ptr(draft_tokens), _ptr(draft_probs),
                                          _ptr(uniforms), float(judge_threshold), _ptr(accepted_len), _ptr(next_token),
                                          _stream(stream)))
+
+
+def sj_draft_block(model: int, kv: int, gamma: int, uniforms, feed_last: bool, draft_tokens, draft_probs, stream=None) -> None:
+    _check(load_library().sj_draft_block(model, kv, gamma, _ptr(uniforms), 1 if feed_last else 0, _ptr(draft_tokens),
+                                         _ptr(draft_probs), _stream(stream)))
 
 
 def sj_set_mode(kv: int, mode: int) -> None:

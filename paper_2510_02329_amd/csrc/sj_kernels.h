@@ -646,6 +646,30 @@ __global__ __launch_bounds__(256) void resample_pick_kernel(const StepParams* __
     }
 }
 
+// Draft proposal (Eq. 1), output of one single-row decode: the row's next-token law q = softmax(l / T)
+// as fp32 probabilities into column j of draft_probs [nseq][gamma][V], and the token just drawn from it
+// (the sequence's new pending token) into draft_tokens [nseq][gamma].  T = 0: one-hot at the arg-max.
+__global__ __launch_bounds__(256) void draft_emit_kernel(int V, float inv_temp, const float* __restrict__ logits,
+                                                         const float4* __restrict__ rowstat,
+                                                         const int32_t* __restrict__ pending, int seq_base, int gamma, int j,
+                                                         int32_t* __restrict__ draft_tokens, float* __restrict__ draft_probs) {
+    const int bi = blockIdx.y;
+    const float4 st = rowstat[bi];
+    const float* l = logits + (size_t)bi * V;
+    float* q = draft_probs + ((size_t)bi * gamma + j) * V;
+    const float invz = 1.0f / st.y;
+    const int arg = __float_as_int(st.z);
+    for (int k = blockIdx.x * 256 + threadIdx.x; k < V; k += gridDim.x * 256)
+        q[k] = (inv_temp > 0.f) ? expf((l[k] - st.x) * inv_temp) * invz : (k == arg ? 1.f : 0.f);
+    if (blockIdx.x == 0 && threadIdx.x == 0) draft_tokens[bi * gamma + j] = pending[seq_base + bi];
+}
+
+// the cache rows of this call are kept: advance every sequence's length by rps
+__global__ void advance_len_kernel(const StepParams* __restrict__ sp, int32_t* __restrict__ len) {
+    const int bi = blockIdx.x * blockDim.x + threadIdx.x;
+    if (bi < sp->nseq) len[sp->seq_base + bi] += sp->rps;
+}
+
 // Prefill bookkeeping: advance the length by the chunk; after the last chunk the pending token is the
 // arg-max continuation of the last prompt token.
 __global__ void prefill_commit_kernel(const StepParams* __restrict__ sp, const float4* __restrict__ rowstat,

@@ -90,7 +90,7 @@ struct sj_kv {
     void *xn = nullptr, *attn_out = nullptr, *act = nullptr;
     unsigned* tickets = nullptr;
     float4 *stats = nullptr, *rowstat = nullptr;
-    int32_t *row_tok = nullptr, *bits = nullptr, *nacc = nullptr, *prefill_tok = nullptr;
+    int32_t *row_tok = nullptr, *bits = nullptr, *nacc = nullptr, *prefill_tok = nullptr, *draft_tok = nullptr;
     double *epart = nullptr, *wpart = nullptr;
     int chunk_keys = 64, nchunk_max = 1, nslab = 0, slab_len = 0;
     GemmPlan plan_qkv[2], plan_o[2], plan_d[2];   // [0]: few-row kernel (at most 32 rows), [1]: more
@@ -378,6 +378,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     ALLOC(kv->p_at_d, (size_t)R * 4);
     ALLOC(kv->bits, (size_t)R * 4);
     ALLOC(kv->nacc, (size_t)batch * 4);
+    ALLOC(kv->draft_tok, (size_t)batch * 4);
     // resampling slabs: about 16 vocabulary entries per thread
     {
         int blocks = std::max(1, (V / 16 + 255) / 256);
@@ -808,8 +809,10 @@ struct Runner {
     // Eq. 3, Eq. 5, scan, extra token, state commit
     int tail(int gamma, const float* row_scale = nullptr) {
         const ModelDims& md = m->md;
-        judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, row_scale, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores);
-        LAUNCHCHK("judge");
+        if (gamma > 0) {                                   // gamma = 0: a plain decode step (draft proposal)
+            judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, row_scale, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores);
+            LAUNCHCHK("judge");
+        }
         accept_scan_kernel<<<nseq, 64, 0, st>>>(kv->sp_dev, md.V, md.inv_temp, kv->logits, kv->rowstat, kv->scores, kv->p_at_d,
                                                  kv->bits, kv->nacc);
         LAUNCHCHK("accept_scan");
@@ -1111,6 +1114,61 @@ extern "C" int sj_verify_step(sj_model* m, sj_kv* kv, int32_t gamma, const int32
     for (int b = 0; b < kv->batch; ++b) kv->len_upper[b] += gamma + 1;
     kv->last_gamma = gamma;
     kv->last_rows = kv->batch * (gamma + 1);
+    return SJ_OK;
+}
+
+// Layers only (no LM head, no decisions) over one row per sequence, then the rows are kept.
+template <typename T, int SPL>
+static int feed_pending_impl(sj_model* m, sj_kv* kv, hipStream_t st) {
+    Runner<T, SPL> run{m, kv, st, kv->batch, 1, kv->batch};
+    int rc = run.layers();
+    if (rc) return rc;
+    advance_len_kernel<<<(kv->batch + 63) / 64, 64, 0, st>>>(kv->sp_dev, kv->len_dev);
+    LAUNCHCHK("advance_len");
+    return SJ_OK;
+}
+
+extern "C" int sj_draft_block(sj_model* m, sj_kv* kv, int32_t gamma, const float* uniforms, int32_t feed_last,
+                              int32_t* draft_tokens, float* draft_probs, void* stream) {
+    if (!m || !kv) return fail(SJ_EINVAL, "model / kv is null");
+    if (kv->m != m) return fail(SJ_EINVAL, "kv was created for a different model");
+    if (gamma < 1 || gamma > 63) return fail(SJ_EINVAL, "gamma %d outside 1..63", gamma);
+    if (!uniforms || !draft_tokens || !draft_probs) return fail(SJ_EINVAL, "null device pointer argument");
+    if (m->cfg.n_layers == 0) return fail(SJ_EINVAL, "head-only model has no decode loop");
+    const int need = gamma + (feed_last ? 1 : 0);
+    int rc = refresh_lengths(kv);
+    if (rc) return rc;
+    for (int b = 0; b < kv->batch; ++b)
+        if (kv->len_upper[b] + need > kv->cap[b])
+            return fail(SJ_ECAPACITY, "sequence %d: len %d + %d rows exceeds capacity %d", b, kv->len_upper[b], need, kv->cap[b]);
+    hipStream_t st = (hipStream_t)stream;
+    const int V = m->cfg.vocab;
+    for (int j = 0; j < gamma; ++j) {
+        // one decode step = a verification step without draft tokens: the "all accepted" token is drawn from
+        // the row's distribution with the step's uniform and becomes the pending token; length += 1
+        StepParams p{};
+        p.nseq = kv->batch; p.seq_base = 0; p.rps = 1; p.gamma = 0; p.tok_mode = 0; p.mode = kv->mode;
+        p.theta = 0.5f;
+        p.draft_tokens = nullptr; p.draft_probs = nullptr; p.uniforms = uniforms + (size_t)j * kv->batch;
+        p.accepted_len = kv->nacc; p.next_token = kv->draft_tok;   // scratch: the token is read back from the state
+        if ((rc = dispatch_step(m, kv, 0, p, st, false, nullptr))) return rc;
+        draft_emit_kernel<<<dim3(std::min(64, (V + 255) / 256), kv->batch), 256, 0, st>>>(V, m->md.inv_temp, kv->logits, kv->rowstat,
+                                                                                          kv->pending_dev, 0, gamma, j, draft_tokens, draft_probs);
+        LAUNCHCHK("draft_emit");
+    }
+    if (feed_last) {
+        StepParams p{};
+        p.nseq = kv->batch; p.seq_base = 0; p.rps = 1; p.gamma = 0; p.tok_mode = 0; p.mode = kv->mode;
+        if ((rc = set_params(kv, st, p))) return rc;
+        if (m->cfg.dtype == SJ_DTYPE_FP32) rc = feed_pending_impl<float, 1>(m, kv, st);
+        else if (kv->planes == 1) rc = feed_pending_impl<bf16_t, 1>(m, kv, st);
+        else if (kv->planes == 3) rc = feed_pending_impl<bf16_t, 3>(m, kv, st);
+        else rc = feed_pending_impl<bf16_t, 2>(m, kv, st);
+        if (rc) return rc;
+    }
+    for (int b = 0; b < kv->batch; ++b) kv->len_upper[b] += need;
+    kv->last_gamma = 0;
+    kv->last_rows = kv->batch;
     return SJ_OK;
 }
 

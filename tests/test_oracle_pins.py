@@ -431,3 +431,96 @@ def test_verify_step_commits_length_and_pending():
     w = t[("judge_w", -1)]
     expect = 1 / (1 + np.exp(-(fw["hn"][1:] @ w)))
     assert np.allclose(res["judge_scores"], expect, atol=1e-12)
+
+
+# ------------------------------------------------------------------ P8: draft proposal (Eq. 1)
+# The draft block is gamma single-token decodes.  Pinned against things it does not compute itself:
+# a from-scratch forward of the whole sequence (positions, caching, which token is fed), the verification
+# step of an identical target (p = q makes the ratio test of Eq. 3 accept everything), the greedy
+# continuation at temperature 0, and the exact law of the first draw.
+
+
+def _from_scratch_logits(cfg, W, prefix_cache_seed, L, fed):
+    """Logits of every fed token when the whole run is one block on a fresh copy of the cache."""
+    c = helpers.random_cache(cfg, L, 64, seed=prefix_cache_seed)
+    return orc.block_forward(cfg, W, [c], [list(fed)])[0]["logits"]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_draft_block_rows_equal_from_scratch_forward(seed):
+    shape, cfg, t = _tiny(seed)
+    W = helpers.dict_weights(t)
+    L, gamma = 5, 4
+    cache = helpers.random_cache(cfg, L, 64, seed=11)
+    pend0 = cache.pending
+    u = np.random.default_rng(seed).random((gamma, 1))
+    toks, probs = orc.draft_block(cfg, W, [cache], gamma, u, feed_last=True)
+    fed = [pend0] + [int(x) for x in toks[0]]                     # the tokens that entered the model, in order
+    logits = _from_scratch_logits(cfg, W, 11, L, fed)
+    for j in range(gamma):
+        z = logits[j] / cfg.temperature
+        e = np.exp(z - z.max())
+        assert np.allclose(probs[0, j], e / e.sum(), atol=1e-12)   # q_j is the law after j drafted tokens
+        assert abs(probs[0, j].sum() - 1.0) < 1e-12
+        c = np.cumsum(probs[0, j])                                  # R5: smallest k with cdf > u
+        assert c[toks[0, j]] > u[j, 0] * c[-1] and (toks[0, j] == 0 or c[toks[0, j] - 1] <= u[j, 0] * c[-1])
+    assert cache.length == L + gamma + 1 and cache.pending == int(toks[0, -1])
+    # the cache rows are those of the from-scratch block (all gamma + 1 fed tokens with feed_last)
+    c2 = helpers.random_cache(cfg, L, 64, seed=11)
+    orc.block_forward(cfg, W, [c2], [fed])
+    for l in range(cfg.n_layers):
+        assert np.allclose(cache.k[l][:, :L + gamma + 1], c2.k[l][:, :L + gamma + 1], atol=1e-12)
+        assert np.allclose(cache.v[l][:, :L + gamma + 1], c2.v[l][:, :L + gamma + 1], atol=1e-12)
+    # without feed_last the last drafted token has no row yet
+    cache3 = helpers.random_cache(cfg, L, 64, seed=11)
+    toks3, _ = orc.draft_block(cfg, W, [cache3], gamma, u, feed_last=False)
+    assert (toks3 == toks).all() and cache3.length == L + gamma
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_identical_draft_and_target_accept_every_token(seed):
+    """p = q: u * q < p holds for every u in [0, 1) wherever q > 0, so the alignment test alone keeps all
+    gamma tokens, whatever the uniforms (Sec. 2.2: the acceptance rate is sum min(p, q) = 1)."""
+    shape, cfg, t = _tiny(seed)
+    W = helpers.dict_weights(t)
+    L, gamma, B = 6, 5, 2
+    rng = np.random.default_rng(100 + seed)
+    draft_caches = [helpers.random_cache(cfg, L + b, 64, seed=20 + b) for b in range(B)]
+    target_caches = [helpers.random_cache(cfg, L + b, 64, seed=20 + b) for b in range(B)]
+    toks, probs = orc.draft_block(cfg, W, draft_caches, gamma, rng.random((gamma, B)), feed_last=True)
+    res = orc.verify_step(cfg, W, target_caches, toks, probs, rng.random((B, gamma + 1)), theta=0.5, mode="alignment")
+    for b in range(B):
+        assert res[b]["accepted_len"] == gamma
+        # both caches now describe the same accepted prefix once the draft's is cut to len0 + 1 + n
+        assert target_caches[b].length == L + b + 1 + gamma == draft_caches[b].length
+        for l in range(cfg.n_layers):
+            n = target_caches[b].length
+            assert np.allclose(draft_caches[b].k[l][:, :n], target_caches[b].k[l][:, :n], atol=1e-11)
+
+
+def test_draft_block_is_greedy_at_temperature_zero():
+    shape, cfg, t = _tiny(5, temperature=0.0)
+    W = helpers.dict_weights(t)
+    L, gamma = 4, 5
+    cache = helpers.random_cache(cfg, L, 64, seed=31)
+    pend0 = cache.pending
+    toks, probs = orc.draft_block(cfg, W, [cache], gamma, np.random.default_rng(0).random((gamma, 1)))
+    logits = _from_scratch_logits(cfg, W, 31, L, [pend0] + [int(x) for x in toks[0]])
+    assert [int(np.argmax(logits[j])) for j in range(gamma)] == [int(x) for x in toks[0]]
+    assert all(probs[0, j, toks[0, j]] == 1.0 and probs[0, j].sum() == 1.0 for j in range(gamma))
+
+
+def test_first_draft_token_follows_q_exactly():
+    """Exhaustive over a grid of uniforms (midpoints of N equal cells): the share of the grid that draws token
+    k is q_k up to one cell per token."""
+    shape, cfg, t = _tiny(7)
+    W = helpers.dict_weights(t)
+    N = 4000
+    counts = np.zeros(cfg.vocab)
+    q = None
+    for i in range(N):
+        cache = helpers.random_cache(cfg, 3, 16, seed=41)
+        toks, probs = orc.draft_block(cfg, W, [cache], 1, np.array([[(i + 0.5) / N]]), feed_last=False)
+        counts[toks[0, 0]] += 1
+        q = probs[0, 0]
+    assert np.abs(counts / N - q).max() <= 1.0 / N + 1e-12
