@@ -119,6 +119,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--cycle", action="store_true",
+                    help="also time the whole speculate -> verify cycle: a 1B-shaped draft model proposes gamma tokens "
+                         "(sj_draft_block), the target verifies them; adds a \"cycle\" object to the JSON line")
     ap.add_argument("--theta", type=float, default=0.5)
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
@@ -212,6 +215,53 @@ def main() -> int:
             if "traffic_bytes_per_launch:" in line:
                 traffic = int(line.split("traffic_bytes_per_launch:")[1].split()[0])
 
+    cycle = None
+    if args.cycle:
+        import dataclasses
+        dshape = dataclasses.replace(synth.DRAFT_1B, batch=B, gamma=gamma, kv_len=shape.kv_len, vocab=shape.vocab)
+        log(f"[bench] cycle: loading the draft model ({dshape.name}) ...")
+        dsrc = synth.WeightSource(dshape, args.seed + 1)
+        dmodel = G.load_model(dshape, dsrc)
+        dkv = sj.sj_kv_create(dmodel, B, cap)
+        for b in range(B):
+            for l in range(dshape.n_layers):
+                k, v = synth.make_kv_cache(dshape, args.seed + 1, b, l, int(lens[b]))
+                sj.sj_kv_set_layer(dkv, b, l, k, v, int(lens[b]))
+            sj.sj_kv_set_state(dkv, b, int(lens[b]), int(pend[b]))
+        un_d = torch.rand((gamma, B), dtype=torch.float32, device=dev, generator=torch.Generator(device=dev).manual_seed(args.seed))
+        dtok = torch.zeros((B, gamma), dtype=torch.int32, device=dev)
+        dprob = torch.zeros((B, gamma, shape.vocab), dtype=torch.float32, device=dev)
+
+        def draft_only():
+            sj.sj_kv_rewind(dkv, lens.tolist(), pend.tolist(), stream)
+            sj.sj_draft_block(dmodel, dkv, gamma, un_d, True, dtok, dprob, stream)
+
+        def one_cycle():
+            draft_only()
+            sj.sj_kv_rewind(kv, lens.tolist(), pend.tolist(), stream)
+            sj.sj_verify_step(model, kv, gamma, dtok, dprob, un, args.theta, acc, nxt, stream)
+
+        def timed(fn, n):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / n * 1e3
+
+        n_c = min(args.steps, 50)
+        d_ms, c_ms = timed(draft_only, n_c), timed(one_cycle, n_c)
+        mean_acc = float((acc.cpu().numpy() + 1).mean())
+        cycle = {"draft_model": f"{dshape.name}: {dshape.n_layers} layers d={dshape.d_model} heads {dshape.n_q_heads}/"
+                                f"{dshape.n_kv_heads}x{dshape.head_dim} ffn={dshape.d_ffn}", "cycles_timed": n_c,
+                 "draft_block_ms": round(d_ms, 4), "cycle_ms": round(c_ms, 4), "cycles_per_s": round(1e3 / c_ms, 2),
+                 "tokens_per_seq_cycle": round(mean_acc, 3),
+                 "note": "random-weight draft and target agree on nothing: acceptance here says nothing about the method"}
+        sj.sj_kv_free(dkv)
+        sj.sj_model_free(dmodel)
+
     out = {
         "metric": "verify_steps_per_s", "value": round(steps_per_s, 3), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -231,6 +281,8 @@ def main() -> int:
                      "frac": round(k_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": k_bytes, "avg_launch_us": round(k_avg_s * 1e6, 2), "launches_timed": int(k_launches)},
     }
+    if cycle is not None:
+        out["cycle"] = cycle
     sj.sj_kv_free(kv)
     sj.sj_model_free(model)
     if not args.no_cpu_baseline:

@@ -7,7 +7,7 @@ arithmetic: no transformer math, no accept test, no sampling of the emitted
 token.  Both the CPU oracle's tests and the HIP library's tests / benchmark
 pull their inputs from here so that the two sides see identical values.
 """
-from .configs import CONFIGS, ModelShape, shape_of  # noqa: F401
+from .configs import CONFIGS, DRAFT_1B, ModelShape, shape_of  # noqa: F401
 from .generate import (  # noqa: F401
     bf16_bits_to_f32,
     bf16_bits_to_f64,

@@ -77,5 +77,11 @@ CONFIGS = {
 }
 
 
+# Draft model of the speculate -> verify cycle: Llama-3.2-1B-shaped (the paper pairs an 8B target with a 1B
+# draft of the same family and vocabulary); workload fields follow the target they are paired with.
+DRAFT_1B = ModelShape("llama1b_draft", "bf16", 16, 2048, 32, 8, 64, 8192, 128256, 500000.0,
+                      batch=1, gamma=5, kv_len=(1024, 1024))
+
+
 def shape_of(idx: int) -> ModelShape:
     return CONFIGS[idx]
