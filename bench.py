@@ -197,6 +197,19 @@ def main() -> int:
     steps_per_s = args.steps / total_s
     mean_tokens = float((acc.cpu().numpy() + 1).mean())
 
+    # spread of single steps (outside the timed region): one event pair per step
+    n_sp = min(args.steps, 100)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_sp)]
+    for a_ev, b_ev in evs:
+        sj.sj_kv_rewind(kv, lens.tolist(), pend.tolist(), stream)
+        a_ev.record(stream)
+        sj.sj_verify_step(model, kv, gamma, dt, dp, un, args.theta, acc, nxt, stream)
+        b_ev.record(stream)
+    torch.cuda.synchronize()
+    per_step = np.sort(np.array([a_ev.elapsed_time(b_ev) for a_ev, b_ev in evs]))
+    spread = {"steps": n_sp, "median": round(float(np.median(per_step)), 4),
+              "p10": round(float(per_step[int(0.1 * (n_sp - 1))]), 4), "p90": round(float(per_step[int(0.9 * (n_sp - 1))]), 4)}
+
     ab = algorithmic_bytes(shape, lens, gamma)
     step_gbps = ab["total"] / (ms_per_step * 1e-3) / 1e9
 
@@ -274,6 +287,7 @@ def main() -> int:
                    "judge_threshold": args.theta, "temperature": shape.temperature, "parallelism": "single GPU"},
         "verified_tokens_per_s": round(steps_per_s * B * mean_tokens, 2),
         "mean_tokens_per_seq_step": round(mean_tokens, 3),
+        "step_ms_device_only": spread,
         "step_hbm": {"algorithmic_bytes": ab["total"], "achieved_gbps": round(step_gbps, 1),
                      "frac_of_8TBps": round(step_gbps / HBM_PEAK_GBPS, 4)},
         "roofline": {"kernel": ("gemm_skinny" if B * (gamma + 1) <= 32 else "gemm_rows2") + " (gate/up projection + SwiGLU epilogue)", "bound": "hbm",

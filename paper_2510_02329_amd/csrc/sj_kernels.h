@@ -508,9 +508,17 @@ __global__ __launch_bounds__(256) void resample_e_kernel(const StepParams* __res
     a.epart[(size_t)bi * a.nslab + slab] = s;
 }
 
+// sum of n slab sums by a 256-thread block: 8 independent loads per thread and batch (index clamped,
+// surplus ignored), fixed order
 __device__ __forceinline__ double total_of(const double* part, int n, double* lds4) {
     double s = 0.0;
-    for (int i = threadIdx.x; i < n; i += 256) s += part[i];
+    for (int i0 = threadIdx.x; i0 < n; i0 += 256 * 8) {
+        double t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = part[min(i0 + 256 * u, n - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (i0 + 256 * u < n) ? t[u] : 0.0;
+    }
     return block_sum_256(s, lds4);
 }
 
@@ -547,8 +555,10 @@ __global__ __launch_bounds__(256) void resample_pick_kernel(const StepParams* __
                                                             int32_t* __restrict__ len, int32_t* __restrict__ pending) {
     __shared__ double red[4];
     __shared__ double wave_tot[4];
+    constexpr int PICK_LDS = 8192;               // slab sums staged in LDS (64 KB)
     __shared__ double before_of[257];
     __shared__ double slab_w[256];
+    __shared__ double part_lds[PICK_LDS];
     __shared__ int hit_slab;
     __shared__ double hit_before;
     const int bi = blockIdx.x;
@@ -569,10 +579,25 @@ __global__ __launch_bounds__(256) void resample_pick_kernel(const StepParams* __
         const double* part = use_e ? ep : wp;
         if (use_e) W = Z;
         const double target = (double)sp->uniforms[bi * (gamma + 1) + gamma] * W;
-        // exclusive scan of the slab sums in slab order: thread t owns slabs [t*per, t*per+per)
+        // exclusive scan of the slab sums in slab order: thread t owns slabs [t*per, t*per+per).  The sums
+        // are staged in LDS with coalesced loads first when they fit (a thread's own range is strided
+        // in memory: reading it directly is `per` dependent round trips)
         const int per = a.nslab / 256;
+        const bool in_lds = a.nslab <= PICK_LDS;
+        if (in_lds) {
+            for (int i0 = threadIdx.x; i0 < a.nslab; i0 += 256 * 8) {
+                double t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = part[min(i0 + 256 * u, a.nslab - 1)];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (i0 + 256 * u < a.nslab) part_lds[i0 + 256 * u] = t[u];
+            }
+            __syncthreads();
+        }
+        auto slab_sum = [&](int i) { return in_lds ? part_lds[i] : part[i]; };
         double mine = 0.0;
-        for (int i = 0; i < per; ++i) mine += part[threadIdx.x * per + i];
+        for (int i = 0; i < per; ++i) mine += slab_sum(threadIdx.x * per + i);
         double incl = mine;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -596,7 +621,7 @@ __global__ __launch_bounds__(256) void resample_pick_kernel(const StepParams* __
             int hs = -1, last_pos = -1;
             double hb = 0.0, last_before = 0.0;
             for (int i = 0; i < per; ++i) {
-                const double v = part[threadIdx.x * per + i];
+                const double v = slab_sum(threadIdx.x * per + i);
                 if (v > 0.0) { last_pos = threadIdx.x * per + i; last_before = c; }
                 if (c + v > target) { hs = threadIdx.x * per + i; hb = c; break; }
                 c += v;
