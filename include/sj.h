@@ -155,6 +155,21 @@ int sj_verify_step(sj_model* m, sj_kv* kv, int32_t gamma, const int32_t* draft_t
 int sj_draft_block(sj_model* m, sj_kv* kv, int32_t gamma, const float* uniforms, int32_t feed_last,
                    int32_t* draft_tokens, float* draft_probs, void* stream);
 
+/* Teacher-forced scoring of a block (Sec. 3.3 "Computing Semantic Preservation Score", Eq. 6 - 7: every term of
+ * the score is the log-probability of a known next token after a known prefix).  For every sequence the n
+ * given tokens are fed at positions len .. len+n-1 on top of the cache, and
+ *   logprob[b][j] = log softmax(logits of row j / T)[target_tokens[b][j]].
+ * With inputs [y_{i-1}, x, y_{i+1}, .., y_{i+N-1}] and targets [x, y_{i+1}, .., y_{i+N}] (x = y_i, then x = z_i)
+ * the score is  s(y, z_i) = sum_j logprob_z[j] - sum_j logprob_y[j]  (two calls on the same cache).
+ *   input_tokens, target_tokens  device int32 [batch, n], 1 <= n <= max_gamma + 1 (out-of-range ids are clamped)
+ *   logprob      device float [batch, n] out
+ *   hidden_out   device float [batch, d_model] out or NULL: the normed final hidden state of block row
+ *                hidden_row (the judge's feature h_z of the token fed in that row, Eq. 4)
+ * The cache state (len, pending) is NOT changed: the rows written at len.. are dead.  Launches eagerly.
+ * Errors: SJ_EINVAL, SJ_ECAPACITY. */
+int sj_score_block(sj_model* m, sj_kv* kv, int32_t n, const int32_t* input_tokens, const int32_t* target_tokens,
+                   float* logprob, int32_t hidden_row, float* hidden_out, void* stream);
+
 /* The verification tail alone (LM head, softmax, Eq. 3, Eq. 5, scan, resampling) on given final
  * hidden states: hidden = device [batch*(gamma+1), d_model] in the storage dtype, already
  * RMS-normed, row b*(gamma+1)+j = block row j of sequence b.  No cache is read or written; kv

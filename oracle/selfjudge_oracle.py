@@ -20,6 +20,8 @@ and "Judge Verification"):
     order until the first rejection (Sec. 3.1).
   * the draft proposal that feeds the cycle (Eq. 1): gamma sequential single-token decodes of the
     draft model, each drawing d from its own next-token law q (`draft_block`).
+  * the training-label score (Sec. 3.3, Eq. 6 - 7): log-likelihood difference of the response with one
+    token replaced, from two teacher-forced passes (`score_block`, `semantic_preservation`).
   * one more token is emitted: from the last distribution p_{t+gamma+1} if everything was
     accepted (Sec. 3.1, text after Eq. 2), otherwise from the residual distribution
     norm(max(0, p - q)) of "modified rejection sampling" (Sec. 2.2), which is the choice that
@@ -339,6 +341,50 @@ def draft_block(cfg: OracleConfig, W: WeightFn, caches: Sequence[SeqCache], gamm
         for c in caches:
             c.length += 1
     return tokens, probs
+
+
+def score_block(cfg: OracleConfig, W: WeightFn, caches: Sequence[SeqCache], inputs: np.ndarray,
+                targets: np.ndarray) -> List[Dict[str, np.ndarray]]:
+    """Teacher forcing: feed inputs[b] on top of cache b and return, per row, the log-probability of
+    targets[b][j] under softmax(logits_j / T) (the terms of Eq. 7), with the rows' hidden states.
+    Does not commit the caches."""
+    fw = block_forward(cfg, W, caches, [[int(t) for t in row] for row in inputs])
+    out = []
+    for b in range(len(caches)):
+        lp = np.empty(len(inputs[b]), F64)
+        for j, t in enumerate(targets[b]):
+            if cfg.temperature == 0.0:
+                lp[j] = 0.0 if int(np.argmax(fw[b]["logits"][j])) == int(t) else -np.inf
+            else:
+                z = fw[b]["logits"][j] / cfg.temperature
+                m = z.max()
+                lp[j] = z[int(t)] - (m + np.log(np.exp(z - m).sum()))
+        out.append({"logprob": lp, "hn": fw[b]["hn"]})
+    return out
+
+
+def semantic_preservation(cfg: OracleConfig, W: WeightFn, cache: SeqCache, y_next: Sequence[int], z: int,
+                          tau: float) -> Dict[str, object]:
+    """Semantic preservation score of replacing y_i by z (Sec. 3.3, Eq. 6 in its autoregressive form Eq. 7).
+    The cache holds the response up to y_{i-2} and y_{i-1} is its pending token (R8); y_next = [y_i,
+    y_{i+1}, .., y_{i+N}] (N future tokens).  Two teacher-forced passes of N+1 rows:
+        original:  inputs [y_{i-1}, y_i, y_{i+1}, .., y_{i+N-1}]  targets [y_i, y_{i+1}, .., y_{i+N}]
+        replaced:  inputs [y_{i-1}, z,   y_{i+1}, .., y_{i+N-1}]  targets [z,   y_{i+1}, .., y_{i+N}]
+    s_prefix = log P(z | y_<i) - log P(y_i | y_<i)  (row 0 of both),
+    suffix   = log P(y_>i | y_<i, z) - log P(y_>i | y_<=i)  (rows 1..N),
+    s = s_prefix + suffix, label = s > tau (Step 3), h_z = hidden state of the row that reads z (Eq. 4)."""
+    y_next = [int(t) for t in y_next]
+    ins_y = [cache.pending] + y_next[:-1]
+    ins_z = [cache.pending, int(z)] + y_next[1:-1] if len(y_next) > 1 else [cache.pending]
+    tg_y, tg_z = y_next, [int(z)] + y_next[1:]
+    a = score_block(cfg, W, [cache], [ins_y], [tg_y])[0]
+    b = score_block(cfg, W, [cache], [ins_z], [tg_z])[0]
+    s_prefix = float(b["logprob"][0] - a["logprob"][0])
+    suffix = float(b["logprob"][1:].sum() - a["logprob"][1:].sum())
+    s = s_prefix + suffix
+    h_z = b["hn"][1] if len(y_next) > 1 else None
+    return {"s": s, "s_prefix": s_prefix, "suffix": suffix, "label": bool(s > tau), "h_z": h_z,
+            "logprob_y": a["logprob"], "logprob_z": b["logprob"]}
 
 
 def prefill(cfg: OracleConfig, W: WeightFn, cache: SeqCache, tokens: Sequence[int]) -> int:

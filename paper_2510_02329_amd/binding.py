@@ -66,6 +66,7 @@ def load_library() -> C.CDLL:
         "sj_verify_step": (C.c_int, [vp, vp, i32, vp, vp, vp, f32, vp, vp, vp]),
         "sj_verify_head": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, f32, vp, vp, vp]),
         "sj_draft_block": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, vp]),
+        "sj_score_block": (C.c_int, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
         "sj_set_mode": (C.c_int, [vp, i32]),
         "sj_set_operand_planes": (C.c_int, [vp, i32]),
         "sj_kv_rewind": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
@@ -205,6 +206,12 @@ def sj_verify_head(model: int, kv: int, gamma: int, hidden, draft_tokens, draft_
 def sj_draft_block(model: int, kv: int, gamma: int, uniforms, feed_last: bool, draft_tokens, draft_probs, stream=None) -> None:
     _check(load_library().sj_draft_block(model, kv, gamma, _ptr(uniforms), 1 if feed_last else 0, _ptr(draft_tokens),
                                          _ptr(draft_probs), _stream(stream)))
+
+
+def sj_score_block(model: int, kv: int, n: int, input_tokens, target_tokens, logprob, hidden_row: int = 0, hidden_out=None,
+                   stream=None) -> None:
+    _check(load_library().sj_score_block(model, kv, n, _ptr(input_tokens), _ptr(target_tokens), _ptr(logprob), int(hidden_row),
+                                         _ptr(hidden_out), _stream(stream)))
 
 
 def sj_set_mode(kv: int, mode: int) -> None:

@@ -13,7 +13,8 @@ struct StepParams {
     int32_t seq_base;    // first sequence index (prefill of one sequence: its index)
     int32_t rps;         // query rows per sequence (verify: gamma + 1; prefill: chunk length)
     int32_t gamma;       // draft length (verify only)
-    int32_t tok_mode;    // 0: row 0 = pending token, rows 1.. = draft tokens; 1: rows = prefill tokens
+    int32_t tok_mode;    // 0: row 0 = pending token, rows 1.. = draft tokens; 1: rows = prefill tokens;
+                         // 2: every row's token is given: draft_tokens [nseq, rps]
     int32_t mode;        // SJ_MODE_*
     float theta;         // judge threshold
     float pad0;
@@ -126,6 +127,7 @@ __global__ __launch_bounds__(256) void step_begin_kernel(const StepParams* __res
     const int b = sp->seq_base + bi;
     int tok;
     if (sp->tok_mode == 1) tok = sp->prefill_tokens[j];
+    else if (sp->tok_mode == 2) tok = sp->draft_tokens[bi * rps + j];
     else tok = (j == 0) ? pending[b] : sp->draft_tokens[bi * sp->gamma + (j - 1)];
     tok = min(max(tok, 0), md.V - 1);
     const int pos = len[b] + j;
@@ -687,6 +689,26 @@ __global__ __launch_bounds__(256) void draft_emit_kernel(int V, float inv_temp, 
     for (int k = blockIdx.x * 256 + threadIdx.x; k < V; k += gridDim.x * 256)
         q[k] = (inv_temp > 0.f) ? expf((l[k] - st.x) * inv_temp) * invz : (k == arg ? 1.f : 0.f);
     if (blockIdx.x == 0 && threadIdx.x == 0) draft_tokens[bi * gamma + j] = pending[seq_base + bi];
+}
+
+// Teacher-forced scoring (Sec. 3.3, the terms of Eq. 7): log-probability of a given next token under every
+// row's distribution, logp[r] = (l[r][t] - max) / T - log Z from the row's softmax statistics; T = 0: 0 for
+// the arg-max, -inf otherwise.  Optionally copies the normed hidden state of row `hrow` of every sequence
+// (the judge's feature of the token fed there, Eq. 4).
+__global__ __launch_bounds__(256) void score_gather_kernel(int nseq, int rps, int V, int d, float inv_temp,
+                                                           const float* __restrict__ logits, const float4* __restrict__ rowstat,
+                                                           const int32_t* __restrict__ targets, float* __restrict__ logp,
+                                                           const float* __restrict__ hn32, int hrow, float* __restrict__ hidden_out) {
+    const int R = nseq * rps;
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < R; r += gridDim.x * 256) {
+        const int t = min(max(targets[r], 0), V - 1);
+        const float4 st = rowstat[r];
+        logp[r] = (inv_temp > 0.f) ? (logits[(size_t)r * V + t] - st.x) * inv_temp - logf(st.y)
+                                   : (t == __float_as_int(st.z) ? 0.f : -INFINITY);
+    }
+    if (hidden_out)
+        for (int i = blockIdx.x * 256 + threadIdx.x; i < nseq * d; i += gridDim.x * 256)
+            hidden_out[i] = hn32[((size_t)(i / d) * rps + hrow) * d + i % d];
 }
 
 // the cache rows of this call are kept: advance every sequence's length by rps

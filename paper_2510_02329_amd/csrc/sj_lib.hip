@@ -1172,6 +1172,49 @@ extern "C" int sj_draft_block(sj_model* m, sj_kv* kv, int32_t gamma, const float
     return SJ_OK;
 }
 
+// forward + LM head over given tokens, then the gather of the targets' log-probabilities
+template <typename T, int SPL>
+static int score_impl(sj_model* m, sj_kv* kv, int n, const int32_t* targets, float* logprob, int hrow, float* hidden_out,
+                      hipStream_t st) {
+    Runner<T, SPL> run{m, kv, st, kv->batch, n, kv->batch * n};
+    int rc;
+    if ((rc = run.layers())) return rc;
+    if ((rc = run.lm_head(false))) return rc;
+    const int R = kv->batch * n, work = std::max(R, hidden_out ? kv->batch * m->md.d : 0);
+    score_gather_kernel<<<std::min(256, (work + 255) / 256), 256, 0, st>>>(kv->batch, n, m->md.V, m->md.d, m->md.inv_temp, kv->logits,
+                                                                       kv->rowstat, targets, logprob, kv->hn32, hrow, hidden_out);
+    LAUNCHCHK("score_gather");
+    return SJ_OK;
+}
+
+extern "C" int sj_score_block(sj_model* m, sj_kv* kv, int32_t n, const int32_t* input_tokens, const int32_t* target_tokens,
+                              float* logprob, int32_t hidden_row, float* hidden_out, void* stream) {
+    if (!m || !kv) return fail(SJ_EINVAL, "model / kv is null");
+    if (kv->m != m) return fail(SJ_EINVAL, "kv was created for a different model");
+    if (m->cfg.n_layers == 0) return fail(SJ_EINVAL, "head-only model has no forward");
+    if (n < 1 || n > m->cfg.max_gamma + 1) return fail(SJ_EINVAL, "n %d outside 1..max_gamma + 1 = %d", n, m->cfg.max_gamma + 1);
+    if (!input_tokens || !target_tokens || !logprob) return fail(SJ_EINVAL, "null device pointer argument");
+    if (hidden_out && (hidden_row < 0 || hidden_row >= n)) return fail(SJ_EINVAL, "hidden_row %d outside the block", hidden_row);
+    int rc = refresh_lengths(kv);
+    if (rc) return rc;
+    for (int b = 0; b < kv->batch; ++b)
+        if (kv->len_upper[b] + n > kv->cap[b])
+            return fail(SJ_ECAPACITY, "sequence %d: len %d + %d rows exceeds capacity %d", b, kv->len_upper[b], n, kv->cap[b]);
+    hipStream_t st = (hipStream_t)stream;
+    StepParams p{};
+    p.nseq = kv->batch; p.seq_base = 0; p.rps = n; p.gamma = n - 1; p.tok_mode = 2; p.mode = kv->mode;
+    p.draft_tokens = input_tokens;
+    if ((rc = set_params(kv, st, p))) return rc;
+    if (m->cfg.dtype == SJ_DTYPE_FP32) rc = score_impl<float, 1>(m, kv, n, target_tokens, logprob, hidden_row, hidden_out, st);
+    else if (kv->planes == 1) rc = score_impl<bf16_t, 1>(m, kv, n, target_tokens, logprob, hidden_row, hidden_out, st);
+    else if (kv->planes == 3) rc = score_impl<bf16_t, 3>(m, kv, n, target_tokens, logprob, hidden_row, hidden_out, st);
+    else rc = score_impl<bf16_t, 2>(m, kv, n, target_tokens, logprob, hidden_row, hidden_out, st);
+    if (rc) return rc;
+    kv->last_gamma = 0;
+    kv->last_rows = kv->batch * n;
+    return SJ_OK;
+}
+
 extern "C" int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void* hidden, const int32_t* draft_tokens,
                               const float* draft_probs, const float* uniforms, float judge_threshold, int32_t* accepted_len,
                               int32_t* next_token, void* stream) {

@@ -524,3 +524,70 @@ def test_first_draft_token_follows_q_exactly():
         counts[toks[0, 0]] += 1
         q = probs[0, 0]
     assert np.abs(counts / N - q).max() <= 1.0 / N + 1e-12
+
+
+# ------------------------------------------------------------------ P9: semantic preservation score (Eq. 6 - 7)
+# The score is a difference of joint log-likelihoods of two continuations of the same prefix; the oracle gets
+# it from two teacher-forced blocks.  Pinned against the definition evaluated by single-token decodes, the
+# trivial replacement, the prefix-only special case and the normalisation of the scored distributions.
+
+
+def _joint_loglik_sequential(cfg, W, cache_seed, L, pending, tokens):
+    """log P(tokens | prefix) by feeding one token at a time and committing the cache (no block forward)."""
+    c = helpers.random_cache(cfg, L, 64, seed=cache_seed)
+    c.pending = pending
+    total = 0.0
+    for t in tokens:
+        logits = orc.block_forward(cfg, W, [c], [[c.pending]])[0]["logits"][0] / cfg.temperature
+        total += logits[t] - (logits.max() + np.log(np.exp(logits - logits.max()).sum()))
+        c.length += 1
+        c.pending = int(t)
+    return float(total)
+
+
+@pytest.mark.parametrize("seed,N", [(0, 0), (1, 1), (2, 5), (3, 9)])
+def test_semantic_preservation_score_is_the_joint_likelihood_difference(seed, N):
+    shape, cfg, t = _tiny(seed)
+    W = helpers.dict_weights(t)
+    rng = np.random.default_rng(50 + seed)
+    L = 6
+    cache = helpers.random_cache(cfg, L, 64, seed=60)
+    y_next = [int(x) for x in rng.integers(0, cfg.vocab, N + 1)]
+    z = int((y_next[0] + 1 + rng.integers(0, cfg.vocab - 1)) % cfg.vocab)
+    res = orc.semantic_preservation(cfg, W, cache, y_next, z, tau=0.0)
+    ll_z = _joint_loglik_sequential(cfg, W, 60, L, cache.pending, [z] + y_next[1:])
+    ll_y = _joint_loglik_sequential(cfg, W, 60, L, cache.pending, y_next)
+    assert abs(res["s"] - (ll_z - ll_y)) < 1e-9                       # Eq. 6 == Eq. 7
+    assert abs(res["s"] - (res["s_prefix"] + res["suffix"])) < 1e-12
+    assert res["label"] == (res["s"] > 0.0)
+    assert cache.length == L                                          # scoring does not commit
+    if N == 0:                                                        # prefix-only score: one softmax
+        logits = orc.block_forward(cfg, W, [helpers.random_cache(cfg, L, 64, seed=60)], [[cache.pending]])[0]["logits"][0]
+        p = np.exp(logits - logits.max()); p /= p.sum()
+        assert abs(res["s"] - (np.log(p[z]) - np.log(p[y_next[0]]))) < 1e-10 and res["suffix"] == 0.0
+
+
+def test_replacing_a_token_by_itself_scores_zero_and_swapping_negates():
+    shape, cfg, t = _tiny(4)
+    W = helpers.dict_weights(t)
+    cache = helpers.random_cache(cfg, 5, 64, seed=61)
+    y_next = [3, 17, 40, 8]
+    same = orc.semantic_preservation(cfg, W, cache, y_next, y_next[0], tau=0.0)
+    assert same["s"] == 0.0 and same["label"] is False
+    fwd = orc.semantic_preservation(cfg, W, cache, y_next, 29, tau=-1e9)
+    back = orc.semantic_preservation(cfg, W, cache, [29] + y_next[1:], y_next[0], tau=-1e9)
+    assert abs(fwd["s"] + back["s"]) < 1e-10 and fwd["label"] and back["label"]
+    # h_z is the hidden state of the row that READS z: it changes with z, row 0 (reads y_{i-1}) does not
+    other = orc.semantic_preservation(cfg, W, cache, y_next, 30, tau=0.0)
+    assert not np.allclose(fwd["h_z"], other["h_z"])
+
+
+def test_scored_rows_are_normalised_distributions():
+    shape, cfg, t = _tiny(6)
+    W = helpers.dict_weights(t)
+    cache = helpers.random_cache(cfg, 4, 64, seed=62)
+    ins = [[cache.pending, 5, 9]]
+    tot = np.zeros(3)
+    for v in range(cfg.vocab):                                        # every token as the target of every row
+        tot += np.exp(orc.score_block(cfg, W, [cache], ins, [[v, v, v]])[0]["logprob"])
+    assert np.allclose(tot, 1.0, atol=1e-10)
