@@ -181,11 +181,18 @@ int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void* hidden,
 /* Verifier variants of the paper's ablations and baselines, applied by the following steps:
  *   SJ_MODE_TWO_STAGE (default)  either test approves          (App. D.2)
  *   SJ_MODE_ALIGNMENT            Eq. 3 only (standard speculative decoding)
- *   SJ_MODE_JUDGE                Eq. 5 only */
+ *   SJ_MODE_JUDGE                Eq. 5 only
+ *   SJ_MODE_TOPK                 the relaxed baseline of Sec. 4.1: d_j is kept when fewer than k entries of
+ *                                the target's row precede it (larger logit, or equal logit at a lower
+ *                                index); k = 2 (the paper's setting) unless sj_set_topk changes it.
+ * In every mode the extra token after a rejection comes from the residual rule of Sec. 2.2.
+ * Errors: SJ_EINVAL for a null handle, an unknown mode or k < 1. */
 #define SJ_MODE_TWO_STAGE 0
 #define SJ_MODE_ALIGNMENT 1
 #define SJ_MODE_JUDGE     2
+#define SJ_MODE_TOPK      3
 int sj_set_mode(sj_kv* kv, int32_t mode);
+int sj_set_topk(sj_kv* kv, int32_t k);
 
 /* Sets every sequence's length and pending token from host arrays of `batch` entries, asynchronously
  * on `stream` (a benchmark or a caller rolling back uses it to replay a step from the same state).
@@ -215,7 +222,8 @@ int sj_set_operand_planes(sj_kv* kv, int32_t planes);
  *   SJ_DBG_HIDDEN       float [rows, d_model]   final hidden states after the last RMSNorm
  *   SJ_DBG_JUDGE_SCORES float [batch, gamma]    sigmoid scores, entry j for d_{j+1}
  *   SJ_DBG_P_AT_DRAFT   float [batch, gamma]    p(d_{j+1}) under the target
- *   SJ_DBG_ACCEPT_BITS  int32 [batch, gamma]    bit0 = Eq. 3 accepted, bit1 = judge accepted
+ *   SJ_DBG_ACCEPT_BITS  int32 [batch, gamma]    bit0 = Eq. 3 accepted, bit1 = judge accepted,
+ *                                               bit2 = top-k accepted (top-k mode only)
  * nbytes must equal the size above for the gamma of the last step. */
 #define SJ_DBG_LOGITS       0
 #define SJ_DBG_HIDDEN       1

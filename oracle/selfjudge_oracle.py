@@ -45,6 +45,10 @@ Readings of points the paper leaves open (each is also listed in the design note
       of a new row are rounded to it (nearest even) when appended, and every read - also the
       block's own rows in the same step - sees the stored value.  This keeps "one block
       forward == gamma+1 single-token decodes" exact on what the cache holds.
+  R12 top-k verification (the relaxed baseline of Sec. 4.1, k = 2 in the experiments): d_j is kept
+      when fewer than k vocabulary entries precede it in the target's row j-1, ordered by
+      decreasing logit and, for equal logits, increasing index; the emitted token after a
+      rejection follows the same residual rule as every other mode.                    [parity unpinned]
 """
 from __future__ import annotations
 
@@ -260,41 +264,53 @@ def emitted_token(p_rows: np.ndarray, q_rows: np.ndarray, n: int, gamma: int, u:
     return draw(w, u)
 
 
+def token_rank(logits_row: np.ndarray, token: int) -> int:
+    """Position of `token` in the row ordered by decreasing logit, equal logits by increasing index
+    (the order in which R6 picks the arg-max): 0 for the arg-max itself."""
+    row = np.asarray(logits_row)
+    ref = row[token]
+    return int(np.count_nonzero(row > ref) + np.count_nonzero(row[:token] == ref))
+
+
 def verify_tail(logits: np.ndarray, judge_scores: np.ndarray, draft_tokens: Sequence[int],
                 draft_probs: np.ndarray, uniforms: Sequence[float], theta: float,
-                temperature: float, mode: str = "two_stage") -> Dict[str, object]:
+                temperature: float, mode: str = "two_stage", top_k: int = 2) -> Dict[str, object]:
     """Everything after the forward for one sequence.
 
     logits [gamma+1, V]: row j is the target's next-token logits after reading block row j, so
     row j-1 tests draft d_j (j = 1..gamma) and row gamma is the bonus distribution.
     judge_scores [gamma]: entry j-1 is Verifier(h) of the row whose input is d_j.
     draft_probs [gamma, V]; uniforms [gamma+1] (last one draws the emitted token).
-    mode: "two_stage" (either test), "alignment" (Eq. 3 only), "judge" (Eq. 5 only)."""
+    mode: "two_stage" (either test), "alignment" (Eq. 3 only), "judge" (Eq. 5 only), "topk" (the
+    relaxed baseline of Sec. 4.1: d_j is kept when it is among the target's top_k tokens)."""
     gamma = len(draft_tokens)
     p = np.stack([target_distribution(logits[j], temperature) for j in range(gamma + 1)])
     q = np.asarray(draft_probs, F64)
-    a_bits, g_bits, p_at_d = [], [], []
+    a_bits, g_bits, k_bits, p_at_d = [], [], [], []
     for j in range(1, gamma + 1):
         d = int(draft_tokens[j - 1])
         p_d, q_d = p[j - 1, d], q[j - 1, d]
         p_at_d.append(p_d)
         a_bits.append(alignment_accepts(float(uniforms[j - 1]), q_d, p_d))
         g_bits.append(bool(judge_scores[j - 1] > theta))
+        k_bits.append(token_rank(logits[j - 1], d) < top_k)
     if mode == "alignment":
         ok = list(a_bits)
     elif mode == "judge":
         ok = list(g_bits)
+    elif mode == "topk":
+        ok = list(k_bits)
     else:
         ok = [a or g for a, g in zip(a_bits, g_bits)]
     n = accepted_length(ok)
     nxt = emitted_token(p, q, n, gamma, float(uniforms[gamma]))
-    return {"accepted_len": n, "next_token": nxt, "align_bits": a_bits, "judge_bits": g_bits,
+    return {"accepted_len": n, "next_token": nxt, "align_bits": a_bits, "judge_bits": g_bits, "topk_bits": k_bits,
             "p_at_draft": np.array(p_at_d), "p": p}
 
 
 def verify_step(cfg: OracleConfig, W: WeightFn, caches: Sequence[SeqCache],
                 draft_tokens: np.ndarray, draft_probs: np.ndarray, uniforms: np.ndarray,
-                theta: float, mode: str = "two_stage") -> List[Dict[str, object]]:
+                theta: float, mode: str = "two_stage", top_k: int = 2) -> List[Dict[str, object]]:
     """One full cycle for a batch of sequences; commits every cache (R8).
     draft_tokens [B, gamma], draft_probs [B, gamma, V], uniforms [B, gamma+1]."""
     B, gamma = np.asarray(draft_tokens).shape
@@ -305,7 +321,7 @@ def verify_step(cfg: OracleConfig, W: WeightFn, caches: Sequence[SeqCache],
     for b, cache in enumerate(caches):
         scores = np.array([judge_score(w, bias, fw[b]["hn"][j]) for j in range(1, gamma + 1)])
         res = verify_tail(fw[b]["logits"], scores, draft_tokens[b], draft_probs[b], uniforms[b],
-                          theta, cfg.temperature, mode)
+                          theta, cfg.temperature, mode, top_k)
         L0 = cache.length
         res.update(logits=fw[b]["logits"], hn=fw[b]["hn"], judge_scores=scores,
                    k_new=[cache.k[l][:, L0:L0 + gamma + 1].copy() for l in range(cfg.n_layers)],

@@ -12,7 +12,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 SJ_OK, SJ_EINVAL, SJ_ECAPACITY, SJ_EHIP, SJ_ENOMEM, SJ_ECALLBACK = 0, -1, -2, -3, -4, -5
-SJ_MODE_TWO_STAGE, SJ_MODE_ALIGNMENT, SJ_MODE_JUDGE = 0, 1, 2
+SJ_MODE_TWO_STAGE, SJ_MODE_ALIGNMENT, SJ_MODE_JUDGE, SJ_MODE_TOPK = 0, 1, 2, 3
 SJ_DBG_LOGITS, SJ_DBG_HIDDEN, SJ_DBG_JUDGE_SCORES, SJ_DBG_P_AT_DRAFT, SJ_DBG_ACCEPT_BITS, SJ_DBG_STAGE_TIMES = 0, 1, 2, 3, 4, 5
 
 TENSOR_IDS = {"embed": 0, "attn_norm": 1, "wq": 2, "wk": 3, "wv": 4, "wo": 5, "ffn_norm": 6,
@@ -68,6 +68,7 @@ def load_library() -> C.CDLL:
         "sj_draft_block": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, vp]),
         "sj_score_block": (C.c_int, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
         "sj_set_mode": (C.c_int, [vp, i32]),
+        "sj_set_topk": (C.c_int, [vp, i32]),
         "sj_set_operand_planes": (C.c_int, [vp, i32]),
         "sj_kv_rewind": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
         "sj_set_kernel_timing": (C.c_int, [vp, i32]),
@@ -216,6 +217,10 @@ def sj_score_block(model: int, kv: int, n: int, input_tokens, target_tokens, log
 
 def sj_set_mode(kv: int, mode: int) -> None:
     _check(load_library().sj_set_mode(kv, mode))
+
+
+def sj_set_topk(kv: int, k: int) -> None:
+    _check(load_library().sj_set_topk(kv, k))
 
 
 def sj_kv_rewind(kv: int, lengths: Sequence[int], pending: Sequence[int], stream=None) -> None:

@@ -17,7 +17,7 @@ struct StepParams {
                          // 2: every row's token is given: draft_tokens [nseq, rps]
     int32_t mode;        // SJ_MODE_*
     float theta;         // judge threshold
-    float pad0;
+    int32_t topk;        // k of the top-k mode
     const int32_t* draft_tokens;   // [nseq, gamma]
     const float* draft_probs;      // [nseq, gamma, V]
     const float* uniforms;         // [nseq, gamma + 1]
@@ -407,15 +407,32 @@ __global__ __launch_bounds__(256) void softmax_merge_kernel(const float4* __rest
 // Judge verifier (Eq. 5): score = sigmoid(w . h + b) on the final, normed hidden state of the row
 // whose input is the draft token.  One workgroup per (sequence, draft position); entry j scores
 // d_{j+1}, i.e. block row j + 1.
+// In the top-k mode (the relaxed baseline of Sec. 4.1) the workgroup also ranks d_{j+1} in the target's
+// row j: the number of vocabulary entries with a larger logit, or an equal one at a lower index.
 template <typename T>
 __global__ __launch_bounds__(256) void judge_kernel(const StepParams* __restrict__ sp, int d,
                                                     const float* __restrict__ hn32, const float* __restrict__ row_scale,
                                                     const T* __restrict__ w, const T* __restrict__ bias,
-                                                    float* __restrict__ scores) {
+                                                    float* __restrict__ scores, int V, const float* __restrict__ logits,
+                                                    int32_t* __restrict__ ranks) {
     __shared__ float red[4];
     const int gamma = sp->gamma;
     const int bi = blockIdx.x / gamma, j = blockIdx.x % gamma;
     const int row = bi * (gamma + 1) + j + 1;
+    if (sp->mode == 3) {                                   // uniform for the launch
+        const float* l = logits + (size_t)(row - 1) * V;
+        const int tok = min(max(sp->draft_tokens[bi * gamma + j], 0), V - 1);
+        const float ref = l[tok];
+        int cnt = 0;
+        for (int c = threadIdx.x * 4; c < V; c += 1024) {  // V is a multiple of 128
+            const float4 v = *reinterpret_cast<const float4*>(l + c);
+            cnt += (v.x > ref || (v.x == ref && c < tok)) + (v.y > ref || (v.y == ref && c + 1 < tok)) +
+                   (v.z > ref || (v.z == ref && c + 2 < tok)) + (v.w > ref || (v.w == ref && c + 3 < tok));
+        }
+        const float total = block_sum_256((float)cnt, red);   // exact: counts stay below 2^24
+        if (threadIdx.x == 0) ranks[blockIdx.x] = (int)total;
+        __syncthreads();
+    }
     const float* h = hn32 + (size_t)row * d;
     float acc = 0.f;
     for (int c = threadIdx.x; c < d; c += 256) acc += h[c] * Traits<T>::load(w + c);
@@ -436,7 +453,7 @@ __global__ __launch_bounds__(64) void accept_scan_kernel(const StepParams* __res
                                                          const float4* __restrict__ rowstat,
                                                          const float* __restrict__ scores,
                                                          float* __restrict__ p_at_d, int32_t* __restrict__ bits,
-                                                         int32_t* __restrict__ nacc) {
+                                                         int32_t* __restrict__ nacc, const int32_t* __restrict__ ranks) {
     const int bi = blockIdx.x, j = threadIdx.x;
     const int gamma = sp->gamma;
     bool ok = false;
@@ -452,9 +469,10 @@ __global__ __launch_bounds__(64) void accept_scan_kernel(const StepParams* __res
         const float u = sp->uniforms[bi * (gamma + 1) + j];
         const bool a = (u * q < p);
         const bool jd = scores[bi * gamma + j] > sp->theta;
-        ok = (sp->mode == 1) ? a : (sp->mode == 2) ? jd : (a || jd);
+        const bool tk = (sp->mode == 3) && ranks[bi * gamma + j] < sp->topk;
+        ok = (sp->mode == 1) ? a : (sp->mode == 2) ? jd : (sp->mode == 3) ? tk : (a || jd);
         p_at_d[bi * gamma + j] = p;
-        bits[bi * gamma + j] = (a ? 1 : 0) | (jd ? 2 : 0);
+        bits[bi * gamma + j] = (a ? 1 : 0) | (jd ? 2 : 0) | (tk ? 4 : 0);
     }
     const unsigned long long mask = __ballot(ok);
     if (j == 0) {

@@ -87,6 +87,8 @@ struct sj_kv {
     StepParams* sp_dev = nullptr;
     float *x = nullptr, *hn32 = nullptr, *part = nullptr, *opart = nullptr, *cs = nullptr, *logits = nullptr;
     float *scores = nullptr, *p_at_d = nullptr;
+    int32_t* ranks = nullptr;        // [R] rank of every draft token in its target row (top-k mode)
+    int topk = 2;
     void *xn = nullptr, *attn_out = nullptr, *act = nullptr;
     unsigned* tickets = nullptr;
     float4 *stats = nullptr, *rowstat = nullptr;
@@ -375,6 +377,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     ALLOC(kv->stats, (size_t)R * (V / 16) * sizeof(float4));
     ALLOC(kv->rowstat, (size_t)R * sizeof(float4));
     ALLOC(kv->scores, (size_t)R * 4);
+    ALLOC(kv->ranks, (size_t)R * 4);
     ALLOC(kv->p_at_d, (size_t)R * 4);
     ALLOC(kv->bits, (size_t)R * 4);
     ALLOC(kv->nacc, (size_t)batch * 4);
@@ -457,8 +460,15 @@ extern "C" int sj_kv_free(sj_kv* kv) {
 
 extern "C" int sj_set_mode(sj_kv* kv, int32_t mode) {
     if (!kv) return fail(SJ_EINVAL, "kv is null");
-    if (mode < 0 || mode > 2) return fail(SJ_EINVAL, "mode must be 0, 1 or 2");
+    if (mode < 0 || mode > 3) return fail(SJ_EINVAL, "mode must be 0, 1, 2 or 3");
     kv->mode = mode;
+    return SJ_OK;
+}
+
+extern "C" int sj_set_topk(sj_kv* kv, int32_t k) {
+    if (!kv) return fail(SJ_EINVAL, "kv is null");
+    if (k < 1) return fail(SJ_EINVAL, "k must be at least 1");
+    kv->topk = k;
     return SJ_OK;
 }
 
@@ -810,11 +820,12 @@ struct Runner {
     int tail(int gamma, const float* row_scale = nullptr) {
         const ModelDims& md = m->md;
         if (gamma > 0) {                                   // gamma = 0: a plain decode step (draft proposal)
-            judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, row_scale, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores);
+            judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, row_scale, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores,
+                                                             md.V, kv->logits, kv->ranks);
             LAUNCHCHK("judge");
         }
         accept_scan_kernel<<<nseq, 64, 0, st>>>(kv->sp_dev, md.V, md.inv_temp, kv->logits, kv->rowstat, kv->scores, kv->p_at_d,
-                                                 kv->bits, kv->nacc);
+                                                 kv->bits, kv->nacc, kv->ranks);
         LAUNCHCHK("accept_scan");
         ResampleArgs ra{};
         ra.V = md.V; ra.nslab = kv->nslab; ra.slab_len = kv->slab_len; ra.inv_temp = md.inv_temp;
@@ -1104,7 +1115,7 @@ extern "C" int sj_verify_step(sj_model* m, sj_kv* kv, int32_t gamma, const int32
                 return fail(SJ_ECAPACITY, "sequence %d: len %d + gamma + 1 exceeds capacity %d", b, kv->len_upper[b], kv->cap[b]);
     }
     StepParams p{};
-    p.nseq = kv->batch; p.seq_base = 0; p.rps = gamma + 1; p.gamma = gamma; p.tok_mode = 0; p.mode = kv->mode;
+    p.nseq = kv->batch; p.seq_base = 0; p.rps = gamma + 1; p.gamma = gamma; p.tok_mode = 0; p.mode = kv->mode; p.topk = kv->topk;
     p.theta = judge_threshold;
     p.draft_tokens = draft_tokens; p.draft_probs = draft_probs; p.uniforms = uniforms;
     p.accepted_len = accepted_len; p.next_token = next_token;
@@ -1147,7 +1158,7 @@ extern "C" int sj_draft_block(sj_model* m, sj_kv* kv, int32_t gamma, const float
         // one decode step = a verification step without draft tokens: the "all accepted" token is drawn from
         // the row's distribution with the step's uniform and becomes the pending token; length += 1
         StepParams p{};
-        p.nseq = kv->batch; p.seq_base = 0; p.rps = 1; p.gamma = 0; p.tok_mode = 0; p.mode = kv->mode;
+        p.nseq = kv->batch; p.seq_base = 0; p.rps = 1; p.gamma = 0; p.tok_mode = 0; p.mode = kv->mode; p.topk = kv->topk;
         p.theta = 0.5f;
         p.draft_tokens = nullptr; p.draft_probs = nullptr; p.uniforms = uniforms + (size_t)j * kv->batch;
         p.accepted_len = kv->nacc; p.next_token = kv->draft_tok;   // scratch: the token is read back from the state
@@ -1158,7 +1169,7 @@ extern "C" int sj_draft_block(sj_model* m, sj_kv* kv, int32_t gamma, const float
     }
     if (feed_last) {
         StepParams p{};
-        p.nseq = kv->batch; p.seq_base = 0; p.rps = 1; p.gamma = 0; p.tok_mode = 0; p.mode = kv->mode;
+        p.nseq = kv->batch; p.seq_base = 0; p.rps = 1; p.gamma = 0; p.tok_mode = 0; p.mode = kv->mode; p.topk = kv->topk;
         if ((rc = set_params(kv, st, p))) return rc;
         if (m->cfg.dtype == SJ_DTYPE_FP32) rc = feed_pending_impl<float, 1>(m, kv, st);
         else if (kv->planes == 1) rc = feed_pending_impl<bf16_t, 1>(m, kv, st);
@@ -1202,7 +1213,7 @@ extern "C" int sj_score_block(sj_model* m, sj_kv* kv, int32_t n, const int32_t* 
             return fail(SJ_ECAPACITY, "sequence %d: len %d + %d rows exceeds capacity %d", b, kv->len_upper[b], n, kv->cap[b]);
     hipStream_t st = (hipStream_t)stream;
     StepParams p{};
-    p.nseq = kv->batch; p.seq_base = 0; p.rps = n; p.gamma = n - 1; p.tok_mode = 2; p.mode = kv->mode;
+    p.nseq = kv->batch; p.seq_base = 0; p.rps = n; p.gamma = n - 1; p.tok_mode = 2; p.mode = kv->mode; p.topk = kv->topk;
     p.draft_tokens = input_tokens;
     if ((rc = set_params(kv, st, p))) return rc;
     if (m->cfg.dtype == SJ_DTYPE_FP32) rc = score_impl<float, 1>(m, kv, n, target_tokens, logprob, hidden_row, hidden_out, st);
@@ -1223,7 +1234,7 @@ extern "C" int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void*
     if (!hidden) return fail(SJ_EINVAL, "hidden is null");
     if (!(judge_threshold == judge_threshold)) return fail(SJ_EINVAL, "judge_threshold is NaN");
     StepParams p{};
-    p.nseq = kv->batch; p.seq_base = 0; p.rps = gamma + 1; p.gamma = gamma; p.tok_mode = 0; p.mode = kv->mode;
+    p.nseq = kv->batch; p.seq_base = 0; p.rps = gamma + 1; p.gamma = gamma; p.tok_mode = 0; p.mode = kv->mode; p.topk = kv->topk;
     p.theta = judge_threshold;
     p.draft_tokens = draft_tokens; p.draft_probs = draft_probs; p.uniforms = uniforms;
     p.accepted_len = accepted_len; p.next_token = next_token;

@@ -99,6 +99,42 @@ def test_verifier_modes(mode, name):
         gpu.close()
 
 
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_topk_mode(k):
+    """Top-k verification (the relaxed baseline of Sec. 4.1): drafts placed at the target's first, second,
+    third ... ranked token; decisions replayed exactly by the oracle's tail on the device's own logits."""
+    import copy
+    shape = BASE.scaled(batch=2, gamma=4)
+    gpu, cfg, W, caches = _setup(shape, [50, 31])
+    try:
+        probe = synth.make_draft(shape, seed=3)
+        ref0 = _oracle(cfg, W, copy.deepcopy(caches), probe, 0.5)
+        draft = synth.make_draft(shape, seed=4)
+        # sequence 0: ranks 0, 1, 2, 0 of row 0's ordering (later rows follow other tokens: any rank);
+        # sequence 1: rank 1 first
+        draft["tokens"][0, 0] = np.argsort(-ref0[0]["logits"][0], kind="stable")[0]
+        draft["tokens"][1, 0] = np.argsort(-ref0[1]["logits"][0], kind="stable")[1]
+        sj.sj_set_mode(gpu.kv, sj.SJ_MODE_TOPK)
+        sj.sj_set_topk(gpu.kv, k)
+        out = gpu.step(draft, 0.5)
+        ref = orc.verify_step(cfg, W, caches, draft["tokens"], draft["probs"], draft["uniforms"], 0.5, "topk", k)
+        for b in range(2):
+            G.close_enough(out["logits"][b], ref[b]["logits"], "bf16", "logits")
+            tail = orc.verify_tail(out["logits"][b].astype(np.float64), out["judge_scores"][b], draft["tokens"][b],
+                                   draft["probs"][b], draft["uniforms"][b], 0.5, shape.temperature, "topk", k)
+            assert [(int(x) >> 2) & 1 for x in out["bits"][b]] == [int(t) for t in tail["topk_bits"]]
+            assert int(out["accepted_len"][b]) == tail["accepted_len"]
+            assert int(out["next_token"][b]) == tail["next_token"]
+        assert int(out["accepted_len"][0]) >= 1                      # the arg-max token passes every k
+        assert (int(out["accepted_len"][1]) >= 1) == (k >= 2)        # the runner-up needs k >= 2
+        with pytest.raises(sj.SJError):
+            sj.sj_set_topk(gpu.kv, 0)
+        with pytest.raises(sj.SJError):
+            sj.sj_set_mode(gpu.kv, 4)
+    finally:
+        gpu.close()
+
+
 def test_threshold_extremes_and_rerun_is_bit_identical():
     shape = BASE
     gpu, cfg, W, caches = _setup(shape, [50, 31])

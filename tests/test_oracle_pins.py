@@ -591,3 +591,39 @@ def test_scored_rows_are_normalised_distributions():
     for v in range(cfg.vocab):                                        # every token as the target of every row
         tot += np.exp(orc.score_block(cfg, W, [cache], ins, [[v, v, v]])[0]["logprob"])
     assert np.allclose(tot, 1.0, atol=1e-10)
+
+
+# ------------------------------------------------------------------ P10: top-k verification (Sec. 4.1 baseline, R12)
+def test_token_rank_against_a_stable_sort_with_ties():
+    rng = np.random.default_rng(0)
+    for trial in range(20):
+        row = rng.integers(0, 6, 40).astype(np.float64)            # many equal logits
+        order = np.argsort(-row, kind="stable")                    # library routine: decreasing, ties by index
+        for tok in range(40):
+            assert orc.token_rank(row, tok) == int(np.nonzero(order == tok)[0][0])
+
+
+def test_topk_mode_special_cases():
+    rng = np.random.default_rng(1)
+    V, gamma = 50, 6
+    logits = rng.normal(size=(gamma + 1, V))
+    toks = rng.integers(0, V, gamma)
+    toks[0] = int(np.argmax(logits[0]))                             # the target's own token
+    toks[1] = int(np.argsort(-logits[1])[1])                        # its runner-up
+    toks[2] = int(np.argsort(-logits[2])[2])                        # third: fails k = 2
+    q = rng.dirichlet(np.ones(V), gamma)
+    u = rng.random(gamma + 1)
+    scores = np.zeros(gamma)
+    r2 = orc.verify_tail(logits, scores, toks, q, u, 0.5, 1.0, "topk", 2)
+    assert r2["topk_bits"][:3] == [True, True, False] and r2["accepted_len"] == 2
+    # k = V keeps everything, k = 1 keeps exactly the arg-max tokens, acceptance is monotone in k
+    assert orc.verify_tail(logits, scores, toks, q, u, 0.5, 1.0, "topk", V)["accepted_len"] == gamma
+    r1 = orc.verify_tail(logits, scores, toks, q, u, 0.5, 1.0, "topk", 1)
+    assert r1["topk_bits"] == [int(t) == int(np.argmax(logits[j])) for j, t in enumerate(toks)]
+    lens = [orc.verify_tail(logits, scores, toks, q, u, 0.5, 1.0, "topk", k)["accepted_len"] for k in range(1, V + 1)]
+    assert all(a <= b for a, b in zip(lens, lens[1:]))
+    # k = 1 at temperature 0 with a greedy (one-hot) draft is the alignment test of Eq. 3
+    onehot = np.zeros((gamma, V)); onehot[np.arange(gamma), toks] = 1.0
+    a = orc.verify_tail(logits, scores, toks, onehot, u, 0.5, 0.0, "alignment")
+    k1 = orc.verify_tail(logits, scores, toks, onehot, u, 0.5, 0.0, "topk", 1)
+    assert a["align_bits"] == k1["topk_bits"] and a["accepted_len"] == k1["accepted_len"] and a["next_token"] == k1["next_token"]
