@@ -19,5 +19,6 @@ from .generate import (  # noqa: F401
     make_pending,
     to_f64,
     make_hidden,
+    make_judge_dataset,
     TENSOR_NAMES,
 )

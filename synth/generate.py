@@ -191,3 +191,23 @@ def make_draft(shape: ModelShape, seed: int, base_logits: Optional[np.ndarray] =
     list(_pool().map(work, range(B)))
     uniforms = _rng(seed, "uniform").random((B, G + 1), dtype=np.float32)
     return {"tokens": tokens, "probs": probs, "uniforms": uniforms}
+
+
+def make_judge_dataset(seed: int, n: int, d: int, pos_rate: float = 0.61, shift: float = 1.0, n_dirs: int = 4,
+                       task_seed: int = 0):
+    """Synthetic (hidden state, label) pairs shaped like the verifier training set (paper Table
+    "Data for training verifier": 69,432 samples, 61 % labelled acceptable, features = d-dimensional
+    normed hidden states of unit scale).  Labels are Bernoulli(pos_rate); a feature row is standard
+    normal noise plus a label-dependent offset spread over a few fixed random directions, with a
+    per-sample random strength, so the classes overlap (ROC-AUC well below 1) as in the paper's ROC
+    figure.  The directions depend on task_seed only, so sets drawn with different seeds (training,
+    validation) come from the same population.  Returns (H float32 [n, d], y int32 [n])."""
+    rng = np.random.default_rng([seed, 0x5E1F])
+    y = (rng.random(n) < pos_rate).astype(np.int32)
+    dirs = np.random.default_rng([task_seed, d, 0xD125]).standard_normal((n_dirs, d))
+    dirs /= np.linalg.norm(dirs, axis=1, keepdims=True)
+    strength = shift * rng.gamma(2.0, 0.5, size=(n, n_dirs))          # mean 1, sample-dependent
+    sign = (2.0 * y - 1.0)[:, None]
+    H = rng.standard_normal((n, d), dtype=np.float32)
+    H += ((sign * strength) @ dirs / np.sqrt(n_dirs)).astype(np.float32)
+    return H, y
