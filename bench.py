@@ -122,6 +122,9 @@ def main() -> int:
     ap.add_argument("--cycle", action="store_true",
                     help="also time the whole speculate -> verify cycle: a 1B-shaped draft model proposes gamma tokens "
                          "(sj_draft_block), the target verifies them; adds a \"cycle\" object to the JSON line")
+    ap.add_argument("--judge-train", action="store_true",
+                    help="also time judge training (sj_judge_train) on a synthetic set of the paper's size (69,432 pairs of "
+                         "4096 features, the 10-value C grid); adds a \"judge_train\" object to the JSON line")
     ap.add_argument("--theta", type=float, default=0.5)
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
@@ -275,6 +278,43 @@ def main() -> int:
         sj.sj_kv_free(dkv)
         sj.sj_model_free(dmodel)
 
+    judge_train = None
+    if args.judge_train:
+        from oracle import judge_training_oracle as jt
+        n_t, n_v, d_t = 69432, 6944, shape.d_model
+        log(f"[bench] judge training: generating {n_t} + {n_v} pairs of {d_t} features ...")
+        Ht, yt = synth.make_judge_dataset(args.seed + 21, n_t, d_t)
+        Hv, yv = synth.make_judge_dataset(args.seed + 22, n_v, d_t)
+        Htd, ytd, Hvd, yvd = (torch.from_numpy(a).to(dev) for a in (Ht, yt, Hv, yv))
+        grid = jt.paper_c_grid()
+        sj.sj_judge_train(Htd, ytd, Hvd, yvd, grid[:1], stream)                      # warm-up
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        res = sj.sj_judge_train(Htd, ytd, Hvd, yvd, grid, stream)
+        fit_s = time.perf_counter() - t
+        passes = int(res["passes"].sum())
+        pass_bytes = n_t * d_t * 4
+        # the oracle beside it, on a bounded sample (its dense Hessian is cubic in d): one C
+        ns, ds = 8192, 512
+        Hs, ys = synth.make_judge_dataset(args.seed + 23, ns, ds)
+        t = time.perf_counter()
+        jt.fit_logistic(Hs, ys, float(grid[4]))
+        o_s = time.perf_counter() - t
+        Hsd, ysd = torch.from_numpy(Hs).to(dev), torch.from_numpy(ys).to(dev)
+        sj.sj_judge_train(Hsd, ysd, Hsd, ysd, grid[4:5], stream)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        sj.sj_judge_train(Hsd, ysd, Hsd, ysd, grid[4:5], stream)
+        g_s = time.perf_counter() - t
+        judge_train = {"n_train": n_t, "n_val": n_v, "d": d_t, "C_grid": [float(f"{c:.4g}") for c in grid], "dtype": "f64 on f32 features",
+                       "grid_fit_s": round(fit_s, 4), "passes_over_H": passes, "bytes_per_pass": pass_bytes,
+                       "s_per_pass_incl_solver": round(fit_s / passes, 6),
+                       "gbps_incl_solver": round(passes * pass_bytes / fit_s / 1e9, 1),
+                       "best_C": float(f"{grid[res['best_index']]:.4g}"), "val_auc": round(float(res["auc"].max()), 4),
+                       "theta_f1": round(res["theta_f1"], 4), "theta_recall": round(res["theta_recall"], 4),
+                       "sample_one_C": {"n": ns, "d": ds, "oracle_s": round(o_s, 3), "device_s": round(g_s, 4)}}
+        del Htd, Hvd
+
     out = {
         "metric": "verify_steps_per_s", "value": round(steps_per_s, 3), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -297,6 +337,8 @@ def main() -> int:
     }
     if cycle is not None:
         out["cycle"] = cycle
+    if judge_train is not None:
+        out["judge_train"] = judge_train
     sj.sj_kv_free(kv)
     sj.sj_model_free(model)
     if not args.no_cpu_baseline:

@@ -178,6 +178,33 @@ int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void* hidden,
                    const int32_t* draft_tokens, const float* draft_probs, const float* uniforms,
                    float judge_threshold, int32_t* accepted_len, int32_t* next_token, void* stream);
 
+/* Training of the judge verifier (Sec. 3.4 "Verifier Training", appendix "Training Logistic Regressor"):
+ * for every C of the grid, the L2-regularised logistic regression
+ *     min over (w, b) of  1/2 |w|^2 + C * sum_i log(1 + exp(-(2 y_i - 1) (w . h_i + b)))      (bias unpenalised)
+ * on the training pairs (h_i, y_i); the model with the best ROC-AUC on the validation pairs is kept (equal AUC:
+ * the earlier C), and two thresholds for Eq. 5 are chosen on its validation scores sigmoid(w . h + b):
+ *   theta_f1      best F1 of the rule "acceptable when score > theta" over theta in {0} and every validation
+ *                 score (equal F1: the smallest theta)                                  - the "-F" setting
+ *   theta_recall  the largest score of an unacceptable validation sample: the most permissive threshold that
+ *                 still rejects all of them                                             - the "-R" setting
+ * The paper's grid is 10 logarithmically spaced values from 1e-3 to 1e2.
+ *   H_train [n_train, d], H_val [n_val, d]   DEVICE, fp32, row-major, 16-byte aligned (the feature rows
+ *                                            sj_score_block / sj_debug_fetch return); d a multiple of 4, <= 8192
+ *   y_train [n_train], y_val [n_val]         DEVICE, int32, 1 = acceptable, 0 = not; both classes in each set
+ *   C_grid [n_C]                             HOST, positive
+ *   w_all [n_C, d + 1] (may be NULL)         HOST out: (w, b) of every C
+ *   auc [n_C]                                HOST out: validation ROC-AUC of every C
+ *   passes [n_C] (may be NULL)               HOST out: passes over H_train the solver made
+ *   best_index, w_best [d + 1], theta_f1, theta_recall   HOST out: the kept model (w, then b) and its thresholds
+ * Everything is computed on the device in fp64 (features read as fp32); the call allocates its workspace
+ * (about 8 (n_train + 3 n_val) + 2 MB * (d / 1024) bytes), synchronises `stream` and frees it before returning.
+ * Errors: SJ_EINVAL (null / misaligned pointer, sizes, a label other than 0 / 1, a set with one class only,
+ * non-positive C), SJ_ENOMEM, SJ_EHIP (also when the solver fails to converge). */
+int sj_judge_train(const float* H_train, const int32_t* y_train, int64_t n_train, const float* H_val,
+                   const int32_t* y_val, int64_t n_val, int32_t d, const double* C_grid, int32_t n_C,
+                   double* w_all, double* auc, int32_t* passes, int32_t* best_index, double* w_best,
+                   double* theta_f1, double* theta_recall, void* stream);
+
 /* Verifier variants of the paper's ablations and baselines, applied by the following steps:
  *   SJ_MODE_TWO_STAGE (default)  either test approves          (App. D.2)
  *   SJ_MODE_ALIGNMENT            Eq. 3 only (standard speculative decoding)

@@ -67,6 +67,7 @@ def load_library() -> C.CDLL:
         "sj_verify_head": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, f32, vp, vp, vp]),
         "sj_draft_block": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, vp]),
         "sj_score_block": (C.c_int, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
+        "sj_judge_train": (C.c_int, [vp, vp, C.c_int64, vp, vp, C.c_int64, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]),
         "sj_set_mode": (C.c_int, [vp, i32]),
         "sj_set_topk": (C.c_int, [vp, i32]),
         "sj_set_operand_planes": (C.c_int, [vp, i32]),
@@ -213,6 +214,26 @@ def sj_score_block(model: int, kv: int, n: int, input_tokens, target_tokens, log
                    stream=None) -> None:
     _check(load_library().sj_score_block(model, kv, n, _ptr(input_tokens), _ptr(target_tokens), _ptr(logprob), int(hidden_row),
                                          _ptr(hidden_out), _stream(stream)))
+
+
+def sj_judge_train(H_train, y_train, H_val, y_val, C_grid, stream=None) -> dict:
+    """Judge training on device tensors (fp32 features [n, d], int32 labels [n]); C_grid is a host sequence.
+    Returns the host-side outputs of the C call as a dict."""
+    n_train, d = H_train.shape
+    n_val = H_val.shape[0]
+    grid = np.ascontiguousarray(np.asarray(C_grid, np.float64))
+    n_C = grid.size
+    w_all = np.zeros((n_C, d + 1), np.float64)
+    auc = np.zeros(n_C, np.float64)
+    passes = np.zeros(n_C, np.int32)
+    w_best = np.zeros(d + 1, np.float64)
+    best = C.c_int32(-1)
+    th_f1, th_r = C.c_double(0.0), C.c_double(0.0)
+    _check(load_library().sj_judge_train(_ptr(H_train), _ptr(y_train), n_train, _ptr(H_val), _ptr(y_val), n_val, d,
+                                         grid.ctypes.data, n_C, w_all.ctypes.data, auc.ctypes.data, passes.ctypes.data,
+                                         C.byref(best), w_best.ctypes.data, C.byref(th_f1), C.byref(th_r), _stream(stream)))
+    return {"w_all": w_all, "auc": auc, "passes": passes, "best_index": best.value, "w": w_best[:d].copy(),
+            "b": float(w_best[d]), "theta_f1": th_f1.value, "theta_recall": th_r.value}
 
 
 def sj_set_mode(kv: int, mode: int) -> None:

@@ -8,7 +8,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsj.so")
-SOURCES = [os.path.join(HERE, "csrc", "sj_lib.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "sj_lib.hip"), os.path.join(HERE, "csrc", "sj_train.hip")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1335,5 +1335,11 @@ extern "C" int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, siz
     return SJ_OK;
 }
 
+// the library's other translation units report their errors through this
+__attribute__((visibility("hidden"))) int sj_set_error(int code, const char* msg) {
+    g_err = msg;
+    return code;
+}
+
 extern "C" const char* sj_last_error(void) { return g_err.c_str(); }
 extern "C" const char* sj_version(void) { return "sj-verify 0.1 (gfx950)"; }
