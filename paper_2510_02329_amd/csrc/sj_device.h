@@ -150,6 +150,12 @@ __device__ __forceinline__ void st_coh(unsigned long long* p, unsigned long long
 __device__ __forceinline__ unsigned ld_coh(const unsigned* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float ld_coh(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
+// Workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load (its fence drains the vector-memory counter), which would empty a prefetch
+// pipeline at each barrier; kernels that keep loads in flight across barriers order LDS themselves: data
+// written by direct global->LDS loads is covered by an explicit vmcnt wait of the loading wave.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 }  // namespace sj

@@ -74,12 +74,12 @@ __global__ __launch_bounds__((R2_CW + R2_LW) * 64) void gemm_rows2_kernel(GemmAr
         issue(min(1, nstage - 1));
         issue(min(2, nstage - 1));
         asm volatile("s_waitcnt vmcnt(32)" ::: "memory");          // stage 0 has landed
-        __syncthreads();
+        lds_barrier();
         for (int s = 0; s < nstage; ++s) {
             // buffer (s + 3) % 4 = (s - 1) % 4 was released by the barrier that ended iteration s - 1
             issue(min(s + 3, nstage - 1));
             asm volatile("s_waitcnt vmcnt(32)" ::: "memory");      // stage s + 1 has landed
-            __syncthreads();
+            lds_barrier();
         }
         wait_vm0();
         return;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__((R2_CW + R2_LW) * 64) void gemm_rows2_kernel(GemmAr
     };
 #pragma unroll
     for (int j = 0; j < R2_RING - 1; ++j) load_b(j, j);
-    __syncthreads();                                   // stage 0 is in LDS
+    lds_barrier();                                   // stage 0 is in LDS
     for (int s = 0; s < nstage; ++s) {
         const u32x4* Wb = &Ws[s % R2_NB][0][0][0];
 #pragma unroll
@@ -133,7 +133,7 @@ __global__ __launch_bounds__((R2_CW + R2_LW) * 64) void gemm_rows2_kernel(GemmAr
                 }
             }
         }
-        __syncthreads();                               // everyone is done with this buffer; the next one has landed
+        lds_barrier();                               // everyone is done with this buffer; the next one has landed
     }
 
     // ---- epilogue from the accumulators: lane holds columns nt*16 + 4g .. +3 of row m*16 + r

@@ -74,10 +74,6 @@ struct MegaArgs {
     double log_base;
 };
 
-// workgroup barrier that waits for LDS traffic only: outstanding global loads (the weight ring)
-// stay in flight across it
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
 // element offset inside a packed operand: row16 in 0..15 (0-7 hi plane of rows 0-7, 8-15 lo plane)
 __device__ __forceinline__ size_t packed_off(int row16, int k) {
     return ((size_t)(k >> 5) * 64 + (size_t)((k & 31) >> 3) * 16 + row16) * 8 + (k & 7);

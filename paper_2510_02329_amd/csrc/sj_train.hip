@@ -65,6 +65,10 @@ struct PassArgs {
     int d;
 };
 
+// Workgroup barrier that waits for this wave's LDS traffic only: __syncthreads() would also wait for the
+// next rows' loads, which are meant to stay in flight across the barriers of the current rows.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(256) void lr_pass_kernel(PassArgs a) {
             dot = wave_sum(dot);
             if (lane == 0) part[par][w][rb] = dot;
         }
-        __syncthreads();
+        lds_barrier();
         if (w < RB) {   // wave w finishes row w of the group (wave-uniform)
             const long long i = grp * RB + w;
             const double z = part[par][0][w] + part[par][1][w] + part[par][2][w] + part[par][3][w] + xb;
@@ -152,7 +156,7 @@ __global__ __launch_bounds__(256) void lr_pass_kernel(PassArgs a) {
             if (lane == 0) coef[par][w] = c;
         }
         if constexpr (MODE == PASS_SCORE) return;
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             const double c = coef[par][rb];
