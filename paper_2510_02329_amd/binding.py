@@ -49,6 +49,10 @@ def load_library() -> C.CDLL:
     path = lib_path()
     if not os.path.exists(path):
         raise SJError(SJ_EINVAL, f"{path} is not built; run `python -m paper_2510_02329_amd.build`")
+    # PyTorch owns the caller's device buffers and streams and ships its own HIP runtime: it has to be in the
+    # process before this library is, so that both use that one runtime (loaded the other way round, the
+    # library brings in the system's copy and its first HIP call finds no device).
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
     sig = {
