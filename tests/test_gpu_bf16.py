@@ -2,6 +2,7 @@
 tiles, ragged cache lengths, a batch) and the full 8B-shaped batch-1 workload the benchmark times."""
 import numpy as np
 import pytest
+import torch
 
 import paper_2510_02329_amd as sj
 import synth
@@ -138,9 +139,34 @@ def test_llama8b_batch1_full_size():
         W = helpers.oracle_weights(src, cache_items=0)
         caches = _fill_caches(shape, gpu, cfg, shape.kv_lengths(0), seed=0, capacity=cap)
         draft = synth.make_draft(shape, seed=0)
+        gamma, dev = shape.gamma, gpu.dev
+        len0, pend0 = sj.sj_kv_state(gpu.kv, 1)
+        # teacher-forced scoring of the same rows (Eq. 6 - 7): the state stays put, so the step below sees it unchanged
+        ins = np.concatenate([[caches[0].pending], draft["tokens"][0]]).astype(np.int32)[None]
+        tgt = np.concatenate([draft["tokens"][0], [17]]).astype(np.int32)[None]
+        lp = torch.zeros((1, gamma + 1), dtype=torch.float32, device=dev)
+        sj.sj_score_block(gpu.model, gpu.kv, gamma + 1, torch.from_numpy(ins).to(dev), torch.from_numpy(tgt).to(dev), lp)
+        torch.cuda.synchronize()
+        assert (np.array(sj.sj_kv_state(gpu.kv, 1)) == np.array([len0, pend0])).all()
         print("step", flush=True)
         out, ref, stats = _compare_step(shape, gpu, cfg, W, caches, draft, 0.5, "8B")
         print("8B logits max err %.3e worst err/bound %.2f" % stats["logits"], flush=True)
+        lg = ref[0]["logits"] / shape.temperature
+        lse = np.log(np.exp(lg - lg.max(axis=1, keepdims=True)).sum(axis=1)) + lg.max(axis=1)
+        lp_ref = lg[np.arange(gamma + 1), tgt[0]] - lse
+        a_tol, r_tol = G.TOL["bf16"]
+        lp_err = np.abs(lp.cpu().numpy()[0] - lp_ref).max()
+        print("8B teacher-forced log-probabilities max err %.3e" % lp_err, flush=True)
+        assert lp_err <= 2 * (a_tol + r_tol * np.abs(ref[0]["logits"]).max())
+        # top-k verification on the same state: decisions replayed by the oracle's tail on the device's logits
+        sj.sj_kv_rewind(gpu.kv, len0.tolist(), pend0.tolist())
+        sj.sj_set_mode(gpu.kv, sj.SJ_MODE_TOPK)
+        out_k = gpu.step(draft, 0.5)
+        tail = orc.verify_tail(out_k["logits"][0].astype(np.float64), out_k["judge_scores"][0], draft["tokens"][0],
+                               draft["probs"][0], draft["uniforms"][0], 0.5, shape.temperature, "topk", 2)
+        assert [(int(x) >> 2) & 1 for x in out_k["bits"][0]] == [int(t) for t in tail["topk_bits"]]
+        assert int(out_k["accepted_len"][0]) == tail["accepted_len"] and int(out_k["next_token"][0]) == tail["next_token"]
+        assert np.array_equal(out_k["logits"], out["logits"])               # the mode does not touch the forward
     finally:
         gpu.close()
 
