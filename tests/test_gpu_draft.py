@@ -31,12 +31,25 @@ def _device_draft(gpu, gamma, uniforms, feed_last=True):
 def test_draft_block_matches_oracle(dtype, batch, gamma, temperature):
     shape = dataclasses.replace(SMALL, name=f"draft_{dtype}", dtype=dtype, batch=batch, gamma=gamma, temperature=temperature)
     src = synth.WeightSource(shape, seed=5, norm_jitter=0.1)
-    lens = [40, 133, 7][:batch]
+    _draft_case(shape, src, [40, 133, 7][:batch], own_draws=True)
+
+
+def test_draft_block_1b_shaped_full_size():
+    """The draft model of the paper's Llama pairing at its real shape (16 layers, d 2048, 32/8 heads of 64, vocab
+    128256), cache 1024, gamma 5: the configuration `bench.py --cycle` times."""
+    shape = dataclasses.replace(synth.DRAFT_1B, batch=1, gamma=5)
+    src = synth.WeightSource(shape, seed=0)
+    print("loading the 1B-shaped draft model", flush=True)
+    _draft_case(shape, src, [1024], own_draws=False, cache_items=0)
+
+
+def _draft_case(shape, src, lens, own_draws, cache_items=None):
+    dtype, batch, gamma = shape.dtype, shape.batch, shape.gamma
     cap = [l + gamma + 20 for l in lens]
     gpu = G.Gpu(shape, src, cap)
     try:
         cfg = helpers.oracle_config(shape)
-        W = helpers.oracle_weights(src)
+        W = helpers.oracle_weights(src) if cache_items is None else helpers.oracle_weights(src, cache_items=cache_items)
         caches = _fill_caches(shape, gpu, cfg, lens, seed=6, capacity=cap)
         pend0 = [c.pending for c in caches]
         uniforms = np.random.default_rng(8).random((gamma, batch)).astype(np.float32)
@@ -72,6 +85,8 @@ def test_draft_block_matches_oracle(dtype, batch, gamma, temperature):
                 k, v = gpu.kv_rows(b, l, lens[b], gamma + 1)
                 G.close_enough(k, caches[b].k[l][:, lens[b]:lens[b] + gamma + 1], dtype, f"draft K seq {b} layer {l}")
                 G.close_enough(v, caches[b].v[l][:, lens[b]:lens[b] + gamma + 1], dtype, f"draft V seq {b} layer {l}")
+        if not own_draws:
+            return
         # 4. the oracle's own draft (drawing for itself) agrees on the tokens, except at near-ties of the CDF
         caches2 = _fill_caches(shape, gpu, cfg, lens, seed=6, capacity=cap)     # also resets the device state
         toks_ref, probs_ref = orc.draft_block(cfg, W, caches2, gamma, uniforms.astype(np.float64))
