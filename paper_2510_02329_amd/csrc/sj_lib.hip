@@ -404,12 +404,12 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         }
         kv->mpad = (G * (c.max_gamma + 1) + 63) / 64 * 64;   // whole groups of 4 MFMA tiles
         // key ranges of attention: one wave takes chunk_keys keys (at least one 32-key step, more when the
-        // total context would otherwise need more than 2048 waves: every range costs a partial
+        // total context would otherwise need more than 1024 waves: every range costs a partial
         // result and a share of the final merge), a workgroup 4 waves' worth
         {
             const int64_t total_keys = off / ((int64_t)c.n_kv_heads * hd);
             int ck = 32;
-            while (ck < 1024 && total_keys * c.n_kv_heads / ck > 2048) ck *= 2;
+            while (ck < 1024 && total_keys * c.n_kv_heads / ck > 1024) ck *= 2;
             if (const char* e = std::getenv("SJ_ATTN_CK")) { const int v = std::atoi(e); if (v >= 32 && v <= 4096 && (v & (v - 1)) == 0) ck = v; }
             kv->chunk_keys = ck;
             kv->nchunk_max = (cap_max + 4 * ck - 1) / (4 * ck);
