@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
                                                          const float* __restrict__ cs, KvView<T> kv, int layer,
                                                          int wave_keys, int nchunk_max, float* __restrict__ opart,
                                                          unsigned* __restrict__ tickets, T* __restrict__ attn_out,
-                                                         size_t aplane) {
+                                                         size_t aplane, int otks) {
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
     constexpr int NS = KF / 4;       // S^T tiles per step of KSTEP keys
     static_assert(SPL <= Traits<T>::NS, "more planes than the storage type has");
@@ -436,8 +436,8 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
 
     auto write_out = [&](int mq, int ht, const float (&v)[4]) {
         if (rowvalid[mq]) {
-            const size_t row = (size_t)bi * rps + jrow[mq];
-            Traits<T>::store_split4(attn_out + (row * md.Hq + kvh * md.G + girow[mq]) * HD + ht * 16 + 4 * g, aplane, v);
+            const int row = bi * rps + jrow[mq];
+            Traits<T>::store_split4(attn_out + opnd_off<T>(row, (kvh * md.G + girow[mq]) * HD + ht * 16 + 4 * g, md.Hq * HD, otks), aplane, v);
         }
     };
 

@@ -23,6 +23,8 @@
 // MFMA convention as in the few-row kernel: A = weight fragment (rows = n), B = operand fragment
 // (rows = m), lane 16g + r then holds D[n = 4g + i][m = r].
 #pragma once
+#include <type_traits>
+
 #include "sj_kernels.h"
 
 namespace sj {
@@ -35,6 +37,68 @@ constexpr int R2_KB = 4;           // k-steps per stage
 constexpr int R2_NB = 4;           // LDS stage buffers
 constexpr int R2_MTW = 3;          // row tiles per compute wave (4 waves x 3 >= 9 row tiles)
 constexpr int R2_RING = 4;         // operand ring (k-steps) = k-steps per stage
+
+// s_waitcnt vmcnt(n) with the other counters left alone (vmcnt sits in bits 3:0 and 15:14)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// Epilogue of the many-row kernels from the accumulators: lane holds columns nt*16 + 4g .. +3 of row
+// m*16 + r; wave w owns row tiles w, w + 4, w + 8.
+template <typename T, int EPI>
+__device__ __forceinline__ void rows_epilogue(const GemmArgs& a, const f32x4 (&acc)[R2_MTW][R2_NT], int w, int my_tiles, int nt0,
+                                              int ntiles, int r, int g) {
+#pragma unroll
+    for (int i = 0; i < R2_MTW; ++i) {
+        if (i >= my_tiles) continue;                       // wave-uniform
+        const int row = (w + R2_CW * i) * 16 + r;
+        const bool valid = row < a.R;
+#pragma unroll
+        for (int t = 0; t < R2_NT; ++t) {
+            const int nt = nt0 + t;
+            if (nt >= ntiles) continue;                    // uniform
+            const f32x4 v = acc[i][t];
+            if constexpr (EPI == EPI_PARTIAL) {
+                if (valid)
+                    *reinterpret_cast<f32x4*>(a.out + ((size_t)blockIdx.y * a.slice_rows + row) * a.N + (size_t)nt * 16 + 4 * g) = v;
+            } else if constexpr (EPI == EPI_SWIGLU) {
+                // tile rows 0-7 are gate of FFN columns 8*nt .. 8*nt+7, rows 8-15 their up projections:
+                // the up value of this lane's gate sits two lane groups further
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float up = __shfl_down(v[e], 32, 64);
+                    const float gate = v[e];
+                    y[e] = gate / (1.0f + expf(-gate)) * up;
+                }
+                if (valid && g < 2)
+                    Traits<T>::store_split4(reinterpret_cast<T*>(a.act) + opnd_off<T>(row, nt * 8 + 4 * g, a.N / 2, a.act_tks), a.actplane, y);
+            } else {
+                // logits + this tile's softmax partial of the row (max, sum exp((l - max)/T), lowest arg-max)
+                float mx = v[0];
+                int arg = nt * 16 + 4 * g;
+#pragma unroll
+                for (int e = 1; e < 4; ++e)
+                    if (v[e] > mx) { mx = v[e]; arg = nt * 16 + 4 * g + e; }
+#pragma unroll
+                for (int o = 16; o < 64; o <<= 1) {
+                    const float omx = __shfl_xor(mx, o, 64);
+                    const int oarg = __shfl_xor(arg, o, 64);
+                    if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+                }
+                float se = 0.f;
+                if (a.inv_temp > 0.f) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) se += expf((v[e] - mx) * a.inv_temp);
+                    se += __shfl_xor(se, 16, 64);
+                    se += __shfl_xor(se, 32, 64);
+                }
+                if (valid) {
+                    *reinterpret_cast<f32x4*>(a.out + (size_t)row * a.N + (size_t)nt * 16 + 4 * g) = v;
+                    if (g == 0) a.stats[(size_t)row * ntiles + nt] = float4{mx, se, __int_as_float(arg), 0.f};
+                }
+            }
+        }
+    }
+}
 
 template <typename T, int EPI, int SPL>
 __global__ __launch_bounds__((R2_CW + R2_LW) * 64) void gemm_rows2_kernel(GemmArgs a, int mt) {
@@ -136,59 +200,141 @@ __global__ __launch_bounds__((R2_CW + R2_LW) * 64) void gemm_rows2_kernel(GemmAr
         lds_barrier();                               // everyone is done with this buffer; the next one has landed
     }
 
-    // ---- epilogue from the accumulators: lane holds columns nt*16 + 4g .. +3 of row m*16 + r
+    rows_epilogue<T, EPI>(a, acc, w, my_tiles, nt0, ntiles, r, g);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Same product with the OPERAND delivered through LDS as well (one or two operand planes).
+// Measured on the kernel above: with the compute waves' own operand loads taken out it runs at
+// max(weight stream, MFMA), with them near the sum - a compute unit's loads come back in issue
+// order, so every operand load (an L2 hit by itself) waits behind the ~96 KB of weight loads in
+// flight.  Here the loader waves fetch the operand fragments of all row tiles together with the
+// weight tiles of the same k-step, so both arrive in the same stream with the same lead, and the
+// compute waves issue no global loads at all.  A stage is ONE k-step: 8 weight tiles (8 KB) +
+// 9 row tiles x SPL planes of operand fragments (1 KB each), six stages fill the LDS; one barrier
+// per k-step.  An operand fragment in LDS has the layout the lanes read it in (lane l: 16 bytes at
+// l * 16), which is also how a direct global->LDS load of 16 bytes per lane deposits it.
+constexpr int R4_NS = 6;           // stages (k-steps) in LDS
+constexpr int R4_LW = 4;           // loader waves
+
+template <typename T, int EPI, int SPL>
+__global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmArgs a, int mt) {
+    static_assert(SPL <= 2, "three operand planes do not fit six stages");
+    constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
+    constexpr int NX = ROWS_MT * SPL;                  // operand fragments per stage
+    constexpr int NI = R2_NT + NX;                     // 1 KB items per stage
+    __shared__ u32x4 Ls[R4_NS][NI][64];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int KS = a.K / KSTEP, ntiles = a.N / 16;
+    const int nt0 = blockIdx.x * R2_NT;
+    const int ks0 = (int)((long long)blockIdx.y * KS / gridDim.y), ks1 = (int)((long long)(blockIdx.y + 1) * KS / gridDim.y);
+    const int nks = ks1 - ks0;
+    if (nks <= 0) return;                              // uniform for the workgroup
+
+    if (w >= R2_CW) {
+        // ---------------- loader waves: item i of a stage goes to wave i % 4 -------------------------------
+        const int lw = w - R2_CW;
+        auto run = [&](auto nl_tag) {
+            constexpr int NL = decltype(nl_tag)::value;               // items of this wave per stage
+            // per-item source pointer at k-step 0 of the slice and its stride per k-step
+            const char* src[NL];
+            size_t step[NL];
 #pragma unroll
-    for (int i = 0; i < R2_MTW; ++i) {
-        if (i >= my_tiles) continue;                       // wave-uniform
-        const int row = (w + R2_CW * i) * 16 + r;
-        const bool valid = row < a.R;
-#pragma unroll
-        for (int t = 0; t < R2_NT; ++t) {
-            const int nt = nt0 + t;
-            if (nt >= ntiles) continue;                    // uniform
-            const f32x4 v = acc[i][t];
-            if constexpr (EPI == EPI_PARTIAL) {
-                if (valid)
-                    *reinterpret_cast<f32x4*>(a.out + ((size_t)blockIdx.y * a.slice_rows + row) * a.N + (size_t)nt * 16 + 4 * g) = v;
-            } else if constexpr (EPI == EPI_SWIGLU) {
-                // tile rows 0-7 are gate of FFN columns 8*nt .. 8*nt+7, rows 8-15 their up projections:
-                // the up value of this lane's gate sits two lane groups further
-                float y[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float up = __shfl_down(v[e], 32, 64);
-                    const float gate = v[e];
-                    y[e] = gate / (1.0f + expf(-gate)) * up;
-                }
-                if (valid && g < 2)
-                    Traits<T>::store_split4(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)nt * 8 + 4 * g, a.actplane, y);
-            } else {
-                // logits + this tile's softmax partial of the row (max, sum exp((l - max)/T), lowest arg-max)
-                float mx = v[0];
-                int arg = nt * 16 + 4 * g;
-#pragma unroll
-                for (int e = 1; e < 4; ++e)
-                    if (v[e] > mx) { mx = v[e]; arg = nt * 16 + 4 * g + e; }
-#pragma unroll
-                for (int o = 16; o < 64; o <<= 1) {
-                    const float omx = __shfl_xor(mx, o, 64);
-                    const int oarg = __shfl_xor(arg, o, 64);
-                    if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
-                }
-                float se = 0.f;
-                if (a.inv_temp > 0.f) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) se += expf((v[e] - mx) * a.inv_temp);
-                    se += __shfl_xor(se, 16, 64);
-                    se += __shfl_xor(se, 32, 64);
-                }
-                if (valid) {
-                    *reinterpret_cast<f32x4*>(a.out + (size_t)row * a.N + (size_t)nt * 16 + 4 * g) = v;
-                    if (g == 0) a.stats[(size_t)row * ntiles + nt] = float4{mx, se, __int_as_float(arg), 0.f};
+            for (int j = 0; j < NL; ++j) {
+                const int it = lw + R4_LW * j;
+                if (it < R2_NT) {                                     // weight tile (tiles past N re-read the last)
+                    const size_t tile = (size_t)min(nt0 + it, ntiles - 1);
+                    src[j] = reinterpret_cast<const char*>(a.Wt) + ((tile * KS + ks0) * 64 + lane) * 16;
+                    step[j] = 1024;
+                } else {                                              // operand fragment (row tile m, plane p)
+                    const int m = (it - R2_NT) / SPL, p = (it - R2_NT) % SPL;
+                    const T* plane = reinterpret_cast<const T*>(a.X) + (size_t)p * a.xplane;
+                    if (a.x_tks) {                                    // fragment-tiled plane: 1 KB per (row tile, k-step)
+                        const size_t mt_ok = m * 16 < a.R ? m : 0;    // whole tiles past R re-read tile 0
+                        src[j] = reinterpret_cast<const char*>(plane + ((mt_ok * a.x_tks + ks0) * 64 + lane) * KF);
+                        step[j] = 1024;
+                    } else {
+                        const int row = m * 16 + r;
+                        src[j] = reinterpret_cast<const char*>(plane + (size_t)(row < a.R ? row : 0) * a.ldx + (size_t)ks0 * KSTEP + g * KF);
+                        step[j] = (size_t)KSTEP * sizeof(T);
+                    }
                 }
             }
+            auto issue = [&](int s) {                                 // stage s = k-step s of the slice (clamped)
+                const size_t k = (size_t)min(s, nks - 1);
+#pragma unroll
+                for (int j = 0; j < NL; ++j)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + k * step[j]),
+                                                     (__attribute__((address_space(3))) void*)(&Ls[s % R4_NS][lw + R4_LW * j][0]), 16, 0, 0);
+            };
+            // stages are always issued (clamped), so the loads outstanding behind the stage that has to be
+            // complete are known.  The compute waves read stage s + 1 into registers while they multiply
+            // stage s, so stage s + 2 has to be in LDS when iteration s ends: R4_NS - 3 stages of NL loads
+            // may still be in flight.
+            constexpr int BEHIND = (R4_NS - 3) * NL;
+            static_assert((R4_NS - 1) * NL < 64, "the load counter holds 63");
+#pragma unroll
+            for (int s = 0; s < R4_NS - 1; ++s) issue(s);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(BEHIND));            // stages 0 and 1 have landed
+            lds_barrier();
+            for (int s = 0; s < nks; ++s) {
+                // buffer (s + 5) % 6 = (s - 1) % 6: its fragments went to registers during iteration s - 2
+                issue(s + R4_NS - 1);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(BEHIND));        // stage s + 2 has landed
+                lds_barrier();
+            }
+            wait_vm0();
+        };
+        constexpr int NL_HI = (NI + R4_LW - 1) / R4_LW, NL_LO = NI / R4_LW;
+        if (lw < NI % R4_LW || NI % R4_LW == 0) run(std::integral_constant<int, NL_HI>{});
+        else run(std::integral_constant<int, NL_LO>{});
+        return;
+    }
+
+    // ---------------- compute waves: row tiles w, w + 4, w + 8 ----------------
+    const int my_tiles = (mt > w) ? (mt - w + R2_CW - 1) / R2_CW : 0;
+    f32x4 acc[R2_MTW][R2_NT];
+#pragma unroll
+    for (int i = 0; i < R2_MTW; ++i)
+#pragma unroll
+        for (int t = 0; t < R2_NT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // two register sets of fragments: the next k-step is read from LDS while the current one is multiplied
+    Frag wfA[R2_NT], bqA[R2_MTW][SPL], wfB[R2_NT], bqB[R2_MTW][SPL];
+    auto fetch = [&](Frag (&wf)[R2_NT], Frag (&bq)[R2_MTW][SPL], int s) {
+        const u32x4* St = &Ls[s % R4_NS][0][0];       // a stage past the end holds a copy of the last one
+#pragma unroll
+        for (int i = 0; i < R2_MTW; ++i)
+#pragma unroll
+            for (int sp = 0; sp < SPL; ++sp) bq[i][sp].u = St[(R2_NT + min(w + R2_CW * i, ROWS_MT - 1) * SPL + sp) * 64 + lane];
+#pragma unroll
+        for (int t = 0; t < R2_NT; ++t) wf[t].u = St[t * 64 + lane];
+    };
+    auto multiply = [&](const Frag (&wf)[R2_NT], const Frag (&bq)[R2_MTW][SPL]) {
+#pragma unroll
+        for (int i = 0; i < R2_MTW; ++i) {
+            if (i < my_tiles) {
+#pragma unroll
+                for (int sp = 0; sp < SPL; ++sp)
+#pragma unroll
+                    for (int t = 0; t < R2_NT; ++t) Traits<T>::mma(wf[t], bq[i][sp], acc[i][t]);
+            }
+        }
+    };
+    lds_barrier();                                     // stages 0 and 1 are in LDS
+    fetch(wfA, bqA, 0);
+    for (int s = 0; s < nks; s += 2) {
+        fetch(wfB, bqB, s + 1);
+        multiply(wfA, bqA);
+        lds_barrier();                                 // stage s + 2 has landed
+        if (s + 1 < nks) {                             // uniform
+            fetch(wfA, bqA, s + 2);
+            multiply(wfB, bqB);
+            lds_barrier();                             // stage s + 3 has landed
         }
     }
+    rows_epilogue<T, EPI>(a, acc, w, my_tiles, nt0, ntiles, r, g);
 }
 
 }  // namespace sj

@@ -152,7 +152,7 @@ template <typename T>
 __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(int R, int d, float eps, float* __restrict__ x,
                                                            const float* __restrict__ part, int nparts,
                                                            const T* __restrict__ gain, T* __restrict__ xn,
-                                                           size_t xplane, float* __restrict__ xn32) {
+                                                           size_t xplane, float* __restrict__ xn32, int tks) {
     // one workgroup of 1024 threads per row, 4 columns per thread and pass; all loads of a pass are
     // independent.  Rows wider than 16384 columns are not supported (host-checked).
     constexpr int MAXP = 4;
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(int R, int d, float e
             float y[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) y[i] = v[p][i] * inv * Traits<T>::load(gain + c + i);
-            Traits<T>::store_split4(xn + (size_t)r * d + c, xplane, y);
+            Traits<T>::store_split4(xn + opnd_off<T>(r, c, d, tks), xplane, y);
             if (xn32) *reinterpret_cast<f32x4*>(xn32 + (size_t)r * d + c) = f32x4{y[0], y[1], y[2], y[3]};
         }
     }
@@ -219,6 +219,8 @@ struct GemmArgs {
     void* act;          // EPI_SWIGLU: [MT*16][N/2] storage dtype = silu(gate) * up
     float4* stats;      // EPI_LOGITS: [R][gridDim.x] (max, sum exp((l-max)/T), argmax as float bits, 0)
     float inv_temp;     // 1/T, 0 when T = 0
+    int32_t x_tks;      // 0: X planes are row-major; else K / KSTEP: fragment-tiled planes (opnd_off)
+    int32_t act_tks;    // same for act (its K is N/2)
 };
 
 #ifdef SJ_GEMM_PROF

@@ -673,8 +673,10 @@ static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, in
 // of EPI_LOGITS are per n-tile there ([rows][N/16]).
 template <typename T, int EPI, int SPL>
 static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
-                     float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
+                     float* out, void* act, size_t actplane, float4* stats, float inv_temp, bool tiled) {
     const int ntiles = N / 16;
+    // fragment-tiled operand planes: a group of 144 rows starts row0 * K elements into the plane in either layout
+    if (tiled && ldx != K) return fail(SJ_EINVAL, "a tiled operand has no padding between rows");
     for (int row0 = 0; row0 < rows; row0 += ROWS_MT * 16) {
         const int nr = std::min(ROWS_MT * 16, rows - row0);
         GemmArgs a{};
@@ -684,10 +686,14 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
         a.ldx = ldx; a.K = K; a.N = N;
         a.R = nr; a.slice_rows = rows;
         a.inv_temp = inv_temp;
+        a.x_tks = tiled ? K / Traits<T>::KSTEP : 0;
+        a.act_tks = tiled ? (N / 2) / Traits<T>::KSTEP : 0;
         if (EPI == EPI_PARTIAL) a.out = out + (size_t)row0 * N;            // [split][rows][N]
         else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ntiles; }
         else a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
-        gemm_rows2_kernel<T, EPI, SPL><<<dim3((ntiles + R2_NT - 1) / R2_NT, EPI == EPI_PARTIAL ? split : 1), (R2_CW + R2_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
+        const dim3 grid((ntiles + R2_NT - 1) / R2_NT, EPI == EPI_PARTIAL ? split : 1);
+        if constexpr (SPL <= 2) gemm_rows4_kernel<T, EPI, SPL><<<grid, (R2_CW + R4_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
+        else gemm_rows2_kernel<T, EPI, SPL><<<grid, (R2_CW + R2_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
         LAUNCHCHK("gemm_rows");
     }
     return SJ_OK;
@@ -707,8 +713,12 @@ struct Runner {
         return v;
     }
     size_t plane(int ld) const { return (size_t)kv->rpad * ld; }
+    // Operand planes are written as MFMA fragments when the many-row kernel that reads operands through LDS
+    // consumes them (more than FEW_ROWS rows, at most two planes); row-major otherwise.
+    bool tiled() const { return R > FEW_ROWS && SPL <= 2; }
+    int tks(int K) const { return tiled() ? K / Traits<T>::KSTEP : 0; }
     int partial_gemm(const void* W, const void* X, int ldx, int K, int N, const GemmPlan (&pl)[2]) {
-        if (R > FEW_ROWS) return gemm_rows<T, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, pl[1].split, kv->part, nullptr, 0, nullptr, 0.f);
+        if (R > FEW_ROWS) return gemm_rows<T, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, pl[1].split, kv->part, nullptr, 0, nullptr, 0.f, tiled());
         const GemmPlan& p = pl[0];
         if (p.nt == 3 && p.waves == 8)
             return gemm<T, 3, EPI_PARTIAL, SPL, 8>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
@@ -724,7 +734,7 @@ struct Runner {
     // number of workgroups per CU (2F/16 = 1792 tiles -> 256 workgroups), else 8
     int gate_up(const void* W) {
         const ModelDims& md = m->md;
-        if (R > FEW_ROWS) return gemm_rows<T, EPI_SWIGLU, SPL>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
+        if (R > FEW_ROWS) return gemm_rows<T, EPI_SWIGLU, SPL>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f, tiled());
         if ((2 * md.F / 16) % 7 == 0)
             return gemm<T, 7, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
         return gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
@@ -744,7 +754,7 @@ struct Runner {
 #define ATTN(HD, MQ)                                                                                                   \
     attn_fused_kernel<T, HD, MQ, SPL><<<grid, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->plan_qkv), R, kv->cs, view(), \
                                                             layer, kv->chunk_keys, kv->nchunk_max, kv->opart, kv->tickets,      \
-                                                            (T*)kv->attn_out, plane(md.Hq * md.hd))
+                                                            (T*)kv->attn_out, plane(md.Hq * md.hd), tks(md.Hq * md.hd))
         if (md.hd == 128) {
             switch (mq) { case 1: ATTN(128, 1); break; case 2: ATTN(128, 2); break; case 3: ATTN(128, 3); break; default: ATTN(128, 4); }
         } else {
@@ -768,7 +778,7 @@ struct Runner {
         for (int l = 0; l < c.n_layers; ++l) {
             const LayerW& L = m->layers[l];
             add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)L.attn_norm,
-                                                      (T*)kv->xn, plane(d), nullptr);
+                                                      (T*)kv->xn, plane(d), nullptr, tks(d));
             LAUNCHCHK("add_rmsnorm");
             if ((rc = time_mark(kv, 1, st))) return rc;
             if ((rc = partial_gemm(L.wqkv, kv->xn, d, d, Nqkv, kv->plan_qkv))) return rc;
@@ -778,7 +788,7 @@ struct Runner {
             if ((rc = partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->plan_o))) return rc;
             if ((rc = time_mark(kv, 2, st))) return rc;
             add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, nparts(kv->plan_o), (const T*)L.ffn_norm,
-                                                      (T*)kv->xn, plane(d), nullptr);
+                                                      (T*)kv->xn, plane(d), nullptr, tks(d));
             LAUNCHCHK("add_rmsnorm");
             if ((rc = time_mark(kv, 3, st))) return rc;
             if ((rc = gate_up(L.wgu))) return rc;
@@ -789,7 +799,7 @@ struct Runner {
             pending_parts = nparts(kv->plan_d);
         }
         add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)m->final_norm,
-                                                  (T*)kv->xn, plane(d), kv->hn32);
+                                                  (T*)kv->xn, plane(d), kv->hn32, tks(d));
         LAUNCHCHK("add_rmsnorm");
         return SJ_OK;
     }
@@ -801,8 +811,8 @@ struct Runner {
         int rc, nblk;
         if (R > FEW_ROWS) {
             rc = exact_operand
-                ? gemm_rows<T, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
-                : gemm_rows<T, EPI_LOGITS, SPL>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
+                ? gemm_rows<T, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp, false)
+                : gemm_rows<T, EPI_LOGITS, SPL>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp, tiled());
             nblk = md.V / 16;
         } else {
             rc = exact_operand
