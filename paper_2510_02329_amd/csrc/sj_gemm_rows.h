@@ -206,24 +206,27 @@ __global__ __launch_bounds__((R2_CW + R2_LW) * 64) void gemm_rows2_kernel(GemmAr
 // ---------------------------------------------------------------------------------------------
 // Same product with the OPERAND delivered through LDS as well (one or two operand planes).
 // Measured on the kernel above: with the compute waves' own operand loads taken out it runs at
-// max(weight stream, MFMA), with them near the sum - a compute unit's loads come back in issue
-// order, so every operand load (an L2 hit by itself) waits behind the ~96 KB of weight loads in
-// flight.  Here the loader waves fetch the operand fragments of all row tiles together with the
-// weight tiles of the same k-step, so both arrive in the same stream with the same lead, and the
-// compute waves issue no global loads at all.  A stage is ONE k-step: 8 weight tiles (8 KB) +
-// 9 row tiles x SPL planes of operand fragments (1 KB each), six stages fill the LDS; one barrier
-// per k-step.  An operand fragment in LDS has the layout the lanes read it in (lane l: 16 bytes at
-// l * 16), which is also how a direct global->LDS load of 16 bytes per lane deposits it.
-constexpr int R4_NS = 6;           // stages (k-steps) in LDS
-constexpr int R4_LW = 4;           // loader waves
+// max(weight stream, MFMA), with them near the sum, and a row-major operand fragment touches 16 cache
+// lines of which it uses half.  Here the compute waves issue no global loads at all: loader waves
+// fetch the operand fragments of all row tiles next to the weight tiles of the same k-step, from
+// planes that the producing kernels wrote as fragments (opnd_off: 1 KB of consecutive memory each;
+// row-major planes are still accepted).  A stage is ONE k-step; a wave's loads come back in the order
+// it issued them, so weights (HBM: 8 stages of 8 KB) and operand (an L2 hit: 5 stages of
+// 9 x SPL KB) are fetched by different loader waves with rings of their own; one barrier per k-step;
+// the compute waves read the fragments of step s + 1 from LDS while they multiply step s.  An
+// operand fragment in LDS has the layout the lanes read it in (lane l: 16 bytes at l * 16), which is
+// also how a direct global->LDS load of 16 bytes per lane deposits it.
+constexpr int R4_NSW = 8;          // weight stages (k-steps) in LDS: HBM latency to cover
+constexpr int R4_NSX = 5;          // operand stages: an L2 hit away
+constexpr int R4_LW = 4;           // loader waves: two for the weights, two for the operand
 
 template <typename T, int EPI, int SPL>
 __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmArgs a, int mt) {
-    static_assert(SPL <= 2, "three operand planes do not fit six stages");
+    static_assert(SPL <= 2, "three operand planes do not fit");
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
     constexpr int NX = ROWS_MT * SPL;                  // operand fragments per stage
-    constexpr int NI = R2_NT + NX;                     // 1 KB items per stage
-    __shared__ u32x4 Ls[R4_NS][NI][64];
+    __shared__ u32x4 Wst[R4_NSW][R2_NT][64];           // 64 KB
+    __shared__ u32x4 Xst[R4_NSX][NX][64];              // 90 KB with two planes
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g = lane >> 4;
     const int KS = a.K / KSTEP, ntiles = a.N / 16;
@@ -233,62 +236,67 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
     if (nks <= 0) return;                              // uniform for the workgroup
 
     if (w >= R2_CW) {
-        // ---------------- loader waves: item i of a stage goes to wave i % 4 -------------------------------
+        // ---------------- loader waves ----------------
+        // A wave's loads come back in the order it issued them, so the weights (HBM, deep ring) and the
+        // operand (L2, shallow ring) are fetched by different waves.  Stage = k-step of the slice (clamped:
+        // a stage past the end re-reads the last one into its own buffer).  NS = ring depth of the wave's
+        // stream; the compute waves read stage s + 1 while they multiply stage s, so stage s + 2 has to
+        // be in LDS when iteration s ends: NS - 3 stages of the wave's loads may still be in flight.
         const int lw = w - R2_CW;
-        auto run = [&](auto nl_tag) {
-            constexpr int NL = decltype(nl_tag)::value;               // items of this wave per stage
-            // per-item source pointer at k-step 0 of the slice and its stride per k-step
+        auto run = [&](auto nl_tag, auto ns_tag, auto make_src, auto dst_of) {
+            constexpr int NL = decltype(nl_tag)::value, NS = decltype(ns_tag)::value;
             const char* src[NL];
             size_t step[NL];
 #pragma unroll
-            for (int j = 0; j < NL; ++j) {
-                const int it = lw + R4_LW * j;
-                if (it < R2_NT) {                                     // weight tile (tiles past N re-read the last)
-                    const size_t tile = (size_t)min(nt0 + it, ntiles - 1);
-                    src[j] = reinterpret_cast<const char*>(a.Wt) + ((tile * KS + ks0) * 64 + lane) * 16;
-                    step[j] = 1024;
-                } else {                                              // operand fragment (row tile m, plane p)
-                    const int m = (it - R2_NT) / SPL, p = (it - R2_NT) % SPL;
-                    const T* plane = reinterpret_cast<const T*>(a.X) + (size_t)p * a.xplane;
-                    if (a.x_tks) {                                    // fragment-tiled plane: 1 KB per (row tile, k-step)
-                        const size_t mt_ok = m * 16 < a.R ? m : 0;    // whole tiles past R re-read tile 0
-                        src[j] = reinterpret_cast<const char*>(plane + ((mt_ok * a.x_tks + ks0) * 64 + lane) * KF);
-                        step[j] = 1024;
-                    } else {
-                        const int row = m * 16 + r;
-                        src[j] = reinterpret_cast<const char*>(plane + (size_t)(row < a.R ? row : 0) * a.ldx + (size_t)ks0 * KSTEP + g * KF);
-                        step[j] = (size_t)KSTEP * sizeof(T);
-                    }
-                }
-            }
-            auto issue = [&](int s) {                                 // stage s = k-step s of the slice (clamped)
+            for (int j = 0; j < NL; ++j) make_src(j, src[j], step[j]);
+            auto issue = [&](int s) {
                 const size_t k = (size_t)min(s, nks - 1);
 #pragma unroll
                 for (int j = 0; j < NL; ++j)
                     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + k * step[j]),
-                                                     (__attribute__((address_space(3))) void*)(&Ls[s % R4_NS][lw + R4_LW * j][0]), 16, 0, 0);
+                                                     (__attribute__((address_space(3))) void*)dst_of(s % NS, j), 16, 0, 0);
             };
-            // stages are always issued (clamped), so the loads outstanding behind the stage that has to be
-            // complete are known.  The compute waves read stage s + 1 into registers while they multiply
-            // stage s, so stage s + 2 has to be in LDS when iteration s ends: R4_NS - 3 stages of NL loads
-            // may still be in flight.
-            constexpr int BEHIND = (R4_NS - 3) * NL;
-            static_assert((R4_NS - 1) * NL < 64, "the load counter holds 63");
+            constexpr int BEHIND = (NS - 3) * NL;
+            static_assert((NS - 1) * NL < 64, "the load counter holds 63");
 #pragma unroll
-            for (int s = 0; s < R4_NS - 1; ++s) issue(s);
+            for (int s = 0; s < NS - 1; ++s) issue(s);
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(BEHIND));            // stages 0 and 1 have landed
             lds_barrier();
             for (int s = 0; s < nks; ++s) {
-                // buffer (s + 5) % 6 = (s - 1) % 6: its fragments went to registers during iteration s - 2
-                issue(s + R4_NS - 1);
+                // buffer (s + NS - 1) % NS = (s - 1) % NS: its fragments went to registers during iteration s - 2
+                issue(s + NS - 1);
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(BEHIND));        // stage s + 2 has landed
                 lds_barrier();
             }
             wait_vm0();
         };
-        constexpr int NL_HI = (NI + R4_LW - 1) / R4_LW, NL_LO = NI / R4_LW;
-        if (lw < NI % R4_LW || NI % R4_LW == 0) run(std::integral_constant<int, NL_HI>{});
-        else run(std::integral_constant<int, NL_LO>{});
+        if (lw < 2) {                                                 // weight tiles lw, lw + 2, ..
+            auto make_src = [&](int j, const char*& sp, size_t& st) {
+                const size_t tile = (size_t)min(nt0 + lw + 2 * j, ntiles - 1);      // tiles past N re-read the last
+                sp = reinterpret_cast<const char*>(a.Wt) + ((tile * KS + ks0) * 64 + lane) * 16;
+                st = 1024;
+            };
+            auto dst_of = [&](int buf, int j) { return &Wst[buf][lw + 2 * j][0]; };
+            run(std::integral_constant<int, R2_NT / 2>{}, std::integral_constant<int, R4_NSW>{}, make_src, dst_of);
+        } else {                                                      // operand fragments x, x + 2, ..
+            const int x = lw - 2;
+            auto make_src = [&](int j, const char*& sp, size_t& st) {
+                const int it = min(x + 2 * j, NX - 1);                // an odd count: the last wave repeats the last item
+                const int m = it / SPL, p = it % SPL;
+                const T* plane = reinterpret_cast<const T*>(a.X) + (size_t)p * a.xplane;
+                if (a.x_tks) {                                        // fragment-tiled plane: 1 KB per (row tile, k-step)
+                    const size_t mt_ok = m * 16 < a.R ? m : 0;        // whole tiles past R re-read tile 0
+                    sp = reinterpret_cast<const char*>(plane + ((mt_ok * a.x_tks + ks0) * 64 + lane) * KF);
+                    st = 1024;
+                } else {
+                    const int row = m * 16 + r;
+                    sp = reinterpret_cast<const char*>(plane + (size_t)(row < a.R ? row : 0) * a.ldx + (size_t)ks0 * KSTEP + g * KF);
+                    st = (size_t)KSTEP * sizeof(T);
+                }
+            };
+            auto dst_of = [&](int buf, int j) { return &Xst[buf][min(x + 2 * j, NX - 1)][0]; };
+            run(std::integral_constant<int, (NX + 1) / 2>{}, std::integral_constant<int, R4_NSX>{}, make_src, dst_of);
+        }
         return;
     }
 
@@ -303,13 +311,15 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
     // two register sets of fragments: the next k-step is read from LDS while the current one is multiplied
     Frag wfA[R2_NT], bqA[R2_MTW][SPL], wfB[R2_NT], bqB[R2_MTW][SPL];
     auto fetch = [&](Frag (&wf)[R2_NT], Frag (&bq)[R2_MTW][SPL], int s) {
-        const u32x4* St = &Ls[s % R4_NS][0][0];       // a stage past the end holds a copy of the last one
+        // a stage past the end holds a copy of the last one
+        const u32x4* Xs = &Xst[s % R4_NSX][0][0];
+        const u32x4* Ws = &Wst[s % R4_NSW][0][0];
 #pragma unroll
         for (int i = 0; i < R2_MTW; ++i)
 #pragma unroll
-            for (int sp = 0; sp < SPL; ++sp) bq[i][sp].u = St[(R2_NT + min(w + R2_CW * i, ROWS_MT - 1) * SPL + sp) * 64 + lane];
+            for (int sp = 0; sp < SPL; ++sp) bq[i][sp].u = Xs[(min(w + R2_CW * i, ROWS_MT - 1) * SPL + sp) * 64 + lane];
 #pragma unroll
-        for (int t = 0; t < R2_NT; ++t) wf[t].u = St[t * 64 + lane];
+        for (int t = 0; t < R2_NT; ++t) wf[t].u = Ws[t * 64 + lane];
     };
     auto multiply = [&](const Frag (&wf)[R2_NT], const Frag (&bq)[R2_MTW][SPL]) {
 #pragma unroll
