@@ -330,7 +330,7 @@ def main() -> int:
         "step_ms_device_only": spread,
         "step_hbm": {"algorithmic_bytes": ab["total"], "achieved_gbps": round(step_gbps, 1),
                      "frac_of_8TBps": round(step_gbps / HBM_PEAK_GBPS, 4)},
-        "roofline": {"kernel": ("gemm_skinny" if B * (gamma + 1) <= 32 else "gemm_rows2") + " (gate/up projection + SwiGLU epilogue)", "bound": "hbm",
+        "roofline": {"kernel": ("gemm_skinny" if B * (gamma + 1) <= 32 else "gemm_rows4") + " (gate/up projection + SwiGLU epilogue)", "bound": "hbm",
                      "achieved": round(k_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(k_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": k_bytes, "avg_launch_us": round(k_avg_s * 1e6, 2), "launches_timed": int(k_launches)},

@@ -97,10 +97,22 @@ __global__ void kv_gather_kernel(T* __restrict__ kdst, T* __restrict__ vdst, con
     }
 }
 
+// Caller-supplied hidden states [R][d] (storage dtype) -> operand plane 0 in the layout the LM-head kernel
+// reads (opnd_off), and their fp32 copy for the judge.  One thread per 4 consecutive columns.
 template <typename T>
-__global__ void to_f32_kernel(const T* __restrict__ src, float* __restrict__ dst, size_t n) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
-        dst[i] = Traits<T>::load(src + i);
+__global__ __launch_bounds__(256) void hidden_in_kernel(const T* __restrict__ src, T* __restrict__ xn, float* __restrict__ hn32,
+                                                        int R, int d, int tks) {
+    const size_t n4 = (size_t)R * d / 4;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
+        const int row = (int)(i / (d / 4)), k = (int)(i % (d / 4)) * 4;
+        T* out = xn + opnd_off<T>(row, k, d, tks);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const T v = src[(size_t)row * d + k + e];
+            out[e] = v;
+            hn32[(size_t)row * d + k + e] = Traits<T>::load(&v);
+        }
+    }
 }
 
 __global__ void set_params_kernel(StepParams p, StepParams* dst) {

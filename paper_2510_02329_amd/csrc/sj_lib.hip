@@ -717,6 +717,8 @@ struct Runner {
     // consumes them (more than FEW_ROWS rows, at most two planes); row-major otherwise.
     bool tiled() const { return R > FEW_ROWS && SPL <= 2; }
     int tks(int K) const { return tiled() ? K / Traits<T>::KSTEP : 0; }
+    // the same for a single exact plane (hidden states handed in by the caller), whatever SPL is
+    int tks1(int K) const { return R > FEW_ROWS ? K / Traits<T>::KSTEP : 0; }
     int partial_gemm(const void* W, const void* X, int ldx, int K, int N, const GemmPlan (&pl)[2]) {
         if (R > FEW_ROWS) return gemm_rows<T, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, pl[1].split, kv->part, nullptr, 0, nullptr, 0.f, tiled());
         const GemmPlan& p = pl[0];
@@ -811,7 +813,7 @@ struct Runner {
         int rc, nblk;
         if (R > FEW_ROWS) {
             rc = exact_operand
-                ? gemm_rows<T, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp, false)
+                ? gemm_rows<T, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp, true)
                 : gemm_rows<T, EPI_LOGITS, SPL>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp, tiled());
             nblk = md.V / 16;
         } else {
@@ -867,10 +869,8 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
     int rc;
     Runner<T, SPL> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
     if (head_only) {
-        const size_t n = (size_t)run.R * m->md.d;
-        HIPCHK(hipMemcpyAsync(kv->xn, hidden, n * sizeof(T), hipMemcpyDeviceToDevice, st));
-        to_f32_kernel<T><<<1024, 256, 0, st>>>((const T*)hidden, kv->hn32, n);
-        LAUNCHCHK("to_f32");
+        hidden_in_kernel<T><<<1024, 256, 0, st>>>((const T*)hidden, (T*)kv->xn, kv->hn32, run.R, m->md.d, run.tks1(m->md.d));
+        LAUNCHCHK("hidden_in");
     } else if (stream_eligible(m, kv, gamma, SPL)) {
         if ((rc = stream_forward(m, kv, gamma, st))) return rc;       // includes the LM head and its softmax merge
         return run.tail(gamma);
