@@ -151,14 +151,15 @@ __device__ __forceinline__ unsigned ld_coh(const unsigned* p) { return __hip_ato
 __device__ __forceinline__ float ld_coh(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // Element offset of operand element (row, k) inside one plane.  tks == 0: row-major with leading dimension ld.
-// tks > 0 (= K / KSTEP): the plane is stored as the MFMA fragments the many-row GEMM reads,
-// [row tile][k-step][lane 16 g + r][KF elements], so that a fragment is 1 KB of consecutive memory (a row-major
-// fragment touches 16 cache lines and uses half of each).  Four consecutive k from a multiple of 4 stay together.
+// tks > 0 (= K / KSTEP): the plane is stored in blocks of one MFMA fragment, [row tile][k-step][16 rows][KSTEP
+// elements]: the 1 KB that the many-row GEMM moves into LDS with one load instruction is consecutive memory (lane
+// 16 g + r of that load reads the 16 bytes at row r, element g * KF of the block), where a row-major fragment
+// touches 16 cache lines and uses half of each; a producer still writes a row's KSTEP elements contiguously.
 template <typename T>
 __device__ __forceinline__ size_t opnd_off(int row, int k, int ld, int tks) {
-    constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
+    constexpr int KSTEP = Traits<T>::KSTEP;
     if (tks == 0) return (size_t)row * ld + k;
-    return ((((size_t)(row >> 4) * tks + k / KSTEP) * 64) + ((k % KSTEP) / KF) * 16 + (row & 15)) * KF + (k % KF);
+    return (((size_t)(row >> 4) * tks + k / KSTEP) * 16 + (row & 15)) * KSTEP + (k % KSTEP);
 }
 
 // Workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() also waits for every

@@ -284,10 +284,10 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
                 const int it = min(x + 2 * j, NX - 1);                // an odd count: the last wave repeats the last item
                 const int m = it / SPL, p = it % SPL;
                 const T* plane = reinterpret_cast<const T*>(a.X) + (size_t)p * a.xplane;
-                if (a.x_tks) {                                        // fragment-tiled plane: 1 KB per (row tile, k-step)
+                if (a.x_tks) {                                        // plane in fragment blocks: 1 KB per (row tile, k-step)
                     const size_t mt_ok = m * 16 < a.R ? m : 0;        // whole tiles past R re-read tile 0
-                    sp = reinterpret_cast<const char*>(plane + ((mt_ok * a.x_tks + ks0) * 64 + lane) * KF);
-                    st = 1024;
+                    sp = reinterpret_cast<const char*>(plane + ((mt_ok * a.x_tks + ks0) * 16 + r) * KSTEP + g * KF);
+                    st = (size_t)16 * KSTEP * sizeof(T);
                 } else {
                     const int row = m * 16 + r;
                     sp = reinterpret_cast<const char*>(plane + (size_t)(row < a.R ? row : 0) * a.ldx + (size_t)ks0 * KSTEP + g * KF);
