@@ -70,6 +70,23 @@ def test_judge_training_argument_errors():
     assert out["best_index"] == 0 and 0.5 <= out["auc"][0] <= 1.0
 
 
+@pytest.mark.parametrize("n,d,C", [(2000, 8192, 0.01), (1000, 6144, 3.0), (513, 3072, 0.3)])
+def test_judge_training_wide_rows_meet_optimality_conditions(n, d, C):
+    """Feature widths of the larger targets (d 8192 = 70B-shaped: rows in two-row groups) where the oracle's dense
+    Hessian is too slow: the returned point must be stationary for the strictly convex objective."""
+    H, y = synth.make_judge_dataset(21, n, d)
+    Hv, yv = synth.make_judge_dataset(22, 400, d)
+    out = sj.sj_judge_train(_dev(H), _dev(y), _dev(Hv), _dev(yv), [C], torch.cuda.current_stream())
+    w, b = out["w"], out["b"]
+    Hd = H.astype(np.float64)
+    s = 1.0 / (1.0 + np.exp(-(Hd @ w + b)))
+    gmax = max(np.abs(w + C * ((s - y) @ Hd)).max(), abs(C * np.sum(s - y)))
+    print(f"d = {d}: max |grad| = {gmax:.2e} after {out['passes'][0]} passes", flush=True)
+    assert gmax <= 1e-9 * max(1.0, C * n)
+    sv = jt.scores_of(Hv, w, b)
+    assert abs(out["auc"][0] - jt.roc_auc(sv, yv)) <= _auc_slack(sv, yv, 1e-9) + 1e-15
+
+
 def test_judge_training_at_paper_size_meets_optimality_conditions():
     """69,432 pairs of 4096 features (the paper's Llama-3.1-8B training set size), one C: the result must be the
     stationary point of the strictly convex objective - gradient recomputed on the CPU in fp64."""
