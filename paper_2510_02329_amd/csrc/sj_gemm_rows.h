@@ -43,8 +43,8 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 
 // Epilogue of the many-row kernels from the accumulators: lane holds columns nt*16 + 4g .. +3 of row
 // m*16 + r; wave w owns row tiles w, w + 4, w + 8.
-template <typename T, int EPI>
-__device__ __forceinline__ void rows_epilogue(const GemmArgs& a, const f32x4 (&acc)[R2_MTW][R2_NT], int w, int my_tiles, int nt0,
+template <typename T, int EPI, int NT = R2_NT>
+__device__ __forceinline__ void rows_epilogue(const GemmArgs& a, const f32x4 (&acc)[R2_MTW][NT], int w, int my_tiles, int nt0,
                                               int ntiles, int r, int g) {
 #pragma unroll
     for (int i = 0; i < R2_MTW; ++i) {
@@ -52,7 +52,7 @@ __device__ __forceinline__ void rows_epilogue(const GemmArgs& a, const f32x4 (&a
         const int row = (w + R2_CW * i) * 16 + r;
         const bool valid = row < a.R;
 #pragma unroll
-        for (int t = 0; t < R2_NT; ++t) {
+        for (int t = 0; t < NT; ++t) {
             const int nt = nt0 + t;
             if (nt >= ntiles) continue;                    // uniform
             const f32x4 v = acc[i][t];
@@ -220,17 +220,19 @@ constexpr int R4_NSW = 8;          // weight stages (k-steps) in LDS: HBM latenc
 constexpr int R4_NSX = 5;          // operand stages: an L2 hit away
 constexpr int R4_LW = 4;           // loader waves: two for the weights, two for the operand
 
-template <typename T, int EPI, int SPL>
+// NT = n-tiles per workgroup: 8, or 7 where that makes the number of workgroups a multiple of the CU count
+// (gate/up projection of the 8B shape: 1792 n-tiles = 256 x 7).
+template <typename T, int EPI, int SPL, int NT = R2_NT>
 __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmArgs a, int mt) {
     static_assert(SPL <= 2, "three operand planes do not fit");
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
     constexpr int NX = ROWS_MT * SPL;                  // operand fragments per stage
-    __shared__ u32x4 Wst[R4_NSW][R2_NT][64];           // 64 KB
+    __shared__ u32x4 Wst[R4_NSW][NT][64];              // 64 KB
     __shared__ u32x4 Xst[R4_NSX][NX][64];              // 90 KB with two planes
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g = lane >> 4;
     const int KS = a.K / KSTEP, ntiles = a.N / 16;
-    const int nt0 = blockIdx.x * R2_NT;
+    const int nt0 = blockIdx.x * NT;
     const int ks0 = (int)((long long)blockIdx.y * KS / gridDim.y), ks1 = (int)((long long)(blockIdx.y + 1) * KS / gridDim.y);
     const int nks = ks1 - ks0;
     if (nks <= 0) return;                              // uniform for the workgroup
@@ -272,12 +274,13 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
         };
         if (lw < 2) {                                                 // weight tiles lw, lw + 2, ..
             auto make_src = [&](int j, const char*& sp, size_t& st) {
-                const size_t tile = (size_t)min(nt0 + lw + 2 * j, ntiles - 1);      // tiles past N re-read the last
+                // an odd tile count: the second wave repeats the last tile; tiles past N re-read the last
+                const size_t tile = (size_t)min(nt0 + min(lw + 2 * j, NT - 1), ntiles - 1);
                 sp = reinterpret_cast<const char*>(a.Wt) + ((tile * KS + ks0) * 64 + lane) * 16;
                 st = 1024;
             };
-            auto dst_of = [&](int buf, int j) { return &Wst[buf][lw + 2 * j][0]; };
-            run(std::integral_constant<int, R2_NT / 2>{}, std::integral_constant<int, R4_NSW>{}, make_src, dst_of);
+            auto dst_of = [&](int buf, int j) { return &Wst[buf][min(lw + 2 * j, NT - 1)][0]; };
+            run(std::integral_constant<int, (NT + 1) / 2>{}, std::integral_constant<int, R4_NSW>{}, make_src, dst_of);
         } else {                                                      // operand fragments x, x + 2, ..
             const int x = lw - 2;
             auto make_src = [&](int j, const char*& sp, size_t& st) {
@@ -302,15 +305,15 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
 
     // ---------------- compute waves: row tiles w, w + 4, w + 8 ----------------
     const int my_tiles = (mt > w) ? (mt - w + R2_CW - 1) / R2_CW : 0;
-    f32x4 acc[R2_MTW][R2_NT];
+    f32x4 acc[R2_MTW][NT];
 #pragma unroll
     for (int i = 0; i < R2_MTW; ++i)
 #pragma unroll
-        for (int t = 0; t < R2_NT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // two register sets of fragments: the next k-step is read from LDS while the current one is multiplied
-    Frag wfA[R2_NT], bqA[R2_MTW][SPL], wfB[R2_NT], bqB[R2_MTW][SPL];
-    auto fetch = [&](Frag (&wf)[R2_NT], Frag (&bq)[R2_MTW][SPL], int s) {
+    Frag wfA[NT], bqA[R2_MTW][SPL], wfB[NT], bqB[R2_MTW][SPL];
+    auto fetch = [&](Frag (&wf)[NT], Frag (&bq)[R2_MTW][SPL], int s) {
         // a stage past the end holds a copy of the last one
         const u32x4* Xs = &Xst[s % R4_NSX][0][0];
         const u32x4* Ws = &Wst[s % R4_NSW][0][0];
@@ -319,16 +322,16 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
 #pragma unroll
             for (int sp = 0; sp < SPL; ++sp) bq[i][sp].u = Xs[(min(w + R2_CW * i, ROWS_MT - 1) * SPL + sp) * 64 + lane];
 #pragma unroll
-        for (int t = 0; t < R2_NT; ++t) wf[t].u = Ws[t * 64 + lane];
+        for (int t = 0; t < NT; ++t) wf[t].u = Ws[t * 64 + lane];
     };
-    auto multiply = [&](const Frag (&wf)[R2_NT], const Frag (&bq)[R2_MTW][SPL]) {
+    auto multiply = [&](const Frag (&wf)[NT], const Frag (&bq)[R2_MTW][SPL]) {
 #pragma unroll
         for (int i = 0; i < R2_MTW; ++i) {
             if (i < my_tiles) {
 #pragma unroll
                 for (int sp = 0; sp < SPL; ++sp)
 #pragma unroll
-                    for (int t = 0; t < R2_NT; ++t) Traits<T>::mma(wf[t], bq[i][sp], acc[i][t]);
+                    for (int t = 0; t < NT; ++t) Traits<T>::mma(wf[t], bq[i][sp], acc[i][t]);
             }
         }
     };
@@ -344,7 +347,7 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
             lds_barrier();                             // stage s + 3 has landed
         }
     }
-    rows_epilogue<T, EPI>(a, acc, w, my_tiles, nt0, ntiles, r, g);
+    rows_epilogue<T, EPI, NT>(a, acc, w, my_tiles, nt0, ntiles, r, g);
 }
 
 }  // namespace sj

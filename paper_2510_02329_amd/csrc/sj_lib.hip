@@ -692,8 +692,17 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
         else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ntiles; }
         else a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
         const dim3 grid((ntiles + R2_NT - 1) / R2_NT, EPI == EPI_PARTIAL ? split : 1);
-        if constexpr (SPL <= 2) gemm_rows4_kernel<T, EPI, SPL><<<grid, (R2_CW + R4_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
-        else gemm_rows2_kernel<T, EPI, SPL><<<grid, (R2_CW + R2_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
+        if constexpr (SPL <= 2) {
+            // 7 n-tiles per workgroup where that fills whole rounds of the chip and 8 do not (gate/up of the 8B shape:
+            // 256 workgroups instead of 224), from 8 row tiles on (below that the lighter weight stream per CU loses)
+            const int mt = (nr + 15) / 16;
+            if (EPI == EPI_SWIGLU && mt >= 8 && ntiles % 7 == 0 && (ntiles / 7) % 256 == 0 && ((ntiles + 7) / 8) % 256 != 0)
+                gemm_rows4_kernel<T, EPI, SPL, 7><<<dim3(ntiles / 7, 1), (R2_CW + R4_LW) * 64, 0, st>>>(a, mt);
+            else
+                gemm_rows4_kernel<T, EPI, SPL><<<grid, (R2_CW + R4_LW) * 64, 0, st>>>(a, mt);
+        } else {
+            gemm_rows2_kernel<T, EPI, SPL><<<grid, (R2_CW + R2_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
+        }
         LAUNCHCHK("gemm_rows");
     }
     return SJ_OK;
