@@ -308,11 +308,11 @@ static GemmPlan plan_partial(int ntiles, int ksteps, bool one_row_tile) {
     static const int cand[3][2] = {{4, 4}, {3, 8}, {6, 4}};
     GemmPlan best;
     if (!one_row_tile) {
-        // loader-wave kernel: 8 n-tiles per workgroup, one workgroup per CU; K-slices until the chip is
-        // covered, every slice keeping at least 8 k-steps
+        // loader-wave kernel: 8 n-tiles per workgroup, one workgroup per CU; as many K-slices (at most 8, of at
+        // least 8 k-steps each) as fit one round of the chip - a second, partly filled round costs a whole one
         const int groups = (ntiles + 7) / 8;
-        best.nt = 8; best.waves = 8; best.split = 1;
-        while (groups * best.split < 256 && best.split < 8 && ksteps / (best.split * 2) >= 8) best.split *= 2;
+        best.nt = 8; best.waves = 8;
+        best.split = std::max(1, std::min({8, 256 / std::max(groups, 1), ksteps / 8}));
         return best;
     }
     double best_waste = 1e30;
