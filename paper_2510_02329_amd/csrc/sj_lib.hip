@@ -67,12 +67,17 @@ struct sj_model {
     bool coop = false;
 };
 
+// Up to two row tiles (32 rows) the few-row kernel (every wave fetches its own operand fragments) is the faster
+// one (gate/up of the 70B shape at 24 rows: 179 us against 262 us); from three on the loader-wave kernels.
+constexpr int FEW_ROWS = 32;
+
 // Shape of a split-K projection launch: NT n-tiles and `waves` waves per workgroup, `split` K-slices
-// across workgroups (summed by the consumer).  The chip has 256 CUs and these kernels are a single
-// wave of workgroups long, so a launch whose workgroup count is not a multiple of 256 leaves CUs idle
-// for its whole duration: among the tile groupings the kernel is instantiated for, take the one that
-// wastes the fewest workgroup slots, every wave keeping at least 8 k-steps.
-struct GemmPlan { int nt = 4, waves = 4, split = 1; };
+// across workgroups (summed by the consumer), `depth` k-steps in the few-row kernel's load ring.  The chip has
+// 256 CUs and these kernels are a single wave of workgroups long, so a launch whose workgroup count is not a
+// multiple of 256 leaves CUs idle for its whole duration: plan_partial takes, among the first tile groupings
+// the kernel is instantiated for, the one that wastes the fewest workgroup slots, every wave keeping at least
+// 8 k-steps; tune_plans then measures that choice against the other shapes on the model's own weights.
+struct GemmPlan { int nt = 4, waves = 4, split = 1, depth = 2; };
 
 struct sj_kv {
     const sj_model* m = nullptr;
@@ -324,8 +329,12 @@ static GemmPlan plan_partial(int ntiles, int ksteps, bool one_row_tile) {
         const double waste = (double)((wgs + 255) / 256 * 256) / wgs;
         if (waste < best_waste - 1e-9) { best.nt = c[0]; best.waves = c[1]; best.split = split; best_waste = waste; }
     }
+    // short K-slices (at most 8 k-steps per wave): a deeper register ring puts the whole slice in flight
+    best.depth = (best.nt == 4 && best.waves == 4 && ksteps / (best.split * 4) <= 8) ? 4 : 2;
     return best;
 }
+
+static int tune_plans(sj_kv* kv, int rows);
 
 extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* capacity, sj_kv** out) {
     if (!m || !out) return fail(SJ_EINVAL, "model / out is null");
@@ -402,6 +411,8 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
             part_elems = std::max({part_elems, (size_t)kv->plan_qkv[i].split * R * (Nq + 2 * Nk),
                                    (size_t)kv->plan_o[i].split * R * d, (size_t)kv->plan_d[i].split * R * d});
         }
+        // room for any few-row plan the start-up measurement may pick (at most 8 K-slices of at most 32 rows)
+        part_elems = std::max(part_elems, (size_t)8 * std::min(R, FEW_ROWS) * std::max(Nq + 2 * Nk, d));
         kv->mpad = (G * (c.max_gamma + 1) + 63) / 64 * 64;   // whole groups of 4 MFMA tiles
         // key ranges of attention: one wave takes chunk_keys keys (at least one 32-key step, more when the
         // total context would otherwise need more than 1024 waves: every range costs a partial
@@ -441,6 +452,10 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     if (hipMemcpy(kv->seq_off_dev, kv->seq_off.data(), sizeof(int64_t) * batch, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(kv->cap_dev, kv->cap.data(), sizeof(int32_t) * batch, hipMemcpyHostToDevice) != hipSuccess)
         return bail(fail(SJ_EHIP, "hipMemcpy of cache geometry failed"));
+    if (c.n_layers > 0) {
+        const char* e = std::getenv("SJ_TUNE");
+        if (!(e && e[0] == '0') && (rc = tune_plans(kv, std::min(R, FEW_ROWS)))) return bail(rc);
+    }
     *out = kv;
     return SJ_OK;
 }
@@ -646,13 +661,10 @@ extern "C" int sj_kv_state(const sj_kv* kv, int32_t* len_host, int32_t* pending_
 // ------------------------------------------------------------------------------------------------
 // kernel sequence
 
+
 // Few rows (at most 32 = two MFMA row tiles): Y = X W^T with the few-row kernel.  X has SPL planes `xplane`
 // elements apart; act (EPI_SWIGLU) planes are `actplane` apart.  NT n-tiles per workgroup (N/16 must be a
 // multiple of NT), WAVES waves split the K-slice, D = depth of the register ring.
-// up to two row tiles the few-row kernel (every wave fetches its own operand fragments) is the faster
-// one (gate/up of the 70B shape at 24 rows: 179 us against 262 us); from three on the loader-wave kernel
-constexpr int FEW_ROWS = 32;
-
 template <typename T, int NT, int EPI, int SPL, int WAVES, int D = 2>
 static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
                 float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
@@ -667,6 +679,97 @@ static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, in
     else gemm_skinny_kernel<T, NT, 2, EPI, SPL, WAVES, D><<<dim3(ngroups, split), WAVES * 64, 0, st>>>(a);
     LAUNCHCHK("gemm_skinny");
     return SJ_OK;
+}
+
+// The few-row split-K projection in the launch shape of a plan.  Shapes beyond the first four exist for the
+// default two-plane / one-plane operands only (they are what the start-up measurement may pick).
+template <typename T, int SPL>
+static int few_partial(const GemmPlan& p, hipStream_t st, const void* W, const void* X, size_t xplane, int ldx, int K, int N,
+                       int rows, float* out) {
+#define SJ_SHAPE(NT, WV, D)                                                                                         \
+    if (p.nt == NT && p.waves == WV && p.depth == D)                                                                \
+        return gemm<T, NT, EPI_PARTIAL, SPL, WV, D>(st, W, X, xplane, ldx, K, N, rows, p.split, out, nullptr, 0, nullptr, 0.f);
+    SJ_SHAPE(4, 4, 2) SJ_SHAPE(4, 4, 4) SJ_SHAPE(3, 8, 2) SJ_SHAPE(6, 4, 2)
+    if constexpr (SPL <= 2) { SJ_SHAPE(5, 4, 2) SJ_SHAPE(8, 8, 2) SJ_SHAPE(4, 8, 2) SJ_SHAPE(8, 4, 2) SJ_SHAPE(3, 4, 4) }
+#undef SJ_SHAPE
+    return fail(SJ_EINVAL, "internal: no few-row kernel for %d tiles x %d waves, ring %d", p.nt, p.waves, p.depth);
+}
+
+// Launch shapes of the three split-K projections for few rows, chosen by measurement when the cache object is
+// created: which of (n-tiles, waves, K-slices, ring depth) streams a given weight matrix fastest depends on its
+// shape and on the number of row tiles in ways the workgroup-count rule of plan_partial does not capture (70B-shaped
+// QKV with two row tiles: 50 us with the rule's shape, 35 us with the best one).  Every candidate runs over up to 16
+// layers' weights back to back (distinct layers, so nothing is served from cache); the rule's plan stays unless a
+// candidate is at least 3 % faster.  SJ_TUNE=0 keeps the rule's plans (launch shapes then never differ between runs).
+template <typename T, int SPL>
+static int tune_one(sj_kv* kv, GemmPlan& plan, void* LayerW::*which, const void* X, int K, int N, int rows,
+                    hipEvent_t e0, hipEvent_t e1) {
+    const sj_model* m = kv->m;
+    const int ksteps = K / Traits<T>::KSTEP, ntiles = N / 16;
+    const int nl = std::min(m->cfg.n_layers, 16);
+    const size_t xplane = (size_t)kv->rpad * K;
+    auto time_plan = [&](const GemmPlan& p, double& us) -> int {
+        float ms = 0.f;
+        for (int rep = 0; rep < 2; ++rep) {                 // the first repetition warms up
+            HIPCHK(hipEventRecord(e0, nullptr));
+            for (int l = 0; l < nl; ++l) {
+                const int rc = few_partial<T, SPL>(p, nullptr, m->layers[l].*which, X, xplane, K, K, N, rows, kv->part);
+                if (rc) return rc;
+            }
+            HIPCHK(hipEventRecord(e1, nullptr));
+            HIPCHK(hipEventSynchronize(e1));
+            HIPCHK(hipEventElapsedTime(&ms, e0, e1));
+        }
+        us = (double)ms * 1e3 / nl;
+        return SJ_OK;
+    };
+    int rc;
+    double base_us = 0.0;
+    if ((rc = time_plan(plan, base_us))) return rc;
+    static const int shapes[][3] = {{4, 4, 2}, {4, 4, 4}, {3, 8, 2}, {6, 4, 2}, {5, 4, 2}, {8, 8, 2}, {4, 8, 2}, {8, 4, 2}, {3, 4, 4}};
+    GemmPlan best = plan;
+    double best_us = base_us * 0.97;
+    for (int i = 0; i < (int)(sizeof(shapes) / sizeof(shapes[0])); ++i) {
+        if (SPL > 2 && i >= 4) break;
+        const int nt = shapes[i][0], wv = shapes[i][1], dp = shapes[i][2];
+        if (ntiles % nt) continue;
+        for (int split = 1; split <= 8; split *= 2) {
+            const int kpw = ksteps / (wv * split);          // k-steps of a wave
+            const long long wgs = (long long)ntiles / nt * split;
+            if (kpw < 4 || (dp == 4 && kpw > 8) || wgs < 128 || wgs > 4096) continue;
+            GemmPlan p;
+            p.nt = nt; p.waves = wv; p.split = split; p.depth = dp;
+            double us = 0.0;
+            if ((rc = time_plan(p, us))) return rc;
+            if (us < best_us) { best_us = us; best = p; }
+        }
+    }
+    plan = best;
+    return SJ_OK;
+}
+
+static int tune_plans(sj_kv* kv, int rows) {
+    const sj_model* m = kv->m;
+    const sj_config& c = m->cfg;
+    const int d = c.d_model, Nq = c.n_q_heads * c.head_dim, Nk = c.n_kv_heads * c.head_dim, F = c.d_ffn;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIPCHK(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(SJ_EHIP, "hipEventCreate failed"); }
+    int rc = SJ_OK;
+#define SJ_TUNE3(T, SPL)                                                                                          \
+    do {                                                                                                          \
+        if (!rc) rc = tune_one<T, SPL>(kv, kv->plan_qkv[0], &LayerW::wqkv, kv->xn, d, Nq + 2 * Nk, rows, e0, e1);  \
+        if (!rc) rc = tune_one<T, SPL>(kv, kv->plan_o[0], &LayerW::wo, kv->attn_out, Nq, d, rows, e0, e1);         \
+        if (!rc) rc = tune_one<T, SPL>(kv, kv->plan_d[0], &LayerW::wd, kv->act, F, d, rows, e0, e1);               \
+    } while (0)
+    if (c.dtype == SJ_DTYPE_FP32) SJ_TUNE3(float, 1);
+    else if (kv->planes == 1) SJ_TUNE3(bf16_t, 1);
+    else if (kv->planes == 3) SJ_TUNE3(bf16_t, 3);
+    else SJ_TUNE3(bf16_t, 2);
+#undef SJ_TUNE3
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
 }
 
 // More rows: groups of at most 144 rows (9 MFMA row tiles) through the loader-wave kernel; the statistics
@@ -730,15 +833,7 @@ struct Runner {
     int tks1(int K) const { return R > FEW_ROWS ? K / Traits<T>::KSTEP : 0; }
     int partial_gemm(const void* W, const void* X, int ldx, int K, int N, const GemmPlan (&pl)[2]) {
         if (R > FEW_ROWS) return gemm_rows<T, EPI_PARTIAL, SPL>(st, W, X, plane(ldx), ldx, K, N, R, pl[1].split, kv->part, nullptr, 0, nullptr, 0.f, tiled());
-        const GemmPlan& p = pl[0];
-        if (p.nt == 3 && p.waves == 8)
-            return gemm<T, 3, EPI_PARTIAL, SPL, 8>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
-        if (p.nt == 6 && p.waves == 4)
-            return gemm<T, 6, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
-        // short K-slices (at most 8 k-steps per wave): a deeper register ring puts the whole slice in flight
-        if (K / Traits<T>::KSTEP / (p.split * 4) <= 8)
-            return gemm<T, 4, EPI_PARTIAL, SPL, 4, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
-        return gemm<T, 4, EPI_PARTIAL, SPL, 4>(st, W, X, plane(ldx), ldx, K, N, R, p.split, kv->part, nullptr, 0, nullptr, 0.f);
+        return few_partial<T, SPL>(pl[0], st, W, X, plane(ldx), ldx, K, N, R, kv->part);
     }
     int nparts(const GemmPlan (&pl)[2]) const { return pl[R <= FEW_ROWS ? 0 : 1].split; }
     // gate / up projection with the SwiGLU epilogue: 7 n-tiles per workgroup when that gives a whole
