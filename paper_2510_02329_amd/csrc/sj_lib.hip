@@ -101,6 +101,7 @@ struct sj_kv {
     double *epart = nullptr, *wpart = nullptr;
     int chunk_keys = 64, nchunk_max = 1, nslab = 0, slab_len = 0;
     GemmPlan plan_qkv[2], plan_o[2], plan_d[2];   // [0]: few-row kernel (at most 32 rows), [1]: more
+    GemmPlan plan_gu;                             // gate / up projection with few rows (no K-slices)
     int lm_nt = 2;
     int mode = SJ_MODE_TWO_STAGE;
     int planes = 2;            // bf16 planes of the activation operand (fp32 storage: always 1)
@@ -411,6 +412,8 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
             part_elems = std::max({part_elems, (size_t)kv->plan_qkv[i].split * R * (Nq + 2 * Nk),
                                    (size_t)kv->plan_o[i].split * R * d, (size_t)kv->plan_d[i].split * R * d});
         }
+        kv->plan_gu.nt = (2 * F / 16) % 7 == 0 ? 7 : 8;   // whole rounds of workgroups where 7 tiles give them
+        kv->plan_gu.waves = 8; kv->plan_gu.split = 1; kv->plan_gu.depth = 2;
         // room for any few-row plan the start-up measurement may pick (at most 8 K-slices of at most 32 rows)
         part_elems = std::max(part_elems, (size_t)8 * std::min(R, FEW_ROWS) * std::max(Nq + 2 * Nk, d));
         kv->mpad = (G * (c.max_gamma + 1) + 63) / 64 * 64;   // whole groups of 4 MFMA tiles
@@ -695,6 +698,19 @@ static int few_partial(const GemmPlan& p, hipStream_t st, const void* W, const v
     return fail(SJ_EINVAL, "internal: no few-row kernel for %d tiles x %d waves, ring %d", p.nt, p.waves, p.depth);
 }
 
+// The few-row gate / up projection (SwiGLU epilogue, no K-slices) in the launch shape of a plan.
+template <typename T, int SPL>
+static int few_swiglu(const GemmPlan& p, hipStream_t st, const void* W, const void* X, size_t xplane, int K, int N2, int rows,
+                      void* act, size_t actplane) {
+#define SJ_SHAPE(NT, WV)                                                                                            \
+    if (p.nt == NT && p.waves == WV)                                                                                \
+        return gemm<T, NT, EPI_SWIGLU, SPL, WV>(st, W, X, xplane, K, K, N2, rows, 1, nullptr, act, actplane, nullptr, 0.f);
+    SJ_SHAPE(7, 8) SJ_SHAPE(8, 8)
+    if constexpr (SPL <= 2) { SJ_SHAPE(4, 8) SJ_SHAPE(4, 4) SJ_SHAPE(2, 8) }
+#undef SJ_SHAPE
+    return fail(SJ_EINVAL, "internal: no few-row gate/up kernel for %d tiles x %d waves", p.nt, p.waves);
+}
+
 // Launch shapes of the three split-K projections for few rows, chosen by measurement when the cache object is
 // created: which of (n-tiles, waves, K-slices, ring depth) streams a given weight matrix fastest depends on its
 // shape and on the number of row tiles in ways the workgroup-count rule of plan_partial does not capture (70B-shaped
@@ -748,6 +764,47 @@ static int tune_one(sj_kv* kv, GemmPlan& plan, void* LayerW::*which, const void*
     return SJ_OK;
 }
 
+template <typename T, int SPL>
+static int tune_gate_up(sj_kv* kv, int rows, hipEvent_t e0, hipEvent_t e1) {
+    const sj_model* m = kv->m;
+    const int d = m->cfg.d_model, F = m->cfg.d_ffn, ntiles = 2 * F / 16;
+    const int nl = std::min(m->cfg.n_layers, 16);
+    auto time_plan = [&](const GemmPlan& p, double& us) -> int {
+        float ms = 0.f;
+        for (int rep = 0; rep < 2; ++rep) {                 // the first repetition warms up
+            HIPCHK(hipEventRecord(e0, nullptr));
+            for (int l = 0; l < nl; ++l) {
+                const int rc = few_swiglu<T, SPL>(p, nullptr, m->layers[l].wgu, kv->xn, (size_t)kv->rpad * d, d, 2 * F, rows, kv->act,
+                                                  (size_t)kv->rpad * F);
+                if (rc) return rc;
+            }
+            HIPCHK(hipEventRecord(e1, nullptr));
+            HIPCHK(hipEventSynchronize(e1));
+            HIPCHK(hipEventElapsedTime(&ms, e0, e1));
+        }
+        us = (double)ms * 1e3 / nl;
+        return SJ_OK;
+    };
+    int rc;
+    double base_us = 0.0;
+    if ((rc = time_plan(kv->plan_gu, base_us))) return rc;
+    static const int shapes[][2] = {{7, 8}, {8, 8}, {4, 8}, {4, 4}, {2, 8}};
+    GemmPlan best = kv->plan_gu;
+    double best_us = base_us * 0.97;
+    for (int i = 0; i < (int)(sizeof(shapes) / sizeof(shapes[0])); ++i) {
+        if (SPL > 2 && i >= 2) break;
+        const int nt = shapes[i][0], wv = shapes[i][1];
+        if (ntiles % nt || (d / Traits<T>::KSTEP) / wv < 4 || ntiles / nt < 128) continue;
+        GemmPlan p;
+        p.nt = nt; p.waves = wv; p.split = 1; p.depth = 2;
+        double us = 0.0;
+        if ((rc = time_plan(p, us))) return rc;
+        if (us < best_us) { best_us = us; best = p; }
+    }
+    kv->plan_gu = best;
+    return SJ_OK;
+}
+
 static int tune_plans(sj_kv* kv, int rows) {
     const sj_model* m = kv->m;
     const sj_config& c = m->cfg;
@@ -761,6 +818,7 @@ static int tune_plans(sj_kv* kv, int rows) {
         if (!rc) rc = tune_one<T, SPL>(kv, kv->plan_qkv[0], &LayerW::wqkv, kv->xn, d, Nq + 2 * Nk, rows, e0, e1);  \
         if (!rc) rc = tune_one<T, SPL>(kv, kv->plan_o[0], &LayerW::wo, kv->attn_out, Nq, d, rows, e0, e1);         \
         if (!rc) rc = tune_one<T, SPL>(kv, kv->plan_d[0], &LayerW::wd, kv->act, F, d, rows, e0, e1);               \
+        if (!rc) rc = tune_gate_up<T, SPL>(kv, rows, e0, e1);                                                     \
     } while (0)
     if (c.dtype == SJ_DTYPE_FP32) SJ_TUNE3(float, 1);
     else if (kv->planes == 1) SJ_TUNE3(bf16_t, 1);
@@ -841,9 +899,7 @@ struct Runner {
     int gate_up(const void* W) {
         const ModelDims& md = m->md;
         if (R > FEW_ROWS) return gemm_rows<T, EPI_SWIGLU, SPL>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f, tiled());
-        if ((2 * md.F / 16) % 7 == 0)
-            return gemm<T, 7, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
-        return gemm<T, 8, EPI_SWIGLU, SPL, 8>(st, W, kv->xn, plane(md.d), md.d, md.d, 2 * md.F, R, 1, nullptr, kv->act, plane(md.F), nullptr, 0.f);
+        return few_swiglu<T, SPL>(kv->plan_gu, st, W, kv->xn, plane(md.d), md.d, 2 * md.F, R, kv->act, plane(md.F));
     }
 
     // rotary + cache append + attention of one layer from the QKV partials in kv->part
