@@ -102,6 +102,7 @@ struct sj_kv {
     int chunk_keys = 64, nchunk_max = 1, nslab = 0, slab_len = 0;
     GemmPlan plan_qkv[2], plan_o[2], plan_d[2];   // [0]: few-row kernel (at most 32 rows), [1]: more
     GemmPlan plan_gu;                             // gate / up projection with few rows (no K-slices)
+    GemmPlan plan_lm{8, 4, 1, 2};                 // LM head with few rows: nt in {4, 8}, waves in {4, 8}
     int lm_nt = 2;
     int mode = SJ_MODE_TWO_STAGE;
     int planes = 2;            // bf16 planes of the activation operand (fp32 storage: always 1)
@@ -711,6 +712,19 @@ static int few_swiglu(const GemmPlan& p, hipStream_t st, const void* W, const vo
     return fail(SJ_EINVAL, "internal: no few-row gate/up kernel for %d tiles x %d waves", p.nt, p.waves);
 }
 
+// The few-row LM head (logits + per-workgroup softmax statistics: V / 16 / nt entries per row) in the launch shape of a plan.
+template <typename T, int SPL>
+static int few_logits(const GemmPlan& p, hipStream_t st, const void* W, const void* X, size_t xplane, int K, int V, int rows,
+                      float* logits, float4* stats, float inv_temp) {
+#define SJ_SHAPE(NT, WV)                                                                                            \
+    if (p.nt == NT && p.waves == WV)                                                                                \
+        return gemm<T, NT, EPI_LOGITS, SPL, WV>(st, W, X, xplane, K, K, V, rows, 1, logits, nullptr, 0, stats, inv_temp);
+    SJ_SHAPE(8, 4)
+    if constexpr (SPL <= 2) { SJ_SHAPE(8, 8) SJ_SHAPE(4, 8) SJ_SHAPE(4, 4) }
+#undef SJ_SHAPE
+    return fail(SJ_EINVAL, "internal: no few-row LM-head kernel for %d tiles x %d waves", p.nt, p.waves);
+}
+
 // Launch shapes of the three split-K projections for few rows, chosen by measurement when the cache object is
 // created: which of (n-tiles, waves, K-slices, ring depth) streams a given weight matrix fastest depends on its
 // shape and on the number of row tiles in ways the workgroup-count rule of plan_partial does not capture (70B-shaped
@@ -805,6 +819,46 @@ static int tune_gate_up(sj_kv* kv, int rows, hipEvent_t e0, hipEvent_t e1) {
     return SJ_OK;
 }
 
+template <typename T, int SPL>
+static int tune_lm_head(sj_kv* kv, int rows, hipEvent_t e0, hipEvent_t e1) {
+    const sj_model* m = kv->m;
+    const int d = m->cfg.d_model, V = m->cfg.vocab;
+    auto time_plan = [&](const GemmPlan& p, double& us) -> int {
+        float ms = 0.f;
+        for (int rep = 0; rep < 2; ++rep) {                 // the first repetition warms up
+            HIPCHK(hipEventRecord(e0, nullptr));
+            for (int l = 0; l < 3; ++l) {
+                const int rc = few_logits<T, SPL>(p, nullptr, m->lm_head, kv->xn, (size_t)kv->rpad * d, d, V, rows, kv->logits, kv->stats,
+                                                  m->md.inv_temp);
+                if (rc) return rc;
+            }
+            HIPCHK(hipEventRecord(e1, nullptr));
+            HIPCHK(hipEventSynchronize(e1));
+            HIPCHK(hipEventElapsedTime(&ms, e0, e1));
+        }
+        us = (double)ms * 1e3 / 3;
+        return SJ_OK;
+    };
+    int rc;
+    double base_us = 0.0;
+    if ((rc = time_plan(kv->plan_lm, base_us))) return rc;
+    static const int shapes[][2] = {{8, 4}, {8, 8}, {4, 8}, {4, 4}};
+    GemmPlan best = kv->plan_lm;
+    double best_us = base_us * 0.97;
+    for (int i = 1; i < (int)(sizeof(shapes) / sizeof(shapes[0])); ++i) {
+        if (SPL > 2) break;
+        const int nt = shapes[i][0], wv = shapes[i][1];
+        if ((V / 16) % nt || (d / Traits<T>::KSTEP) / wv < 4) continue;
+        GemmPlan p;
+        p.nt = nt; p.waves = wv; p.split = 1; p.depth = 2;
+        double us = 0.0;
+        if ((rc = time_plan(p, us))) return rc;
+        if (us < best_us) { best_us = us; best = p; }
+    }
+    kv->plan_lm = best;
+    return SJ_OK;
+}
+
 static int tune_plans(sj_kv* kv, int rows) {
     const sj_model* m = kv->m;
     const sj_config& c = m->cfg;
@@ -819,6 +873,7 @@ static int tune_plans(sj_kv* kv, int rows) {
         if (!rc) rc = tune_one<T, SPL>(kv, kv->plan_o[0], &LayerW::wo, kv->attn_out, Nq, d, rows, e0, e1);         \
         if (!rc) rc = tune_one<T, SPL>(kv, kv->plan_d[0], &LayerW::wd, kv->act, F, d, rows, e0, e1);               \
         if (!rc) rc = tune_gate_up<T, SPL>(kv, rows, e0, e1);                                                     \
+        if (!rc) rc = tune_lm_head<T, SPL>(kv, rows, e0, e1);                                                     \
     } while (0)
     if (c.dtype == SJ_DTYPE_FP32) SJ_TUNE3(float, 1);
     else if (kv->planes == 1) SJ_TUNE3(bf16_t, 1);
@@ -978,9 +1033,9 @@ struct Runner {
             nblk = md.V / 16;
         } else {
             rc = exact_operand
-                ? gemm<T, 8, EPI_LOGITS, 1, 4>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp)
-                : gemm<T, 8, EPI_LOGITS, SPL, 4>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp);
-            nblk = md.V / 16 / 8;
+                ? few_logits<T, 1>(kv->plan_lm, st, m->lm_head, kv->xn, plane(md.d), md.d, md.V, R, kv->logits, kv->stats, md.inv_temp)
+                : few_logits<T, SPL>(kv->plan_lm, st, m->lm_head, kv->xn, plane(md.d), md.d, md.V, R, kv->logits, kv->stats, md.inv_temp);
+            nblk = md.V / 16 / kv->plan_lm.nt;
         }
         if (rc) return rc;
         softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, md.inv_temp, kv->rowstat);
