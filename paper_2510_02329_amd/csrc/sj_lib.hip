@@ -694,7 +694,10 @@ static int few_partial(const GemmPlan& p, hipStream_t st, const void* W, const v
     if (p.nt == NT && p.waves == WV && p.depth == D)                                                                \
         return gemm<T, NT, EPI_PARTIAL, SPL, WV, D>(st, W, X, xplane, ldx, K, N, rows, p.split, out, nullptr, 0, nullptr, 0.f);
     SJ_SHAPE(4, 4, 2) SJ_SHAPE(4, 4, 4) SJ_SHAPE(3, 8, 2) SJ_SHAPE(6, 4, 2)
-    if constexpr (SPL <= 2) { SJ_SHAPE(5, 4, 2) SJ_SHAPE(8, 8, 2) SJ_SHAPE(4, 8, 2) SJ_SHAPE(8, 4, 2) SJ_SHAPE(3, 4, 4) }
+    if constexpr (SPL <= 2) {
+        SJ_SHAPE(5, 4, 2) SJ_SHAPE(8, 8, 2) SJ_SHAPE(4, 8, 2) SJ_SHAPE(8, 4, 2) SJ_SHAPE(3, 4, 4)
+        SJ_SHAPE(2, 4, 4) SJ_SHAPE(2, 4, 2) SJ_SHAPE(2, 8, 2)
+    }
 #undef SJ_SHAPE
     return fail(SJ_EINVAL, "internal: no few-row kernel for %d tiles x %d waves, ring %d", p.nt, p.waves, p.depth);
 }
@@ -707,7 +710,7 @@ static int few_swiglu(const GemmPlan& p, hipStream_t st, const void* W, const vo
     if (p.nt == NT && p.waves == WV)                                                                                \
         return gemm<T, NT, EPI_SWIGLU, SPL, WV>(st, W, X, xplane, K, K, N2, rows, 1, nullptr, act, actplane, nullptr, 0.f);
     SJ_SHAPE(7, 8) SJ_SHAPE(8, 8)
-    if constexpr (SPL <= 2) { SJ_SHAPE(4, 8) SJ_SHAPE(4, 4) SJ_SHAPE(2, 8) }
+    if constexpr (SPL <= 2) { SJ_SHAPE(4, 8) SJ_SHAPE(4, 4) SJ_SHAPE(2, 8) SJ_SHAPE(2, 4) SJ_SHAPE(1, 8) }
 #undef SJ_SHAPE
     return fail(SJ_EINVAL, "internal: no few-row gate/up kernel for %d tiles x %d waves", p.nt, p.waves);
 }
@@ -756,7 +759,8 @@ static int tune_one(sj_kv* kv, GemmPlan& plan, void* LayerW::*which, const void*
     int rc;
     double base_us = 0.0;
     if ((rc = time_plan(plan, base_us))) return rc;
-    static const int shapes[][3] = {{4, 4, 2}, {4, 4, 4}, {3, 8, 2}, {6, 4, 2}, {5, 4, 2}, {8, 8, 2}, {4, 8, 2}, {8, 4, 2}, {3, 4, 4}};
+    static const int shapes[][3] = {{4, 4, 2}, {4, 4, 4}, {3, 8, 2}, {6, 4, 2}, {5, 4, 2}, {8, 8, 2}, {4, 8, 2}, {8, 4, 2}, {3, 4, 4},
+                                    {2, 4, 4}, {2, 4, 2}, {2, 8, 2}};
     GemmPlan best = plan;
     double best_us = base_us * 0.97;
     for (int i = 0; i < (int)(sizeof(shapes) / sizeof(shapes[0])); ++i) {
@@ -802,7 +806,7 @@ static int tune_gate_up(sj_kv* kv, int rows, hipEvent_t e0, hipEvent_t e1) {
     int rc;
     double base_us = 0.0;
     if ((rc = time_plan(kv->plan_gu, base_us))) return rc;
-    static const int shapes[][2] = {{7, 8}, {8, 8}, {4, 8}, {4, 4}, {2, 8}};
+    static const int shapes[][2] = {{7, 8}, {8, 8}, {4, 8}, {4, 4}, {2, 8}, {2, 4}, {1, 8}};
     GemmPlan best = kv->plan_gu;
     double best_us = base_us * 0.97;
     for (int i = 0; i < (int)(sizeof(shapes) / sizeof(shapes[0])); ++i) {
@@ -882,6 +886,16 @@ static int tune_plans(sj_kv* kv, int rows) {
 #undef SJ_TUNE3
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
+    if (const char* e = std::getenv("SJ_TUNE_LOG")) {
+        if (e[0] == '1') {
+            auto show = [](const char* name, const GemmPlan& p) {
+                fprintf(stderr, "[sj] %-8s %d n-tiles x %d waves, %d K-slice(s), ring %d\n", name, p.nt, p.waves, p.split, p.depth);
+            };
+            fprintf(stderr, "[sj] launch shapes for %d rows, d_model %d:\n", rows, d);
+            show("QKV", kv->plan_qkv[0]); show("O", kv->plan_o[0]); show("gate/up", kv->plan_gu); show("down", kv->plan_d[0]);
+            show("LM head", kv->plan_lm);
+        }
+    }
     return rc;
 }
 
