@@ -91,7 +91,12 @@ int sj_model_free(sj_model* m);
 /* Creates the per-batch state: a KV cache with `capacity[b]` positions for sequence b (rounded
  * up to a multiple of 64 internally), lengths 0, pending tokens 0, and the step workspace for
  * batch * (max_gamma + 1) query rows.  capacity is a host array of `batch` entries (ignored
- * and may be NULL for a head-only model).  Synchronous. */
+ * and may be NULL for a head-only model).  Synchronous.  For a model with layers the call also
+ * measures, on the device's default stream and on the model's own weights, which launch shape of
+ * each projection kernel is fastest for this row count (some tens of milliseconds; the workspace
+ * is used as scratch); the environment variable SJ_TUNE=0 keeps the built-in rule instead, which
+ * makes the launch shapes - and with them the summation order of the split-K projections - the
+ * same in every run. */
 int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* capacity, sj_kv** out);
 int sj_kv_free(sj_kv* kv);
 
