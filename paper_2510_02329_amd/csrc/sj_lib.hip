@@ -4,8 +4,7 @@
 #include "sj_kernels.h"
 #include "sj_attn.h"
 #include "sj_gemm_rows.h"
-#include "sj_mega.h"
-#include "sj_stream.h"
+#include "sj_persist_api.h"
 
 #include <algorithm>
 #include <cmath>
@@ -62,9 +61,8 @@ struct sj_model {
     std::vector<void*> allocs;
     int64_t weight_bytes = 0;
     int device = 0;
-    MegaLayer* mega_layers = nullptr;     // device table for the persistent forward kernel (bf16 only)
-    int num_cus = 0;
-    bool coop = false;
+    PersistLayer* persist_layers = nullptr;   // device table for the persistent forward kernel (bf16 only)
+    bool persist_ok = false;                  // shape served by the persistent kernel, 256 CUs, cooperative launch
 };
 
 // Up to two row tiles (32 rows) the few-row kernel (every wave fetches its own operand fragments) is the faster
@@ -114,15 +112,14 @@ struct sj_kv {
     std::map<int, hipGraphExec_t> graphs;
     hipStream_t cap_stream = nullptr;
     bool use_graph = true;
-    // persistent forward kernel (small row counts)
-    bool use_mega = false;     // slower than the launch-graph paths so far: opt-in with SJ_MEGA=1
-    bool use_stream = false;   // stage-per-kernel variant of the persistent kernel: slower than the default path, opt-in with SJ_STREAM=1
-    bf16_t *Bx = nullptr, *Battn = nullptr, *Bact = nullptr;
-    float *ssq = nullptr, *row_scale = nullptr;
-    MegaBar* bar = nullptr;
-    unsigned mega_epoch = 0;
-    size_t mega_lds = 0;
-    unsigned long long* prof = nullptr;   // stage timestamps of the persistent kernel (timing class 9)
+    // persistent forward kernel (at most 8 query rows): SJ_PERSIST=1 selects it, SJ_PERSIST=0 the multi-kernel path
+    bool use_persist = false;
+    bf16_t *Bx = nullptr, *Battn = nullptr, *Bact = nullptr, *knew = nullptr, *vnewT = nullptr;
+    float *ssq = nullptr, *apart = nullptr, *pqkv = nullptr;
+    PersistBar* bar = nullptr;
+    unsigned persist_epoch = 0;
+    int p_chunk_keys = 32, p_nch_max = 1;
+    unsigned long long* prof = nullptr;   // phase timestamps of the persistent kernel (SJ_PERSIST_PROF=1)
     int timing_class = 0;
     std::vector<hipEvent_t> tev;          // start/stop pairs
     size_t tev_used = 0;
@@ -278,21 +275,19 @@ extern "C" int sj_model_load(const sj_config* cfg, sj_tensor_fn provider, void* 
     if ((rc = ld.tiled(&lm_id, &lm_n, 1, -1, d, 0, &m->lm_head))) return cleanup(rc);
     if ((rc = ld.plain(SJ_T_JUDGE_W, -1, d, &m->judge_w))) return cleanup(rc);
     if ((rc = ld.plain(SJ_T_JUDGE_B, -1, 1, &m->judge_b))) return cleanup(rc);
-    if (cfg->dtype == SJ_DTYPE_BF16 && cfg->n_layers > 0) {
-        std::vector<MegaLayer> tab(cfg->n_layers);
+    if (cfg->dtype == SJ_DTYPE_BF16 && cfg->n_layers > 0 && persist_plan(md, cfg->n_layers, nullptr)) {
+        std::vector<PersistLayer> tab(cfg->n_layers);
         for (int l = 0; l < cfg->n_layers; ++l) {
             const LayerW& L = m->layers[l];
-            tab[l] = MegaLayer{(const u32x4*)L.wqkv, (const u32x4*)L.wo, (const u32x4*)L.wgu, (const u32x4*)L.wd,
-                               (const bf16_t*)L.attn_norm, (const bf16_t*)L.ffn_norm};
+            tab[l] = PersistLayer{(const u32x4*)L.wqkv, (const u32x4*)L.wo, (const u32x4*)L.wgu, (const u32x4*)L.wd,
+                                  (const bf16_t*)L.attn_norm, (const bf16_t*)L.ffn_norm};
         }
-        if ((rc = dev_alloc(m->allocs, &m->mega_layers, sizeof(MegaLayer) * tab.size(), false))) return cleanup(rc);
-        if (hipMemcpy(m->mega_layers, tab.data(), sizeof(MegaLayer) * tab.size(), hipMemcpyHostToDevice) != hipSuccess)
+        if ((rc = dev_alloc(m->allocs, &m->persist_layers, sizeof(PersistLayer) * tab.size(), false))) return cleanup(rc);
+        if (hipMemcpy(m->persist_layers, tab.data(), sizeof(PersistLayer) * tab.size(), hipMemcpyHostToDevice) != hipSuccess)
             return cleanup(fail(SJ_EHIP, "hipMemcpy of the layer table failed"));
         hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, m->device) == hipSuccess) {
-            m->num_cus = prop.multiProcessorCount;
-            m->coop = prop.cooperativeLaunch != 0;
-        }
+        if (hipGetDeviceProperties(&prop, m->device) == hipSuccess)
+            m->persist_ok = prop.multiProcessorCount == PERSIST_WGS && prop.cooperativeLaunch != 0;
     }
     cleanup(0);
     *out = m;
@@ -348,8 +343,7 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     kv->m = m;
     kv->batch = batch;
     if (const char* e = std::getenv("SJ_NO_GRAPH")) kv->use_graph = !(e[0] == '1');
-    if (const char* e = std::getenv("SJ_MEGA")) kv->use_mega = (e[0] == '1');
-    if (const char* e = std::getenv("SJ_STREAM")) kv->use_stream = (e[0] == '1');
+    if (const char* e = std::getenv("SJ_PERSIST")) kv->use_persist = !(e[0] == '0');
     kv->cap.assign(batch, 64);
     kv->len_upper.assign(batch, 0);
     kv->seq_off.assign(batch, 0);
@@ -441,15 +435,28 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         ALLOC(kv->act, (size_t)3 * kv->rpad * F * m->esz);
         ALLOC(kv->cs, (size_t)R * hd * 4);
         ALLOC(kv->prefill_tok, (size_t)R * 4);
-        if (c.dtype == SJ_DTYPE_BF16) {
-            ALLOC(kv->Bx, (size_t)d * 32);                 // packed operands: K/32 tiles of 1 KB
-            ALLOC(kv->Battn, (size_t)Nq * 32);
-            ALLOC(kv->Bact, (size_t)F * 32);
-            ALLOC(kv->ssq, (size_t)MEGA_MAXR * (d / 16) * 4);
-            ALLOC(kv->row_scale, (size_t)std::max(R, MEGA_MAXR) * 4);
-            ALLOC(kv->bar, sizeof(MegaBar));
-            ALLOC(kv->prof, sizeof(unsigned long long) * 4096);
-            kv->mega_lds = sizeof(MegaShared) + 1024;      // + slack for the 1 KB alignment of the staging area
+        if (m->persist_ok && batch <= PERSIST_MAXR) {
+            // write-once slots of the persistent kernel (one per layer and producer): packed operands are K/32
+            // fragments of 1 KB
+            const size_t NLs = (size_t)c.n_layers;
+            ALLOC(kv->Bx, (2 * NLs + 1) * d * 32);
+            ALLOC(kv->Battn, NLs * Nq * 32);
+            ALLOC(kv->Bact, NLs * F * 32);
+            ALLOC(kv->ssq, (2 * NLs + 1) * PERSIST_MAXR * (d / 16) * 4);
+            ALLOC(kv->pqkv, NLs * 2 * PERSIST_MAXR * (Nq + 2 * Nk) * 4);
+            ALLOC(kv->knew, NLs * batch * c.n_kv_heads * PERSIST_MAXR * hd * 2);
+            ALLOC(kv->vnewT, NLs * batch * c.n_kv_heads * PERSIST_MAXR * hd * 2);
+            ALLOC(kv->bar, sizeof(PersistBar));
+            // attention chunks of the persistent kernel: 32 keys each, more while the 8 waves of the workgroups that
+            // serve one (sequence, kv head, query tile) would not cover the longest context in one pass
+            const int qt = (G * std::min(PERSIST_MAXR, c.max_gamma + 1) + 15) / 16;
+            const int cpg = std::max(1, PERSIST_WGS / (batch * c.n_kv_heads * qt));
+            int ck = 32;
+            while (ck < (1 << 22) && (cap_max + ck - 1) / ck > 8 * cpg) ck *= 2;
+            kv->p_chunk_keys = ck;
+            kv->p_nch_max = (cap_max + ck - 1) / ck + 1;
+            ALLOC(kv->apart, (size_t)batch * c.n_kv_heads * qt * kv->p_nch_max * PERSIST_APART * 4);
+            if (const char* e = std::getenv("SJ_PERSIST_PROF")) { if (e[0] == '1') { ALLOC(kv->prof, sizeof(unsigned long long) * 8192); } }
         }
     }
 #undef ALLOC
@@ -514,7 +521,7 @@ extern "C" int sj_kv_rewind(sj_kv* kv, const int32_t* len_host, const int32_t* p
 
 extern "C" int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class) {
     if (!kv) return fail(SJ_EINVAL, "kv is null");
-    if ((kernel_class < 0 || kernel_class > 4) && kernel_class != 9) return fail(SJ_EINVAL, "kernel_class must be 0..4 or 9");
+    if (kernel_class < 0 || kernel_class > 4) return fail(SJ_EINVAL, "kernel_class must be 0..4");
     kv->timing_class = kernel_class;
     kv->tev_used = 0;
     return SJ_OK;
@@ -1101,9 +1108,6 @@ static int set_params(sj_kv* kv, hipStream_t st, const StepParams& p) {
     return SJ_OK;
 }
 
-static bool stream_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl);
-static int stream_forward(const sj_model* m, sj_kv* kv, int gamma, hipStream_t st);
-
 template <typename T, int SPL>
 static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool head_only, const void* hidden) {
     int rc;
@@ -1111,9 +1115,6 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
     if (head_only) {
         hidden_in_kernel<T><<<1024, 256, 0, st>>>((const T*)hidden, (T*)kv->xn, kv->hn32, run.R, m->md.d, run.tks1(m->md.d));
         LAUNCHCHK("hidden_in");
-    } else if (stream_eligible(m, kv, gamma, SPL)) {
-        if ((rc = stream_forward(m, kv, gamma, st))) return rc;       // includes the LM head and its softmax merge
-        return run.tail(gamma);
     } else {
         if ((rc = run.layers())) return rc;
     }
@@ -1124,36 +1125,16 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
 // The full step is ~200 dependent launches of a few microseconds each: it is captured once per
 // (gamma, planes) into a launch graph and replayed; only the per-call parameter block, written by a
 // tiny kernel in front of the replay, changes between calls.
-// The persistent forward kernel serves bf16 models when the whole batch fits 8 query rows.
-// shapes the stream kernels (and the persistent kernel built from the same parts) serve
-static bool stream_shape_ok(const sj_model* m, const sj_kv* kv, int gamma, int spl);
-
-static bool mega_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl) {
-    if (!kv->use_mega || !m->coop) return false;
-    if (kv->timing_class != 0 && kv->timing_class != 9) return false;
-    if (m->cfg.n_layers * 10 + 8 > 4096) return false;
-    return stream_shape_ok(m, kv, gamma, spl);
+// The persistent forward kernel serves bf16 models of the shapes it is instantiated for when the whole batch fits
+// 8 query rows and the default two operand planes are in use.
+static bool persist_eligible(const sj_model* m, const sj_kv* kv, int rows, int spl) {
+    return kv->use_persist && m->persist_ok && kv->bar && spl == 2 && rows <= PERSIST_MAXR && kv->timing_class == 0;
 }
 
-static bool stream_eligible(const sj_model* m, const sj_kv* kv, int gamma, int spl) {
-    return kv->use_stream && kv->timing_class == 0 && stream_shape_ok(m, kv, gamma, spl);
-}
-
-static bool stream_shape_ok(const sj_model* m, const sj_kv* kv, int gamma, int spl) {
-    const sj_config& c = m->cfg;
-    if (m->num_cus < 1 || c.dtype != SJ_DTYPE_BF16 || spl != 2 || c.n_layers < 1) return false;
-    const int R = kv->batch * (gamma + 1);
-    if (R > MEGA_MAXR || c.head_dim != 128) return false;
-    const int Nq = c.n_q_heads * c.head_dim;
-    auto ok = [](int K, int D) { return K % (32 * MEGA_SW) == 0 && (K / 32 / MEGA_SW) % D == 0; };
-    // K of the LDS-staged operands is bounded by the staging area (1 KB per k-step)
-    return ok(c.d_model, MEGA_D) && ok(Nq, MEGA_D) && ok(c.d_ffn, 8) && c.d_model / 32 * 1024 <= MEGA_BIG &&
-           Nq / 32 * 1024 <= MEGA_BIG && m->num_cus <= 1024;
-}
-
-static MegaArgs mega_args(const sj_model* m, const sj_kv* kv) {
-    MegaArgs a{};
-    a.layers = m->mega_layers;
+static int launch_persist(const sj_model* m, sj_kv* kv, hipStream_t st) {
+    PersistArgs a{};
+    if (!persist_plan(m->md, m->cfg.n_layers, &a)) return fail(SJ_EINVAL, "internal: persistent kernel does not serve this shape");
+    a.layers = m->persist_layers;
     a.lm_head = (const u32x4*)m->lm_head;
     a.final_gain = (const bf16_t*)m->final_norm;
     a.embed = (const bf16_t*)m->embed;
@@ -1162,89 +1143,24 @@ static MegaArgs mega_args(const sj_model* m, const sj_kv* kv) {
     a.sp = kv->sp_dev;
     a.kv.K = (bf16_t*)kv->K; a.kv.V = (bf16_t*)kv->V; a.kv.seq_off = kv->seq_off_dev; a.kv.cap = kv->cap_dev;
     a.kv.len = kv->len_dev; a.kv.pending = kv->pending_dev; a.kv.layer_stride = kv->layer_stride;
-    a.x = kv->x; a.qkv = kv->part; a.Bx = kv->Bx; a.Battn = kv->Battn; a.Bact = kv->Bact; a.ssq = kv->ssq;
-    a.hn32 = kv->hn32; a.row_scale = kv->row_scale; a.logits = kv->logits; a.stats = kv->stats; a.cs = kv->cs;
+    a.x = kv->x; a.qkv = kv->pqkv; a.knew = kv->knew; a.vnewT = kv->vnewT; a.Bx = kv->Bx; a.Battn = kv->Battn; a.Bact = kv->Bact; a.ssq = kv->ssq;
+    a.hn32 = kv->hn32; a.logits = kv->logits; a.stats = kv->stats; a.cs = kv->cs; a.apart = kv->apart;
+    a.chunk_keys = kv->p_chunk_keys; a.nch_max = kv->p_nch_max;
     a.bar = kv->bar;
-    a.prof = nullptr;
     a.log_base = std::log((double)m->cfg.rope_base);
-    return a;
-}
-
-// The stages of the forward as separate stream kernels (sj_stream.h), for a launch graph to chain.
-template <int EPI, int D, bool BLDS>
-static int launch_stream_gemm(const sj_model* m, const sj_kv* kv, hipStream_t st, const MegaArgs& a, const StreamStage& sg) {
-    static bool attr_set = false;
-    auto fn = stream_gemm_kernel<EPI, D, BLDS>;
-    if (!attr_set) {
-        HIPCHK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv->mega_lds));
-        attr_set = true;
-    }
-    fn<<<m->num_cus, MEGA_THREADS, kv->mega_lds, st>>>(a, sg);
-    LAUNCHCHK("stream_gemm");
-    return SJ_OK;
-}
-
-static int stream_forward(const sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
-    const sj_config& c = m->cfg;
-    const MegaArgs a = mega_args(m, kv);
-    const int d = c.d_model, Nq = c.n_q_heads * c.head_dim, Nk = c.n_kv_heads * c.head_dim, Nqkv = Nq + 2 * Nk;
-    const int ntx = d / 16, R = kv->batch * (gamma + 1);
-    int rc;
-    stream_embed_kernel<<<std::max(ntx, R), 64, 0, st>>>(a);
-    LAUNCHCHK("stream_embed");
-    static bool attn_attr = false;
-    if (!attn_attr) {
-        HIPCHK(hipFuncSetAttribute((const void*)stream_attn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(AttnShared) + 1024));
-        attn_attr = true;
-    }
-    std::vector<MegaLayer> dummy;
-    for (int l = 0; l < c.n_layers; ++l) {
-        const LayerW& L = m->layers[l];
-        StreamStage sg{};
-        sg.W = (const u32x4*)L.wqkv; sg.ntiles = Nqkv / 16; sg.KS = d / 32; sg.B = kv->Bx;
-        if ((rc = launch_stream_gemm<SEPI_QKV, MEGA_D, true>(m, kv, st, a, sg))) return rc;
-        stream_attn_kernel<<<kv->batch * c.n_q_heads, MEGA_SW * 64, sizeof(AttnShared) + 1024, st>>>(a, (size_t)l * kv->layer_stride);
-        LAUNCHCHK("stream_attn");
-        sg = StreamStage{};
-        sg.W = (const u32x4*)L.wo; sg.ntiles = ntx; sg.KS = Nq / 32; sg.B = kv->Battn; sg.gain_next = (const bf16_t*)L.ffn_norm;
-        if ((rc = launch_stream_gemm<SEPI_RESID, MEGA_D, true>(m, kv, st, a, sg))) return rc;
-        sg = StreamStage{};
-        sg.W = (const u32x4*)L.wgu; sg.ntiles = 2 * c.d_ffn / 16; sg.KS = d / 32; sg.B = kv->Bx;
-        if ((rc = launch_stream_gemm<SEPI_SWIGLU, MEGA_D, true>(m, kv, st, a, sg))) return rc;
-        const bool last = (l + 1 == c.n_layers);
-        sg = StreamStage{};
-        sg.W = (const u32x4*)L.wd; sg.ntiles = ntx; sg.KS = c.d_ffn / 32; sg.B = kv->Bact;
-        sg.gain_next = (const bf16_t*)(last ? m->final_norm : m->layers[l + 1].attn_norm);
-        sg.last = last ? 1 : 0;
-        if ((rc = launch_stream_gemm<SEPI_RESID, MEGA_DD, false>(m, kv, st, a, sg))) return rc;
-    }
-    StreamStage sg{};
-    sg.W = (const u32x4*)m->lm_head; sg.ntiles = c.vocab / 16; sg.KS = d / 32; sg.B = kv->Bx;
-    if ((rc = launch_stream_gemm<SEPI_LOGITS, MEGA_D, true>(m, kv, st, a, sg))) return rc;
-    softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, c.vocab / 16, m->md.inv_temp, kv->rowstat);
-    LAUNCHCHK("softmax_merge");
-    return SJ_OK;
-}
-
-static int launch_mega(sj_model* m, sj_kv* kv, int gamma, hipStream_t st) {
-    MegaArgs a = mega_args(m, kv);
-    a.prof = (kv->timing_class == 9) ? kv->prof : nullptr;
-    const unsigned nbar = 1u + 5u * (unsigned)m->cfg.n_layers;
-    if (kv->mega_epoch > 0xF0000000u) {                       // epochs are monotonic: restart well before wrap-around
+    a.prof = kv->prof;
+    if (kv->persist_epoch > 0xF0000000u) {                    // epochs are monotonic: restart well before wrap-around
         HIPCHK(hipStreamSynchronize(st));
-        HIPCHK(hipMemset(kv->bar, 0, sizeof(MegaBar)));
-        kv->mega_epoch = 0;
+        HIPCHK(hipMemset(kv->bar, 0, sizeof(PersistBar)));
+        kv->persist_epoch = 0;
     }
-    a.epoch0 = kv->mega_epoch;
-    static bool attr_set = false;
-    if (!attr_set) {
-        HIPCHK(hipFuncSetAttribute((const void*)mega_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv->mega_lds));
-        attr_set = true;
+    a.epoch0 = kv->persist_epoch;
+    if (kv->persist_epoch == 0) {
+        const char* e = std::getenv("SJ_TUNE_LOG");
+        if (e && e[0] == '1') fprintf(stderr, "[sj] forward served by the persistent kernel (%d key(s) per attention task)\n", kv->p_chunk_keys);
     }
-    void* args[] = {&a};
-    HIPCHK(hipLaunchCooperativeKernel((const void*)mega_forward_kernel, dim3(m->num_cus), dim3(MEGA_THREADS), args,
-                                      kv->mega_lds, st));
-    kv->mega_epoch += nbar;
+    HIPCHK(persist_launch(a, st));
+    kv->persist_epoch += persist_barriers(m->cfg.n_layers);
     return SJ_OK;
 }
 
@@ -1252,9 +1168,9 @@ template <typename T, int SPL>
 static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,
                             const void* hidden) {
     int rc;
-    if (!head_only && mega_eligible(m, kv, gamma, SPL)) {
+    if (!head_only && persist_eligible(m, kv, kv->batch * (gamma + 1), SPL)) {
         if ((rc = set_params(kv, st, p))) return rc;
-        if ((rc = launch_mega(m, kv, gamma, st))) return rc;
+        if ((rc = launch_persist(m, kv, st))) return rc;
         Runner<T, SPL> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
         softmax_merge_kernel<<<run.R, 256, 0, st>>>(kv->stats, m->md.V / 16, m->md.inv_temp, kv->rowstat);
         LAUNCHCHK("softmax_merge");
@@ -1553,27 +1469,14 @@ extern "C" int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, siz
         case SJ_DBG_P_AT_DRAFT: src = kv->p_at_d; want = (size_t)kv->batch * gamma * 4; break;
         case SJ_DBG_ACCEPT_BITS: src = kv->bits; want = (size_t)kv->batch * gamma * 4; break;
         case SJ_DBG_STAGE_TIMES: {
-            if (!kv->prof || kv->timing_class != 9) return fail(SJ_EINVAL, "stage times need timing class 9 and a step of the persistent kernel");
-            if (nbytes == 8 * sizeof(float)) {           // inner stamps of the attention stage (workgroup 0, last layer)
-                unsigned long long t8[8];
-                HIPCHK(hipDeviceSynchronize());
-                HIPCHK(hipMemcpy(t8, kv->prof + 3000, sizeof t8, hipMemcpyDeviceToHost));
-                float* o8 = (float*)dst_host;
-                o8[0] = 0.f;
-                for (int i = 1; i < 8; ++i) o8[i] = (float)((double)(t8[i] - t8[0]) * 0.01);
-                return SJ_OK;
-            }
-            if (nbytes != 11 * sizeof(float)) return fail(SJ_EINVAL, "nbytes must be 44");
-            const int NL = kv->m->cfg.n_layers, n = 4 + 10 * NL;
+            // diagnostic: microseconds since the first stamp of the persistent kernel's phase stamps (workgroup 0)
+            if (!kv->prof) return fail(SJ_EINVAL, "stage times need SJ_PERSIST_PROF=1 when the cache object is created");
+            const size_t n = nbytes / sizeof(float);
+            if (n < 1 || n > 8192) return fail(SJ_EINVAL, "nbytes must cover 1..8192 floats");
             std::vector<unsigned long long> t(n);
             HIPCHK(hipDeviceSynchronize());
             HIPCHK(hipMemcpy(t.data(), kv->prof, sizeof(unsigned long long) * n, hipMemcpyDeviceToHost));
-            double acc[11] = {0};
-            for (int l = 0; l < NL; ++l)
-                for (int i = 0; i < 10; ++i) acc[i] += (double)(t[3 + 10 * l + i] - t[2 + 10 * l + i]);
-            float* o = (float*)dst_host;
-            for (int i = 0; i < 10; ++i) o[i] = (float)(acc[i] / NL * 0.01);      // 100 MHz ticks -> microseconds
-            o[10] = (float)((double)(t[3 + 10 * NL] - t[2 + 10 * NL]) * 0.01);
+            for (size_t i = 0; i < n; ++i) ((float*)dst_host)[i] = (float)((double)(t[i] - t[0]) * 0.01);
             return SJ_OK;
         }
         default: return fail(SJ_EINVAL, "unknown debug item %d", what);

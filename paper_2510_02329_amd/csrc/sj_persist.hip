@@ -1,0 +1,1085 @@
+// Persistent whole-forward kernel for small row counts (R = batch * (gamma + 1) <= 8, bf16): the target forward of
+// the verification step (paper Eq. 2 / Eq. 4) from the embedding to the LM head in ONE launch.
+//
+// Why: at batch 1 a decoder layer is five dependent weight streams of 33 - 235 MB plus attention.  As separate
+// kernels every one of them drains and refills the memory pipeline, and nothing streams while attention and the
+// norms resolve their dependent round trips.  Here the weights of the whole model flow through one continuous
+// stream per compute unit that never waits for a dependency:
+//   * 256 workgroups, one per CU, each 8 compute waves + 2 loader waves;
+//   * the LOADER waves walk the workgroup's static schedule of weight fragments (1 KB = one 16 x 32 bf16 MFMA
+//     operand) and move them with direct global->LDS loads (streaming cache policy) into a ring of 14 stages of
+//     8 fragments, 13 stages (104 KB per CU) ahead of the compute waves.  Weights do not depend on activations, so
+//     the ring keeps filling while the compute waves wait at a device-wide barrier, run an epilogue or do attention;
+//   * a STAGE is one fragment per compute wave; all ten waves meet at one LDS-only barrier per stage;
+//   * a matrix is split so that every CU owns `nt` n-tiles and a K-slice; the 8 compute waves split that slice again
+//     and keep their share of the activation operand in registers (loaded once per phase), so the operand is not
+//     streamed at all; their partial tiles meet in LDS (wave order: deterministic) and 512 threads run the epilogue;
+//   * phases are separated by a flag barrier across the 256 workgroups (every workgroup publishes an epoch, workgroup
+//     0 collects them and releases one word).  Data crossing it is written with write-through stores and read after
+//     an agent-scope acquire;
+//   * with R <= 8 the 16 operand rows of an MFMA carry BOTH bf16 planes of the fp32 activation (row r: hi, row
+//     r + 8: lo); the two halves of the product are added in the epilogue: one MFMA per weight fragment;
+//   * RMSNorm is split around the products: the producer of the residual writes x * gain as the packed operand plus
+//     per-tile sums of squares, the consumer scales its outputs by the row's 1/rms;
+//   * attention is wave-local: task = (sequence, kv head, query tile, 32-key chunk), the block's own rows being one
+//     more chunk (rotary, storage rounding and the cache append happen there); partials are merged in chunk order by
+//     a second set of tasks after a barrier.
+// Every wait is bounded; a wait that runs out sets an abort word that makes all later waits fall through, so the
+// grid always drains.
+#include "sj_persist_api.h"
+
+namespace sj {
+
+constexpr int P_CW = 8;                          // compute waves
+constexpr int P_LW = 2;                          // loader waves (4 fragments per stage each)
+constexpr int P_THREADS = (P_CW + P_LW) * 64;
+constexpr int P_NSA = 14;                        // ring stages
+constexpr int P_PER = P_CW / P_LW;               // loads per loader wave and stage
+constexpr unsigned P_SPIN_LIMIT = 2000000u;
+constexpr int P_AUX_STREAM = 2;                  // cache policy of the weight loads: non-temporal
+
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+constexpr int P_MAXL = 128;                      // decoder layers whose weight table fits the LDS copy
+struct PShared {
+    float inv_rms[PERSIST_MAXR];
+    int pad[8];
+    PersistLayer lay[P_MAXL];                                         // the layer table: read by every wave without a vector load
+    PersistArgs args;                                                 // the compute waves' copy of the kernel arguments
+    float red[4][P_CW][256];                                          // 32 KB: partial tiles of one reduce round
+    __attribute__((aligned(1024))) u32x4 ring[P_NSA][P_CW][64];       // 112 KB
+};
+
+// ---- device-wide barrier ---------------------------------------------------------------------------
+__device__ __forceinline__ bool aborted(const PersistBar* bar) { return ld_coh(&bar->abort) != 0; }
+
+// one wave; every store of the workgroup that the others must see has completed (vmcnt(0) + workgroup barrier)
+__device__ __forceinline__ void grid_arrive(PersistBar* bar, unsigned epoch) {
+    if ((threadIdx.x & 63) == 0) st_coh(&bar->flag[blockIdx.x * 32], epoch);
+}
+__device__ __forceinline__ void grid_wait(PersistBar* bar, unsigned epoch) {
+    const int lane = threadIdx.x & 63;
+    if (blockIdx.x == 0) {
+        int ok = 1;
+        for (unsigned w = lane; w < gridDim.x; w += 64) {
+            unsigned spins = 0;
+            while ((int)(ld_coh(&bar->flag[w * 32]) - epoch) < 0) {
+                if (++spins > P_SPIN_LIMIT || aborted(bar)) { ok = 0; break; }
+            }
+        }
+        ok = __all(ok);
+        if (lane == 0) { if (!ok) st_coh(&bar->abort, 1u); st_coh(&bar->go, epoch); }
+    }
+    if (lane == 0) {
+        unsigned spins = 0;
+        while ((int)(ld_coh(&bar->go) - epoch) < 0) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > P_SPIN_LIMIT || aborted(bar)) { st_coh(&bar->abort, 1u); break; }
+        }
+    }
+}
+
+// ---- packed operand ------------------------------------------------------------------------------
+// element offset of (row16, k): row16 0-7 = hi plane of rows 0-7, 8-15 = lo plane
+__device__ __forceinline__ size_t packed_off(int row16, int k) {
+    return ((size_t)(k >> 5) * 64 + (size_t)((k & 31) >> 3) * 16 + row16) * 8 + (k & 7);
+}
+// 8 neighbouring lanes (lane & 7 = position) hold 8 consecutive columns k0 .. k0 + 7 of row `row`: the leader
+// (position 0, `store` set) writes both planes as 2 x 2 eight-byte write-through stores.
+__device__ __forceinline__ void pack8_store(bf16_t* B, int row, int k0, float v, bool store) {
+    const bf16_t h = f32_to_bf16(v);
+    const bf16_t l = f32_to_bf16(v - bf16_to_f32(h));
+    const unsigned h32 = (unsigned)h | ((unsigned)(__shfl_down((int)h, 1, 64) & 0xffff) << 16);
+    const unsigned l32 = (unsigned)l | ((unsigned)(__shfl_down((int)l, 1, 64) & 0xffff) << 16);
+    const unsigned long long h64 = (unsigned long long)h32 | ((unsigned long long)(unsigned)__shfl_down((int)h32, 2, 64) << 32);
+    const unsigned long long l64 = (unsigned long long)l32 | ((unsigned long long)(unsigned)__shfl_down((int)l32, 2, 64) << 32);
+    const unsigned long long h64b = __shfl_down(h64, 4, 64), l64b = __shfl_down(l64, 4, 64);
+    if (store) {
+        unsigned long long* ph = reinterpret_cast<unsigned long long*>(B + packed_off(row, k0));
+        unsigned long long* pl = reinterpret_cast<unsigned long long*>(B + packed_off(row + 8, k0));
+        st_coh(ph, h64); st_coh(ph + 1, h64b);
+        st_coh(pl, l64); st_coh(pl + 1, l64b);
+    }
+}
+
+// ---- write-once slots ------------------------------------------------------------------------------
+__device__ __forceinline__ bf16_t* bx_slot(const PersistArgs& a, int i) { return a.Bx + (size_t)i * a.md.d * 16; }
+__device__ __forceinline__ float* ssq_slot(const PersistArgs& a, int i) { return a.ssq + (size_t)i * PERSIST_MAXR * (a.md.d / 16); }
+__device__ __forceinline__ bf16_t* battn_slot(const PersistArgs& a, int l) { return a.Battn + (size_t)l * a.md.Hq * a.md.hd * 16; }
+__device__ __forceinline__ bf16_t* bact_slot(const PersistArgs& a, int l) { return a.Bact + (size_t)l * a.md.F * 16; }
+__device__ __forceinline__ float* qkv_slot(const PersistArgs& a, int l) {
+    return a.qkv + (size_t)l * 2 * PERSIST_MAXR * (a.md.Hq + 2 * a.md.Hkv) * a.md.hd;
+}
+__device__ __forceinline__ size_t new_slot(const PersistArgs& a, int l, int bi, int kvh) {
+    return (((size_t)l * a.sp->nseq + bi) * a.md.Hkv + kvh) * PERSIST_MAXR * a.md.hd;
+}
+
+// ---- schedule -------------------------------------------------------------------------------------
+// One segment = one item of a GEMM phase of this workgroup: NT tiles from tile0, k-steps ks0 + 8 q + w of wave w
+// (q < KW): the 8 fragments of a stage are 8 KB of consecutive memory and a tile is one sequential stream.
+struct Seg {
+    const char* W;
+    int KS, NT, KW, tile0, ks0, tmax;
+    bool first, last;
+};
+enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3 };
+
+struct Sched {
+    const PersistArgs& a;
+    const PersistLayer* lay;
+    int cu, nlayerseg, lm_t0, lm_t1, nlm, nseg;
+    __device__ Sched(const PersistArgs& a_, const PersistLayer* lay_) : a(a_), lay(lay_) {
+        cu = blockIdx.x;
+        nlayerseg = a.NL * 4;
+        const long long tv = a.md.V / 16;
+        lm_t0 = (int)(cu * tv / PERSIST_WGS);
+        lm_t1 = (int)((cu + 1) * tv / PERSIST_WGS);
+        nlm = (lm_t1 - lm_t0 + 7) / 8;
+        nseg = nlayerseg + nlm;
+    }
+    __device__ Seg seg(int idx) const {
+        Seg s;
+        const ModelDims& md = a.md;
+        if (idx < nlayerseg) {
+            const int l = idx >> 2, ph = idx & 3;
+            const PersistLayer& L = lay[l];
+            PersistSplit sp;
+            int tiles;
+            if (ph == PH_QKV) { s.W = (const char*)L.wqkv; s.KS = md.d / 32; sp = a.s_qkv; tiles = (md.Hq + 2 * md.Hkv) * md.hd / 16; }
+            else if (ph == PH_O) { s.W = (const char*)L.wo; s.KS = md.Hq * md.hd / 32; sp = a.s_o; tiles = md.d / 16; }
+            else if (ph == PH_GU) { s.W = (const char*)L.wgu; s.KS = md.d / 32; sp = a.s_gu; tiles = 2 * md.F / 16; }
+            else { s.W = (const char*)L.wd; s.KS = md.F / 32; sp = a.s_d; tiles = md.d / 16; }
+            s.NT = sp.nt; s.KW = sp.kw;
+            s.tile0 = (cu / sp.ksplit) * sp.nt;
+            s.ks0 = (cu % sp.ksplit) * P_CW * sp.kw;
+            s.tmax = tiles;
+            s.first = s.last = true;
+        } else {
+            const int i = idx - nlayerseg;
+            s.W = (const char*)a.lm_head; s.KS = md.d / 32; s.NT = 8; s.KW = md.d / 32 / P_CW;
+            s.tile0 = lm_t0 + 8 * i; s.ks0 = 0; s.tmax = lm_t1;
+            s.first = (i == 0); s.last = (i == nlm - 1);
+        }
+        return s;
+    }
+};
+
+// ---- loader waves ---------------------------------------------------------------------------------
+__device__ __forceinline__ int attn_merge_rounds(const PersistArgs& a);
+__device__ void loader_main(const PersistArgs& a, PShared& sm, int lw) {
+    const Sched sc(a, sm.lay);
+    const int lane = threadIdx.x & 63;
+    // Issue cursor.  A stage is 8 KB of consecutive memory (this wave moves 4 KB of it: four loads whose
+    // instruction offsets 0, 1, 2, 3 KB apply to the global and the LDS address alike); stages of a tile follow
+    // each other, tiles are `tile_skip` apart.  The per-stage work is a handful of instructions: the loader must
+    // never be what a stage waits for.
+    int iidx = 0, islot = 0, qleft = 0, tleft = 0, tile_cur = 0, tile_max = 0, kw = 0;
+    long long tile_skip = 0;
+    const char* p = nullptr;
+    auto enter = [&](int idx) {
+        const Seg g = sc.seg(idx);
+        p = g.W + (((size_t)min(g.tile0, g.tmax - 1) * g.KS + g.ks0 + lw * P_PER) * 64 + lane) * 16;
+        kw = g.KW; qleft = g.KW; tleft = g.NT; tile_cur = g.tile0; tile_max = g.tmax - 1;
+        tile_skip = (long long)(g.KS - P_CW * g.KW) * 1024;
+    };
+    enter(0);
+    auto issue = [&]() {
+        const __attribute__((address_space(1))) void* src = (const __attribute__((address_space(1))) void*)p;
+        __attribute__((address_space(3))) void* dst = (__attribute__((address_space(3))) void*)&sm.ring[islot][lw * P_PER][0];
+        __builtin_amdgcn_global_load_lds(src, dst, 16, 0, P_AUX_STREAM);
+        __builtin_amdgcn_global_load_lds(src, dst, 16, 1024, P_AUX_STREAM);
+        __builtin_amdgcn_global_load_lds(src, dst, 16, 2048, P_AUX_STREAM);
+        __builtin_amdgcn_global_load_lds(src, dst, 16, 3072, P_AUX_STREAM);
+        islot = (islot + 1 == P_NSA) ? 0 : islot + 1;
+        p += P_CW * 1024;
+        if (--qleft == 0) {                                  // next tile (a tile past the end of N repeats the last one)
+            qleft = kw;
+            if (tile_cur < tile_max) { p += tile_skip; ++tile_cur; } else p -= (long long)P_CW * kw * 1024;
+            if (--tleft == 0) {
+                // next segment; past the end of the schedule the cursor re-reads the last tile into free slots
+                if (iidx + 1 < sc.nseg) { ++iidx; enter(iidx); } else tleft = 1;     // stays inside the last segment's tiles
+            }
+        }
+    };
+    static_assert(P_PER == 4, "four loads per stage and loader wave");
+    static_assert((P_NSA - 1) * P_PER < 64, "the load counter holds 63");
+    constexpr int BEHIND = (P_NSA - 2) * P_PER;
+    const int merge_rounds = attn_merge_rounds(a);
+    for (int s = 0; s < P_NSA - 1; ++s) issue();
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(BEHIND));       // stage 0 has landed
+    lds_barrier();                                       // end of the embedding stage
+    for (int idx = 0; idx < sc.nseg; ++idx) {
+        const Seg sg = sc.seg(idx);
+        if (idx < sc.nlayerseg && (idx & 3) == PH_O) {   // the workgroup barriers of the attention phases
+            lds_barrier(); lds_barrier(); lds_barrier();          // chunks: after the wait, query fragments, end
+            lds_barrier();                                        // merge: after the wait
+            for (int r = 0; r < 3 * merge_rounds; ++r) lds_barrier();
+            lds_barrier();
+        }
+        if (sg.first) lds_barrier();
+        const int nst = sg.NT * sg.KW;
+        for (int j = 0; j < nst; ++j) {
+#ifdef P_DEBUG_STAGES
+            const bool dbg = a.prof && blockIdx.x == 0 && lw == 0 && lane == 0 && idx == sc.nlayerseg - 4 + PH_O && j < 16;
+            if (dbg) a.prof[5100 + j] = wall_clock64();
+#endif
+            issue();                                     // its slot was read during the previous stage
+#ifdef P_DEBUG_STAGES
+            if (dbg) a.prof[5200 + j] = wall_clock64();
+#endif
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(BEHIND));   // the next stage has landed
+#ifdef P_DEBUG_STAGES
+            if (dbg) a.prof[5000 + j] = wall_clock64();
+#endif
+            lds_barrier();
+        }
+        const int rounds = (sg.NT + 3) / 4;
+        for (int r = 0; r < 2 * rounds; ++r) lds_barrier();
+        if (sg.last) lds_barrier();
+    }
+    wait_vm0();
+}
+
+// ---- GEMM phase of the compute waves ----------------------------------------------------------------
+enum { PEPI_QKV = 0, PEPI_RESID = 1, PEPI_SWIGLU = 2, PEPI_LOGITS = 3 };
+
+struct EpiCtx {
+    int R;
+    const bf16_t* gain;     // PEPI_RESID: gain of the norm that follows
+    bool last_layer;        // PEPI_RESID of the last down projection: also the final hidden state
+    int kslice;             // PEPI_QKV: K-slice index of this workgroup
+    const float* ssq_in;    // sums of squares of the operand's rows (phases that apply 1/rms)
+    bf16_t* Bout;           // PEPI_RESID / PEPI_SWIGLU: packed operand written for the next phase
+    float* ssq_out;         // PEPI_RESID
+    float* qkv_out;         // PEPI_QKV
+};
+
+struct CState {
+    unsigned epoch;
+    int slot;
+    int nprof;
+};
+// diagnostic timestamp of workgroup 0, wave 0 (compiled in with -DP_PROFILE only)
+__device__ __forceinline__ void pstamp(const PersistArgs& a, CState& cs) {
+#ifdef P_PROFILE
+    if (a.prof && blockIdx.x == 0 && threadIdx.x == 0 && cs.nprof < 8192) a.prof[cs.nprof] = wall_clock64();
+    ++cs.nprof;
+#endif
+}
+
+// 1/rms of every row from the per-tile sums of squares (one wave): the loads are issued when the phase starts and
+// consumed just before the epilogue that needs the result, so their latency is never waited for
+struct RmsLoads {
+    float v[PERSIST_MAXR][4];
+    __device__ __forceinline__ void issue(const PersistArgs& a, const float* __restrict__ ssq, int R) {
+        const int lane = threadIdx.x & 63, ntx = a.md.d / 16;   // ntx = 256 (checked by the plan): four tiles per lane
+#pragma unroll
+        for (int r = 0; r < PERSIST_MAXR; ++r)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[r][t] = ssq[(size_t)min(r, R - 1) * ntx + lane + 64 * t];
+    }
+    __device__ __forceinline__ void finish(const PersistArgs& a, int R, PShared& sm, float (&inv)[PERSIST_MAXR]) const {
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int r = 0; r < PERSIST_MAXR; ++r) {
+            const float tot = wave_sum((v[r][0] + v[r][1]) + (v[r][2] + v[r][3]));
+            inv[r] = 1.0f / sqrtf(tot / (float)a.md.d + a.md.eps);
+            if (lane == 0 && r < R) sm.inv_rms[r] = inv[r];
+        }
+    }
+};
+
+template <int EPI>
+__device__ __forceinline__ void epilogue(const PersistArgs& a, const EpiCtx& ec, PShared& sm, int tile, int m, int n, float v, bool tvalid, float xpre) {
+    const ModelDims& md = a.md;
+    const bool valid = tvalid && m < ec.R;
+    if constexpr (EPI == PEPI_QKV) {
+        const int N = (md.Hq + 2 * md.Hkv) * md.hd;
+        if (valid) st_coh(&ec.qkv_out[((size_t)ec.kslice * PERSIST_MAXR + m) * N + tile * 16 + n], v * sm.inv_rms[m]);
+    } else if constexpr (EPI == PEPI_RESID) {
+        const int col = tile * 16 + n, ntx = md.d / 16;
+        float xn = 0.f;
+        if (valid) {
+            xn = xpre + v;
+            st_coh(&a.x[(size_t)m * md.d + col], xn);
+        }
+        const float y = xn * bf16_to_f32(ec.gain[col]);
+        pack8_store(ec.Bout, m, tile * 16 + (n & 8), y, valid && (n & 7) == 0);
+        if (ec.last_layer && valid) st_coh(&a.hn32[(size_t)m * md.d + col], y);
+        float ss = xn * xn;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) ss += __shfl_xor(ss, o, 64);
+        if (valid && n == 0) st_coh(&ec.ssq_out[(size_t)m * ntx + tile], ss);
+    } else if constexpr (EPI == PEPI_SWIGLU) {
+        // tile column n < 8 is gate of FFN column 8*tile + n, column n + 8 its up projection
+        const float up = __shfl_down(v, 8, 64);
+        const float sc = sm.inv_rms[m & 7];
+        const float gate = v * sc;
+        const float act = gate / (1.0f + expf(-gate)) * (up * sc);
+        pack8_store(ec.Bout, m, tile * 8, act, valid && n == 0);
+    } else {
+        const int ntv = md.V / 16;
+        const float logit = v * sm.inv_rms[m & 7];
+        float mx = logit;
+        int arg = tile * 16 + n;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+            const float omx = __shfl_xor(mx, o, 64);
+            const int oarg = __shfl_xor(arg, o, 64);
+            if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+        }
+        float se = 0.f;
+        if (md.inv_temp > 0.f) {
+            se = expf((logit - mx) * md.inv_temp);
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) se += __shfl_xor(se, o, 64);
+        }
+        if (valid) {
+            a.logits[(size_t)m * md.V + tile * 16 + n] = logit;
+            if (n == 0) a.stats[(size_t)m * ntv + tile] = float4{mx, se, __int_as_float(arg), 0.f};
+        }
+    }
+}
+
+// One segment.  KW = KB * SUB k-steps per wave: the wave's operand fragments are held in registers KB at a time (two
+// sets when SUB > 1: the next set is requested while the current one is used).
+template <int NT, int KB, int SUB, int EPI, bool NEED_RMS, bool ONE_ITEM>
+__device__ __forceinline__ void gemm_seg(const PersistArgs& a, const Seg& sg, const bf16_t* __restrict__ Bp, const EpiCtx& ec,
+                                         PShared& sm, CState& cs, Frag (&bf)[16]) {
+    static_assert(EPI != PEPI_RESID || NT == 1, "the residual epilogue prefetches the one tile of the workgroup");
+    static_assert(SUB == 1 || NT == 1, "K-blocks are walked in order only for a single tile");
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, g = lane >> 4;
+    const bool first = ONE_ITEM || sg.first, last = ONE_ITEM || sg.last;
+    pstamp(a, cs);
+    // the residual of this workgroup's own tile: written by this workgroup two phases ago, independent of the barrier
+    float xpre = 0.f;
+    if (EPI == PEPI_RESID && tid < 128 && (tid >> 4) < ec.R) xpre = ld_coh(&a.x[(size_t)(tid >> 4) * a.md.d + sg.tile0 * 16 + (tid & 15)]);
+    auto load_b = [&](Frag (&dst)[16], int sb) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(Bp) + ((size_t)(sg.ks0 + sb * KB * P_CW + w)) * 64 + lane;
+#pragma unroll
+        for (int q = 0; q < KB; ++q) dst[q].u = src[(size_t)q * P_CW * 64];
+    };
+    RmsLoads rms;
+    if (first) {
+        if (w == 0) grid_wait(a.bar, cs.epoch);
+        pstamp(a, cs);
+        lds_barrier();
+        pstamp(a, cs);
+        load_b(bf, 0);
+        if (NEED_RMS && w == 0) rms.issue(a, ec.ssq_in, ec.R);
+        pstamp(a, cs);
+    }
+    pstamp(a, cs);
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int slot_r = cs.slot;                                    // in a register: cs lives in the caller's frame
+#ifdef P_DEBUG_STAGES
+    unsigned long long dbg[16];
+    const unsigned long long dbg0 = wall_clock64();
+#endif
+    // stage order: tile-major, k-step inner: the workgroup's tiles are one sequential stream of 8 KB stages
+    auto k_loop = [&](Frag (&b)[16]) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+            for (int q = 0; q < KB; ++q) {
+                Frag fa;
+                fa.u = sm.ring[slot_r][w][lane];
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.h, b[q].h, acc[t], 0, 0, 0);
+                lds_barrier();
+                slot_r = (slot_r + 1 == P_NSA) ? 0 : slot_r + 1;
+#ifdef P_DEBUG_STAGES
+                if (EPI == PEPI_RESID && KB == 16 && t == 0) dbg[q] = wall_clock64();
+#endif
+            }
+        }
+    };
+    if constexpr (SUB == 1) {
+        k_loop(bf);
+    } else {
+        Frag bf2[16];
+#pragma unroll
+        for (int sb = 0; sb < SUB; sb += 2) {
+            if (sb + 1 < SUB) load_b(bf2, sb + 1);
+            k_loop(bf);
+            if (sb + 2 < SUB) load_b(bf, sb + 2);
+            if (sb + 1 < SUB) k_loop(bf2);
+        }
+    }
+    cs.slot = slot_r;
+#ifdef P_DEBUG_STAGES
+    if (EPI == PEPI_RESID && KB == 16 && a.prof && blockIdx.x == 0 && threadIdx.x == 0) {
+        a.prof[4000] = dbg0;
+        for (int q = 0; q < 16; ++q) a.prof[4001 + q] = dbg[q];
+    }
+#endif
+    pstamp(a, cs);
+    if (NEED_RMS && first && w == 0) {
+        float inv[PERSIST_MAXR];
+        rms.finish(a, ec.R, sm, inv);
+        if (EPI == PEPI_LOGITS) {
+            // this workgroup stored its 16 columns of the final hidden state as x * gain: apply 1/rms so that the
+            // judge (Eq. 5) and the debug read-out see the normed state
+            const int ntx = a.md.d / 16;
+            for (int tile = blockIdx.x; tile < ntx; tile += gridDim.x)
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int e = lane + 64 * half, m = e >> 4, n = e & 15;
+                    if (m < ec.R) {
+                        float* p = &a.hn32[(size_t)m * a.md.d + tile * 16 + n];
+                        st_coh(p, ld_coh(p) * inv[m]);
+                    }
+                }
+        }
+    }
+    // reduce rounds of 4 tiles: D[n = 4g+i][row16 = r] -> red[slot][w][row16*16 + n]; thread (slot, e): m = e / 16,
+    // n = e % 16 adds the 8 waves' hi (row16 = m) and lo (row16 = m + 8) halves and runs the epilogue
+    constexpr int ROUNDS = (NT + 3) / 4;
+#pragma unroll
+    for (int rd = 0; rd < ROUNDS; ++rd) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (rd * 4 + s < NT) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sm.red[s][w][r * 16 + 4 * g + i] = acc[rd * 4 + s][i];
+            }
+        }
+        lds_barrier();
+        const int slot = w >> 1, e = tid & 127;
+        if (rd * 4 + slot < NT) {                                        // uniform for the wave
+            float v = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < P_CW; ++ww) v += sm.red[slot][ww][e] + sm.red[slot][ww][e + 128];
+            const int tile = sg.tile0 + rd * 4 + slot;
+            epilogue<EPI>(a, ec, sm, tile, e >> 4, e & 15, v, tile < sg.tmax, xpre);
+        }
+        lds_barrier();
+    }
+    pstamp(a, cs);
+    if (last) {
+        wait_vm0();
+        lds_barrier();
+        ++cs.epoch;
+        if (w == 0) grid_arrive(a.bar, cs.epoch);
+    }
+    pstamp(a, cs);
+}
+
+// ---- attention ---------------------------------------------------------------------------------------
+// Everything a wave needs is requested before anything is consumed: the phases are chains of dependent memory
+// round trips, not bytes.  K-slice partials of the QKV projection: P_NP of them (fixed by the plan).
+constexpr int P_NP = 2;
+constexpr int A_HD = 128, A_KSTEP = 32, A_KF = 8, A_KK = 4, A_HT = 8, A_HALF = 64;
+
+struct AttnGeom {
+    int rps, R, M, Nq, Nk, N, b, L, cap;
+    bf16_t *Kb, *Vb;
+    const float* qkv;        // this layer's K-slice partials
+    bf16_t *knew, *vnewT;    // this layer's staging of the block's own rows of (sequence, kv head)
+    bf16_t* Battn;
+};
+__device__ __forceinline__ AttnGeom attn_geom(const PersistArgs& a, int layer, int bi, int kvh) {
+    const size_t layer_off = (size_t)layer * a.kv.layer_stride;
+    AttnGeom g;
+    const ModelDims& md = a.md;
+    g.rps = a.sp->rps; g.R = a.sp->nseq * g.rps; g.M = md.G * g.rps;
+    g.Nq = md.Hq * A_HD; g.Nk = md.Hkv * A_HD; g.N = g.Nq + 2 * g.Nk;
+    g.b = a.sp->seq_base + bi;
+    g.L = a.kv.len[g.b]; g.cap = a.kv.cap[g.b];
+    g.Kb = a.kv.K + layer_off + a.kv.seq_off[g.b] + (size_t)kvh * g.cap * A_HD;
+    g.Vb = a.kv.V + layer_off + a.kv.seq_off[g.b] + (size_t)kvh * A_HD * g.cap;
+    g.qkv = qkv_slot(a, layer);
+    g.knew = a.knew + new_slot(a, layer, bi, kvh);
+    g.vnewT = a.vnewT + new_slot(a, layer, bi, kvh);
+    g.Battn = battn_slot(a, layer);
+    return g;
+}
+
+// Query fragments of one (sequence, kv head, query tile) are built ONCE per workgroup and shared through LDS: waves
+// 0..3 each sum, rotate and split a quarter (pair of head-dimension steps k2, k2 + 2; elements 4v .. 4v + 3 of the
+// lane's eight) and deposit it in fragment layout [step kk][plane][lane]; after a workgroup barrier any wave reads
+// the eight fragments with eight LDS loads.  issue() only loads, finish() consumes.
+struct QPiece {
+    float4 lo[P_NP], hi[P_NP], cs[2];
+    __device__ __forceinline__ void issue(const PersistArgs& a, const AttnGeom& ag, int row, int head, int g, int wq) {
+        const int i0 = (wq >> 1) * A_KSTEP + g * A_KF + 4 * (wq & 1);
+#pragma unroll
+        for (int s = 0; s < P_NP; ++s) {
+            const float* p = ag.qkv + ((size_t)s * PERSIST_MAXR + row) * ag.N + head * A_HD + i0;
+            lo[s] = *reinterpret_cast<const float4*>(p);
+            hi[s] = *reinterpret_cast<const float4*>(p + A_HALF);
+        }
+        const float* csr = a.cs + ((size_t)row * A_HALF + i0) * 2;
+        cs[0] = *reinterpret_cast<const float4*>(csr);
+        cs[1] = *reinterpret_cast<const float4*>(csr + 4);
+    }
+    __device__ __forceinline__ void finish(u32x4* qlds, int lane, int wq) const {
+        float4 sl = lo[0], sh = hi[0];
+#pragma unroll
+        for (int s = 1; s < P_NP; ++s) {
+            sl.x += lo[s].x; sl.y += lo[s].y; sl.z += lo[s].z; sl.w += lo[s].w;
+            sh.x += hi[s].x; sh.y += hi[s].y; sh.z += hi[s].z; sh.w += hi[s].w;
+        }
+        const float l4[4] = {sl.x, sl.y, sl.z, sl.w}, h4[4] = {sh.x, sh.y, sh.z, sh.w};
+        const float c4[4] = {cs[0].x, cs[0].z, cs[1].x, cs[1].z}, s4[4] = {cs[0].y, cs[0].w, cs[1].y, cs[1].w};
+        bf16_t out[2][2][4];                                   // [lo / hi half of the head dimension][plane][element]
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float f[2] = {l4[e] * c4[e] - h4[e] * s4[e], h4[e] * c4[e] + l4[e] * s4[e]};
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const bf16_t h = f32_to_bf16(f[hh]);
+                out[hh][0][e] = h;
+                out[hh][1][e] = f32_to_bf16(f[hh] - bf16_to_f32(h));
+            }
+        }
+        const int k2 = wq >> 1, v = wq & 1;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int pl = 0; pl < 2; ++pl) {
+                const uint2 pk = uint2{(uint32_t)out[hh][pl][0] | ((uint32_t)out[hh][pl][1] << 16), (uint32_t)out[hh][pl][2] | ((uint32_t)out[hh][pl][3] << 16)};
+                reinterpret_cast<uint2*>(&qlds[((k2 + 2 * hh) * 2 + pl) * 64 + lane])[v] = pk;
+            }
+    }
+};
+__device__ __forceinline__ void q_read(const u32x4* qlds, int lane, Frag (&qf)[A_KK][2]) {
+#pragma unroll
+    for (int kk = 0; kk < A_KK; ++kk)
+#pragma unroll
+        for (int pl = 0; pl < 2; ++pl) qf[kk][pl].u = qlds[(kk * 2 + pl) * 64 + lane];
+}
+
+// S^T of one step of 32 keys, masked, scaled:  s[t][i] belongs to in-step key index 8g + 4t + i
+template <typename Vis>
+__device__ __forceinline__ void attn_scores(const Frag (&kf)[2][A_KK], const Frag (&qf)[A_KK][2], float scale, int g, Vis visible, f32x4 (&s)[2]) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < A_KK; ++kk)
+#pragma unroll
+            for (int pl = 0; pl < 2; ++pl) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][kk].h, qf[kk][pl].h, s[t], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s[t][i] = visible(A_KF * g + 4 * t + i) ? s[t][i] * scale : -INFINITY;
+    }
+}
+
+// online-softmax update of (m_run, l_run) with the step's scores; returns the rescale factor of the accumulators and
+// the probabilities as the two-plane B operand of the PV product
+__device__ __forceinline__ float attn_softmax(const f32x4 (&s)[2], float& m_run, float& l_run, Frag (&pf)[2]) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[t][i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const bool dead = (m_new == -INFINITY);
+    const float alpha = dead ? 1.f : __expf(m_run - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float p = dead ? 0.f : __expf(s[t][i] - m_new);
+            psum += p;
+            Traits<bf16_t>::pack_split<2>(pf, 4 * t + i, p);
+        }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    return alpha;
+}
+
+// Task 1a: one chunk of CACHED keys against one query tile, in two halves: load() requests the chunk's first K / V
+// step (nothing in it depends on this layer's projections, so it is called before the device-wide barrier);
+// run() takes the shared query fragments and publishes o^T (8 head tiles), running max and sum.
+struct ChunkTask {
+    AttnGeom ag;
+    int k_begin, k_end, r, g, j;
+    bool exists, valid;
+    Frag kf[2][A_KK], vf[A_HT];
+    __device__ __forceinline__ void load_k(int key0) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int krow = key0 + A_KF * (r >> 2) + 4 * t + (r & 3);          // capacities are multiples of 64: inside
+#pragma unroll
+            for (int kk = 0; kk < A_KK; ++kk)
+                kf[t][kk].u = *reinterpret_cast<const u32x4*>(ag.Kb + (size_t)krow * A_HD + kk * A_KSTEP + g * A_KF);
+        }
+    }
+    __device__ __forceinline__ void load_v(int key0) {
+#pragma unroll
+        for (int ht = 0; ht < A_HT; ++ht) vf[ht].u = *reinterpret_cast<const u32x4*>(ag.Vb + (size_t)(ht * 16 + r) * ag.cap + key0 + g * A_KF);
+    }
+    __device__ __forceinline__ void load(const PersistArgs& a, int layer, int bi, int kvh, int qt, int c, bool has_task) {
+        const int lane = threadIdx.x & 63;
+        r = lane & 15; g = lane >> 4;
+        exists = false;
+        if (!has_task) return;
+        ag = attn_geom(a, layer, bi, kvh);
+        k_begin = c * a.chunk_keys;
+        if (k_begin >= ag.L) return;                               // uniform: this chunk does not exist
+        exists = true;
+        k_end = min(k_begin + a.chunk_keys, ag.L);
+        const int m = qt * 16 + r;
+        valid = m < ag.M;
+        j = valid ? m % ag.rps : 0;
+        load_k(k_begin);
+        load_v(k_begin);
+    }
+    __device__ __forceinline__ void run(const PersistArgs& a, const u32x4* qlds, float* __restrict__ out) {
+        if (!exists) return;
+        const int lane = threadIdx.x & 63;
+        Frag qf[A_KK][2];
+        q_read(qlds, lane, qf);
+        f32x4 o[A_HT];
+        float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+        for (int ht = 0; ht < A_HT; ++ht) o[ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int key0 = k_begin; key0 < k_end; key0 += A_KSTEP) {
+            if (key0 != k_begin) { load_k(key0); load_v(key0); }
+            f32x4 s[2];
+            attn_scores(kf, qf, a.md.scale, g, [&](int kidx) { return valid && key0 + kidx < ag.L; }, s);
+            Frag pf[2];
+            const float alpha = attn_softmax(s, m_run, l_run, pf);
+            if (key0 + A_KSTEP > ag.L) {                   // columns of V past the context: 0 * garbage must stay 0
+#pragma unroll
+                for (int ht = 0; ht < A_HT; ++ht)
+#pragma unroll
+                    for (int e = 0; e < A_KF; ++e)
+                        if (key0 + g * A_KF + e >= ag.L) vf[ht].s[e] = 0;
+            }
+#pragma unroll
+            for (int ht = 0; ht < A_HT; ++ht) {
+                o[ht] *= alpha;
+#pragma unroll
+                for (int pl = 0; pl < 2; ++pl) o[ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[ht].h, pf[pl].h, o[ht], 0, 0, 0);
+            }
+        }
+        float l = l_run;
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+#pragma unroll
+        for (int ht = 0; ht < A_HT; ++ht)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st_coh(out + (ht * 4 + i) * 64 + lane, o[ht][i]);
+        st_coh(out + (A_HT * 4) * 64 + lane, m_run);
+        st_coh(out + (A_HT * 4 + 1) * 64 + lane, l);
+    }
+};
+
+// Task 1b: K / V of one new row (block row j of one sequence, one kv head): sum of the K-slice partials, rotary on K,
+// rounding to the storage type, append at position L + j.  The rows also go, written through, into the layer's
+// staging slot, where the merge tasks of other workgroups read them in the same launch (cache lines around position
+// L may already sit in a cache from the chunk tasks; the staging lines cannot).
+__device__ __forceinline__ void attn_append(const PersistArgs& a, int layer, int bi, int kvh, int j) {
+    const AttnGeom ag = attn_geom(a, layer, bi, kvh);
+    const int lane = threadIdx.x & 63;
+    const int row = bi * ag.rps + j;
+    float klo[P_NP], khi[P_NP];
+    float2 vv[P_NP];
+#pragma unroll
+    for (int s = 0; s < P_NP; ++s) {
+        const float* p = ag.qkv + ((size_t)s * PERSIST_MAXR + row) * ag.N;
+        klo[s] = p[ag.Nq + kvh * A_HD + lane];
+        khi[s] = p[ag.Nq + kvh * A_HD + lane + A_HALF];
+        vv[s] = *reinterpret_cast<const float2*>(p + ag.Nq + ag.Nk + kvh * A_HD + 2 * lane);
+    }
+    const float2 cs = *reinterpret_cast<const float2*>(a.cs + ((size_t)row * A_HALF + lane) * 2);
+    float lo = klo[0], hi = khi[0], v0 = vv[0].x, v1 = vv[0].y;
+#pragma unroll
+    for (int s = 1; s < P_NP; ++s) { lo += klo[s]; hi += khi[s]; v0 += vv[s].x; v1 += vv[s].y; }
+    const bf16_t k0 = f32_to_bf16(lo * cs.x - hi * cs.y), k1 = f32_to_bf16(hi * cs.x + lo * cs.y);
+    const bf16_t w0 = f32_to_bf16(v0), w1 = f32_to_bf16(v1);
+    __hip_atomic_store(ag.knew + j * A_HD + lane, k0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(ag.knew + j * A_HD + lane + A_HALF, k1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(ag.vnewT + (2 * lane) * PERSIST_MAXR + j, w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(ag.vnewT + (2 * lane + 1) * PERSIST_MAXR + j, w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ag.L + j < ag.cap) {                                       // the host refuses calls that would not fit; never write outside
+        bf16_t* Kr = ag.Kb + (size_t)(ag.L + j) * A_HD;
+        Kr[lane] = k0;
+        Kr[lane + A_HALF] = k1;
+        ag.Vb[(size_t)(2 * lane) * ag.cap + ag.L + j] = w0;
+        ag.Vb[(size_t)(2 * lane + 1) * ag.cap + ag.L + j] = w1;
+    }
+}
+
+// Task 2: one (sequence, kv head, query tile, head tile) by the 8 compute waves of a workgroup: waves 0..6 merge their
+// share of the cached chunks' partials (chunk order), waves 0..3 also build the shared query fragments, wave 7 takes
+// the block's own rows (row j sees new rows 0..j, read from the layer's staging slot); the waves' results meet in LDS
+// and wave 0 combines them in wave order and writes the packed operand of the O projection.  Three workgroup barriers.
+struct MergePart { float m[P_CW + 1][64], l[P_CW + 1][64], o[P_CW + 1][4][64]; };
+constexpr int A_QLDS_OFF = 16 * 1024;                     // byte offset of the shared query fragments inside the reduce area
+static_assert(sizeof(MergePart) <= A_QLDS_OFF, "merge area overlaps the query fragments");
+
+__device__ __forceinline__ void attn_merge(const PersistArgs& a, int layer, int bi, int kvh, int qt, int ht, bool active, PShared& sm) {
+    constexpr int CB = 8;
+    MergePart& mp = *reinterpret_cast<MergePart*>(&sm.red[0][0][0]);
+    u32x4* qlds = reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(&sm.red[0][0][0]) + A_QLDS_OFF);
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const bool own = (w == P_CW - 1);
+    AttnGeom ag{};
+    int m = 0, gi = 0, j = 0, c_lo = 0, c_hi = 0;
+    bool valid = false;
+    const float* base = nullptr;
+    QPiece qp;
+    Frag kf[2][A_KK], vf;
+    if (active) {
+        ag = attn_geom(a, layer, bi, kvh);
+        m = qt * 16 + r;
+        valid = m < ag.M;
+        gi = valid ? m / ag.rps : 0; j = valid ? m - gi * ag.rps : 0;
+        const int QT = (ag.M + 15) / 16;
+        base = a.apart + (size_t)(((bi * a.md.Hkv + kvh) * QT + qt) * (a.nch_max - 1)) * PERSIST_APART;
+        const int ncc = (ag.L + a.chunk_keys - 1) / a.chunk_keys;
+        const int per = (ncc + P_CW - 2) / (P_CW - 1);               // waves 0..6 share the cached chunks
+        c_lo = min(w * per, ncc); c_hi = min(c_lo + per, ncc);
+        if (w < 4) qp.issue(a, ag, bi * ag.rps + j, kvh * a.md.G + gi, g, w);
+        if (own) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int jp = A_KF * (r >> 2) + 4 * t + (r & 3);
+                const bool kvalid = jp < ag.rps;
+#pragma unroll
+                for (int kk = 0; kk < A_KK; ++kk) {
+                    kf[t][kk].u = u32x4{0u, 0u, 0u, 0u};
+                    if (kvalid) kf[t][kk].u = *reinterpret_cast<const u32x4*>(ag.knew + jp * A_HD + kk * A_KSTEP + g * A_KF);
+                }
+            }
+            // the slot's 8 key columns: columns past this call's rows may hold an earlier call's values
+            vf.u = u32x4{0u, 0u, 0u, 0u};
+            if (g == 0) vf.u = *reinterpret_cast<const u32x4*>(ag.vnewT + (ht * 16 + r) * PERSIST_MAXR);
+#pragma unroll
+            for (int e = 0; e < A_KF; ++e)
+                if (g * A_KF + e >= ag.rps) vf.s[e] = 0;
+        }
+        float mx = -INFINITY, den = 0.f, num[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int c0 = c_lo; c0 < c_hi; c0 += CB) {
+            float mv[CB], lv[CB], ov[CB][4];
+#pragma unroll
+            for (int u = 0; u < CB; ++u) {
+                const float* pc = base + (size_t)min(c0 + u, c_hi - 1) * PERSIST_APART;
+                mv[u] = ld_coh(pc + (A_HT * 4) * 64 + lane);            // one reader per value: straight from memory
+                lv[u] = ld_coh(pc + (A_HT * 4 + 1) * 64 + lane);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ov[u][i] = ld_coh(pc + (ht * 4 + i) * 64 + lane);
+            }
+            if (c0 == c_lo && w < 4) qp.finish(qlds, lane, w);      // (its loads were issued ahead of the batch)
+            float bm = mx;
+#pragma unroll
+            for (int u = 0; u < CB; ++u) bm = fmaxf(bm, (c0 + u < c_hi) ? mv[u] : -INFINITY);
+            const float resc = (mx == -INFINITY) ? 0.f : __expf(mx - bm);
+            mx = bm;
+            den *= resc;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) num[i] *= resc;
+#pragma unroll
+            for (int u = 0; u < CB; ++u) {
+                const float f = (c0 + u < c_hi && mv[u] != -INFINITY) ? __expf(mv[u] - bm) : 0.f;
+                den += f * lv[u];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) num[i] += f * ov[u][i];
+            }
+        }
+        if (c_lo >= c_hi && w < 4) qp.finish(qlds, lane, w);
+        mp.m[w][lane] = mx; mp.l[w][lane] = den;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mp.o[w][i][lane] = num[i];
+    }
+    lds_barrier();                                            // the query fragments are in LDS
+    if (active && own) {
+        Frag qf[A_KK][2];
+        q_read(qlds, lane, qf);
+        f32x4 s[2];
+        attn_scores(kf, qf, a.md.scale, g, [&](int kidx) { return valid && kidx <= j; }, s);
+        Frag pf[2];
+        float m_run = -INFINITY, l_run = 0.f;
+        attn_softmax(s, m_run, l_run, pf);
+        f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int pl = 0; pl < 2; ++pl) o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.h, pf[pl].h, o, 0, 0, 0);
+        float l = l_run;
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        mp.m[P_CW][lane] = m_run; mp.l[P_CW][lane] = l;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mp.o[P_CW][i][lane] = o[i];
+    }
+    lds_barrier();
+    if (active && w == 0) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int u = 0; u <= P_CW; ++u) if (u != P_CW - 1) mx = fmaxf(mx, mp.m[u][lane]);
+        float den = 0.f, num[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u <= P_CW; ++u) {
+            if (u == P_CW - 1) continue;                      // wave 7 holds no cached chunks: its result is slot 8
+            const float mu = mp.m[u][lane];
+            const float f = (mu == -INFINITY) ? 0.f : __expf(mu - mx);
+            den += f * mp.l[u][lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) num[i] += f * mp.o[u][i][lane];
+        }
+        if (valid) {
+            const int row = bi * ag.rps + j, k = (kvh * a.md.G + gi) * A_HD + ht * 16 + 4 * g;
+            const float inv = 1.f / den;
+            unsigned hw[2], lw[2];
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const float v0 = num[2 * p] * inv, v1 = num[2 * p + 1] * inv;
+                const bf16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
+                hw[p] = (unsigned)h0 | ((unsigned)h1 << 16);
+                lw[p] = (unsigned)f32_to_bf16(v0 - bf16_to_f32(h0)) | ((unsigned)f32_to_bf16(v1 - bf16_to_f32(h1)) << 16);
+            }
+            st_coh(reinterpret_cast<unsigned long long*>(ag.Battn + packed_off(row, k)), (unsigned long long)hw[0] | ((unsigned long long)hw[1] << 32));
+            st_coh(reinterpret_cast<unsigned long long*>(ag.Battn + packed_off(row + 8, k)), (unsigned long long)lw[0] | ((unsigned long long)lw[1] << 32));
+        }
+    }
+    lds_barrier();
+}
+
+// rounds of merge tasks (one task per workgroup and round); the loader waves execute two barriers per round
+__device__ __forceinline__ int attn_merge_rounds(const PersistArgs& a) {
+    const int QT = (a.md.G * a.sp->rps + 15) / 16;
+    return (a.sp->nseq * a.md.Hkv * QT * A_HT + PERSIST_WGS - 1) / PERSIST_WGS;
+}
+
+// Workgroup c serves query group (sequence, kv head, query tile) c / cpg, cpg = 256 / groups workgroups per group
+// (at most 8 rows: at most 128 groups); its wave w takes cached chunk (c % cpg) + cpg * w: the host sizes the chunks
+// so that 8 * cpg of them cover the longest context.  The block's own K / V rows are appended by wave 7 of the first
+// nseq * Hkv * rps workgroups.
+__device__ __noinline__ void attention_chunks(const PersistArgs& a, int layer, CState& cs, PShared& sm) {
+    const ModelDims& md = a.md;
+    const StepParams* sp = a.sp;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = threadIdx.x & 63;
+    const int nseq = sp->nseq, rps = sp->rps;
+    const int QT = (md.G * rps + 15) / 16;
+    const int groups = nseq * md.Hkv * QT, cpg = max(1, PERSIST_WGS / groups);
+    const int ncc_max = a.nch_max - 1;
+    u32x4* qlds = reinterpret_cast<u32x4*>(&sm.red[0][0][0]);
+    pstamp(a, cs);
+    const int grp = blockIdx.x / cpg;
+    const bool has_group = grp < groups;
+    const int qt = has_group ? grp % QT : 0, rest = has_group ? grp / QT : 0;
+    const int kvh = rest % md.Hkv, bi = rest / md.Hkv;
+    const int c = (int)(blockIdx.x % cpg) + cpg * w;
+    ChunkTask ct;
+    ct.load(a, layer, bi, kvh, qt, c, has_group && c < ncc_max);       // before the barrier: cached K / V only
+    if (w == 0) grid_wait(a.bar, cs.epoch);
+    lds_barrier();
+    pstamp(a, cs);
+    if (has_group && w < 4) {                                            // shared query fragments
+        const int m = qt * 16 + (lane & 15);
+        const AttnGeom ag = attn_geom(a, layer, bi, kvh);
+        const bool mv = m < ag.M;
+        const int gi = mv ? m / ag.rps : 0, j = mv ? m - gi * ag.rps : 0;
+        QPiece qp;
+        qp.issue(a, ag, bi * ag.rps + j, kvh * md.G + gi, lane >> 4, w);
+        qp.finish(qlds, lane, w);
+    }
+    if (w == P_CW - 1 && (int)blockIdx.x < nseq * md.Hkv * rps) {        // the block's own rows
+        const int t = blockIdx.x, j = t % rps, r2 = t / rps;
+        attn_append(a, layer, r2 / md.Hkv, r2 % md.Hkv, j);
+    }
+    lds_barrier();
+    ct.run(a, qlds, a.apart + ((size_t)grp * ncc_max + c) * PERSIST_APART);
+    pstamp(a, cs);
+    wait_vm0();
+    lds_barrier();
+    ++cs.epoch;
+    if (w == 0) grid_arrive(a.bar, cs.epoch);
+    pstamp(a, cs);
+}
+
+__device__ __noinline__ void attention_merge(const PersistArgs& a, int layer, CState& cs, PShared& sm) {
+    const ModelDims& md = a.md;
+    const StepParams* sp = a.sp;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int nseq = sp->nseq, rps = sp->rps;
+    const int QT = (md.G * rps + 15) / 16;
+    if (w == 0) grid_wait(a.bar, cs.epoch);
+    lds_barrier();
+    pstamp(a, cs);
+    const int n_merge = nseq * md.Hkv * QT * A_HT, rounds = attn_merge_rounds(a);
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int task = blockIdx.x + rd * PERSIST_WGS;
+        const int ht = task & 7, qk = task >> 3;
+        const int qt = qk % QT, rest = qk / QT;
+        attn_merge(a, layer, rest / md.Hkv, rest % md.Hkv, qt, ht, task < n_merge, sm);
+    }
+    pstamp(a, cs);
+    wait_vm0();
+    lds_barrier();
+    ++cs.epoch;
+    if (w == 0) grid_arrive(a.bar, cs.epoch);
+    pstamp(a, cs);
+}
+
+// ---- stage 0: embedding rows -> residual, packed operand of the first QKV, sums of squares, rotary table ----
+__device__ __noinline__ void embed_stage(const PersistArgs& a) {
+    const ModelDims& md = a.md;
+    const StepParams* sp = a.sp;
+    const int R = sp->nseq * sp->rps, d = md.d, ntx = d / 16;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    if (w < 2) {
+        const bf16_t* gain = a.layers[0].attn_gain;
+        const int e = tid & 127, m = e >> 4, n = e & 15;
+        for (int tile = blockIdx.x; tile < ntx; tile += gridDim.x) {
+            const int col = tile * 16 + n;
+            const bool valid = m < R;
+            float v = 0.f;
+            if (valid) {
+                const int bi = m / sp->rps, j = m % sp->rps, b = sp->seq_base + bi;
+                int tok;
+                if (sp->tok_mode == 1) tok = sp->prefill_tokens[j];
+                else if (sp->tok_mode == 2) tok = sp->draft_tokens[bi * sp->rps + j];
+                else tok = (j == 0) ? a.kv.pending[b] : sp->draft_tokens[bi * sp->gamma + (j - 1)];
+                tok = min(max(tok, 0), md.V - 1);
+                v = bf16_to_f32(a.embed[(size_t)tok * d + col]);
+                st_coh(&a.x[(size_t)m * d + col], v);
+            }
+            pack8_store(bx_slot(a, 0), m, tile * 16 + (n & 8), v * bf16_to_f32(gain[col]), valid && (n & 7) == 0);
+            float ss = v * v;
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) ss += __shfl_xor(ss, o, 64);
+            if (valid && n == 0) st_coh(&ssq_slot(a, 0)[(size_t)m * ntx + tile], ss);
+        }
+    } else if (w == 2) {
+        for (int rr = blockIdx.x; rr < R; rr += gridDim.x) {
+            const int bi = rr / sp->rps, j = rr % sp->rps, b = sp->seq_base + bi;
+            const int pos = a.kv.len[b] + j, half = md.hd >> 1;
+            for (int i = lane; i < half; i += 64) {
+                const double inv_freq = exp(-2.0 * (double)i / (double)md.hd * a.log_base);
+                double s, c;
+                sincos((double)pos * inv_freq, &s, &c);
+                st_coh(&a.cs[((size_t)rr * half + i) * 2], (float)c);
+                st_coh(&a.cs[((size_t)rr * half + i) * 2 + 1], (float)s);
+            }
+        }
+    }
+}
+
+// ---- the phases of a layer as functions of their own: each gets a register allocation of its own -------------
+__device__ __noinline__ void phase_qkv(const PersistArgs& a, PShared& sm, CState& cs, int l) {
+    const Sched sc(a, sm.lay);
+    Frag bf[16];
+    EpiCtx ec{};
+    ec.R = a.sp->nseq * a.sp->rps;
+    ec.kslice = (int)(blockIdx.x % a.s_qkv.ksplit);
+    ec.ssq_in = ssq_slot(a, 2 * l);
+    ec.qkv_out = qkv_slot(a, l);
+    gemm_seg<3, 8, 1, PEPI_QKV, true, true>(a, sc.seg(4 * l + PH_QKV), bx_slot(a, 2 * l), ec, sm, cs, bf);
+}
+__device__ __noinline__ void phase_o(const PersistArgs& a, PShared& sm, CState& cs, int l) {
+    const Sched sc(a, sm.lay);
+    Frag bf[16];
+    EpiCtx ec{};
+    ec.R = a.sp->nseq * a.sp->rps;
+    ec.gain = sm.lay[l].ffn_gain;
+    ec.Bout = bx_slot(a, 2 * l + 1);
+    ec.ssq_out = ssq_slot(a, 2 * l + 1);
+    gemm_seg<1, 16, 1, PEPI_RESID, false, true>(a, sc.seg(4 * l + PH_O), battn_slot(a, l), ec, sm, cs, bf);
+}
+__device__ __noinline__ void phase_gu(const PersistArgs& a, PShared& sm, CState& cs, int l) {
+    const Sched sc(a, sm.lay);
+    Frag bf[16];
+    EpiCtx ec{};
+    ec.R = a.sp->nseq * a.sp->rps;
+    ec.ssq_in = ssq_slot(a, 2 * l + 1);
+    ec.Bout = bact_slot(a, l);
+    gemm_seg<7, 16, 1, PEPI_SWIGLU, true, true>(a, sc.seg(4 * l + PH_GU), bx_slot(a, 2 * l + 1), ec, sm, cs, bf);
+}
+__device__ __noinline__ void phase_down(const PersistArgs& a, PShared& sm, CState& cs, int l) {
+    const Sched sc(a, sm.lay);
+    Frag bf[16];
+    const bool last = (l + 1 == a.NL);
+    EpiCtx ec{};
+    ec.R = a.sp->nseq * a.sp->rps;
+    ec.gain = last ? a.final_gain : sm.lay[l + 1].attn_gain;
+    ec.last_layer = last;
+    ec.Bout = bx_slot(a, 2 * l + 2);
+    ec.ssq_out = ssq_slot(a, 2 * l + 2);
+    gemm_seg<1, 14, 4, PEPI_RESID, false, true>(a, sc.seg(4 * l + PH_DOWN), bact_slot(a, l), ec, sm, cs, bf);
+}
+__device__ __noinline__ void phase_lm(const PersistArgs& a, PShared& sm, CState& cs) {
+    const Sched sc(a, sm.lay);
+    Frag bf[16];
+    EpiCtx ec{};
+    ec.R = a.sp->nseq * a.sp->rps;
+    ec.ssq_in = ssq_slot(a, 2 * a.NL);
+    for (int i = 0; i < sc.nlm; ++i)
+        gemm_seg<8, 16, 1, PEPI_LOGITS, true, false>(a, sc.seg(sc.nlayerseg + i), bx_slot(a, 2 * a.NL), ec, sm, cs, bf);
+}
+
+// ---- the kernel -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(P_THREADS) void persist_forward_kernel(PersistArgs a) {
+    extern __shared__ __align__(1024) unsigned char smem_raw[];
+    PShared& sm = *reinterpret_cast<PShared*>(smem_raw);
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    for (int i = threadIdx.x; i < a.NL; i += P_THREADS) sm.lay[i] = a.layers[i];
+    if (threadIdx.x == 0) sm.args = a;
+    __syncthreads();
+    if (w >= P_CW) { loader_main(a, sm, w - P_CW); return; }
+
+    const PersistArgs& A = sm.args;
+    CState cs{a.epoch0, 0, 0};
+    pstamp(A, cs);
+    embed_stage(A);
+    wait_vm0();
+    lds_barrier();
+    ++cs.epoch;
+    if (w == 0) grid_arrive(a.bar, cs.epoch);
+    for (int l = 0; l < a.NL; ++l) {
+        phase_qkv(A, sm, cs, l);
+        attention_chunks(A, l, cs, sm);
+        attention_merge(A, l, cs, sm);
+        phase_o(A, sm, cs, l);
+        phase_gu(A, sm, cs, l);
+        phase_down(A, sm, cs, l);
+    }
+    phase_lm(A, sm, cs);
+}
+
+// ---- host ---------------------------------------------------------------------------------------------
+bool persist_plan(const ModelDims& md, int n_layers, PersistArgs* a) {
+    if (n_layers < 1 || n_layers > P_MAXL || md.hd != 128) return false;
+    const int Nq = md.Hq * md.hd, Nqkv = (md.Hq + 2 * md.Hkv) * md.hd;
+    // the splits the kernel is instantiated for: QKV 3 tiles x 2 K-slices x 8 k-steps per wave, O 1 x 1 x 16,
+    // gate/up 7 x 1 x 16, down 1 x 1 x 56, LM head 8 tiles x 16 k-steps per item
+    if (md.d / 32 != 128 || Nq / 32 != 128) return false;
+    if (Nqkv / 16 != 3 * PERSIST_WGS / 2) return false;
+    if (md.d / 16 != PERSIST_WGS) return false;
+    if (2 * md.F / 16 != 7 * PERSIST_WGS || md.F / 32 != 56 * P_CW) return false;
+    if (md.V / 16 < PERSIST_WGS) return false;
+    if (a) {
+        a->s_qkv = PersistSplit{3, 2, 8};
+        a->s_o = PersistSplit{1, 1, 16};
+        a->s_gu = PersistSplit{7, 1, 16};
+        a->s_d = PersistSplit{1, 1, 56};
+    }
+    return true;
+}
+
+size_t persist_lds_bytes() { return sizeof(PShared) + 1024; }
+
+hipError_t persist_launch(const PersistArgs& a, hipStream_t st) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)persist_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)persist_lds_bytes());
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    PersistArgs args = a;
+    void* params[] = {&args};
+    return hipLaunchCooperativeKernel((const void*)persist_forward_kernel, dim3(PERSIST_WGS), dim3(P_THREADS), params,
+                                      persist_lds_bytes(), st);
+}
+
+}  // namespace sj
