@@ -14,8 +14,8 @@
 //   * a matrix is split so that every CU owns `nt` n-tiles and a K-slice; the 8 compute waves split that slice again
 //     and keep their share of the activation operand in registers (loaded once per phase), so the operand is not
 //     streamed at all; their partial tiles meet in LDS (wave order: deterministic) and 512 threads run the epilogue;
-//   * phases are separated by a flag barrier across the 256 workgroups (every workgroup publishes an epoch, workgroup
-//     0 collects them and releases one word).  Data crossing it is written with write-through stores and read after
+//   * phases are separated by a flag barrier across the 256 workgroups (every workgroup publishes an epoch in a few
+//     replicas of a dense flag array and polls one replica whole).  Data crossing it is written with write-through stores and read after
 //     an agent-scope acquire;
 //   * with R <= 8 the 16 operand rows of an MFMA carry BOTH bf16 planes of the fp32 activation (row r: hi, row
 //     r + 8: lo); the two halves of the product are added in the epilogue: one MFMA per weight fragment;
@@ -55,27 +55,28 @@ __device__ __forceinline__ bool aborted(const PersistBar* bar) { return ld_coh(&
 
 // one wave; every store of the workgroup that the others must see has completed (vmcnt(0) + workgroup barrier)
 __device__ __forceinline__ void grid_arrive(PersistBar* bar, unsigned epoch) {
-    if ((threadIdx.x & 63) == 0) st_coh(&bar->flag[blockIdx.x * 32], epoch);
+    const int lane = threadIdx.x & 63;
+#ifdef P_RELEASE_FENCE
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+#endif
+#ifdef P_ARRIVE_DELAY
+    { const unsigned long long t0 = wall_clock64(); while (wall_clock64() - t0 < P_ARRIVE_DELAY) __builtin_amdgcn_s_sleep(4); }
+#endif
+    if (lane < PERSIST_REPL) st_coh(&bar->rep[lane].flag[blockIdx.x], epoch);
 }
+// one wave: polls the 256 flags of this workgroup's replica (four per lane) until all have reached the epoch
 __device__ __forceinline__ void grid_wait(PersistBar* bar, unsigned epoch) {
     const int lane = threadIdx.x & 63;
-    if (blockIdx.x == 0) {
-        int ok = 1;
-        for (unsigned w = lane; w < gridDim.x; w += 64) {
-            unsigned spins = 0;
-            while ((int)(ld_coh(&bar->flag[w * 32]) - epoch) < 0) {
-                if (++spins > P_SPIN_LIMIT || aborted(bar)) { ok = 0; break; }
-            }
-        }
-        ok = __all(ok);
-        if (lane == 0) { if (!ok) st_coh(&bar->abort, 1u); st_coh(&bar->go, epoch); }
-    }
-    if (lane == 0) {
-        unsigned spins = 0;
-        while ((int)(ld_coh(&bar->go) - epoch) < 0) {
-            __builtin_amdgcn_s_sleep(1);
-            if (++spins > P_SPIN_LIMIT || aborted(bar)) { st_coh(&bar->abort, 1u); break; }
-        }
+    const unsigned long long* f = reinterpret_cast<const unsigned long long*>(&bar->rep[blockIdx.x % PERSIST_REPL].flag[4 * lane]);
+    unsigned spins = 0;
+    for (;;) {
+        const unsigned long long a = __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long b = __hip_atomic_load(f + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool ok = (int)((unsigned)a - epoch) >= 0 && (int)((unsigned)(a >> 32) - epoch) >= 0 &&
+                        (int)((unsigned)b - epoch) >= 0 && (int)((unsigned)(b >> 32) - epoch) >= 0;
+        if (__all(ok)) break;
+        if (++spins > P_SPIN_LIMIT || aborted(bar)) { if (lane == 0) st_coh(&bar->abort, 1u); break; }
+        __builtin_amdgcn_s_sleep(2);
     }
 }
 

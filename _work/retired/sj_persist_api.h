@@ -8,12 +8,17 @@ namespace sj {
 constexpr int PERSIST_MAXR = 8;          // query rows of the whole batch: both bf16 planes share one MFMA operand tile
 constexpr int PERSIST_WGS = 256;         // one workgroup per compute unit; the work split below assumes exactly this many
 
-// device-wide barrier state: one flag per workgroup (128 bytes apart), one release word
+// Device-wide barrier state.  Every workgroup publishes its epoch in PERSIST_REPL replicas of a dense flag array
+// (1 KB per replica, replicas far apart in memory) and polls the whole of ONE replica with a single 1 KB read: one
+// memory round trip from the last arrival to the release, and the 256 pollers are spread over the replicas.
+constexpr int PERSIST_REPL = 8;
 struct PersistBar {
-    unsigned go;
     unsigned abort;                      // set when a bounded wait ran out: every later wait falls through
-    unsigned pad[30];
-    unsigned flag[PERSIST_WGS * 32];
+    unsigned pad[63];
+    struct Replica {
+        unsigned flag[PERSIST_WGS];
+        unsigned pad[4096 - PERSIST_WGS];
+    } rep[PERSIST_REPL];
 };
 
 struct PersistLayer {

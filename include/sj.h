@@ -233,9 +233,9 @@ int sj_kv_rewind(sj_kv* kv, const int32_t* len_host, const int32_t* pending_host
 
 /* Measurement aid.  kernel_class != 0 makes the following sj_verify_step calls bracket every launch
  * of that class with HIP events on the step's stream: 1 = QKV projection, 2 = O projection,
- * 3 = gate/up projection + SwiGLU, 4 = down projection (these use the multi-kernel path).  9 = let the
- * persistent kernel record stage timestamps (read with SJ_DBG_STAGE_TIMES).  sj_get_kernel_timing synchronises, returns
- * the summed duration and launch count since the last call, and clears them.  0 switches it off. */
+ * 3 = gate/up projection + SwiGLU, 4 = down projection (timed steps are launched kernel by kernel, not as
+ * a captured graph).  sj_get_kernel_timing synchronises, returns the summed duration and launch count since the
+ * last call, and clears them.  0 switches it off. */
 int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class);
 /* Launches the projection kernel of class 1..4 `launches` times back to back on `stream`, cycling through
  * the layers' weights (so nothing is re-read from cache) with the operands left by the last step, and
@@ -262,9 +262,6 @@ int sj_set_operand_planes(sj_kv* kv, int32_t planes);
 #define SJ_DBG_JUDGE_SCORES 2
 #define SJ_DBG_P_AT_DRAFT   3
 #define SJ_DBG_ACCEPT_BITS  4
-#define SJ_DBG_STAGE_TIMES  5   /* float [11]: mean microseconds per layer of QKV, barrier, attention, barrier, O,
-                                  barrier, gate/up, barrier, down, barrier, then the LM head; needs
-                                  sj_set_kernel_timing(kv, 9) and a step served by the persistent kernel */
 int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, size_t nbytes);
 
 /* Bytes of weights one step streams from HBM (all projections + LM head), for roofline math. */

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 SJ_OK, SJ_EINVAL, SJ_ECAPACITY, SJ_EHIP, SJ_ENOMEM, SJ_ECALLBACK = 0, -1, -2, -3, -4, -5
 SJ_MODE_TWO_STAGE, SJ_MODE_ALIGNMENT, SJ_MODE_JUDGE, SJ_MODE_TOPK = 0, 1, 2, 3
-SJ_DBG_LOGITS, SJ_DBG_HIDDEN, SJ_DBG_JUDGE_SCORES, SJ_DBG_P_AT_DRAFT, SJ_DBG_ACCEPT_BITS, SJ_DBG_STAGE_TIMES = 0, 1, 2, 3, 4, 5
+SJ_DBG_LOGITS, SJ_DBG_HIDDEN, SJ_DBG_JUDGE_SCORES, SJ_DBG_P_AT_DRAFT, SJ_DBG_ACCEPT_BITS = 0, 1, 2, 3, 4
 
 TENSOR_IDS = {"embed": 0, "attn_norm": 1, "wq": 2, "wk": 3, "wv": 4, "wo": 5, "ffn_norm": 6,
               "w_gate": 7, "w_up": 8, "w_down": 9, "final_norm": 10, "lm_head": 11,

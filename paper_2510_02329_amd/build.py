@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libsj.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
-SOURCES = [os.path.join(HERE, "csrc", n) for n in ("sj_lib.hip", "sj_persist.hip", "sj_train.hip")]
+SOURCES = [os.path.join(HERE, "csrc", n) for n in ("sj_lib.hip", "sj_train.hip")]
 
 FLAGS = [*os.environ.get("SJ_BUILD_DEFS", "").split(),
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -4,7 +4,6 @@
 #include "sj_kernels.h"
 #include "sj_attn.h"
 #include "sj_gemm_rows.h"
-#include "sj_persist_api.h"
 
 #include <algorithm>
 #include <cmath>
@@ -61,8 +60,6 @@ struct sj_model {
     std::vector<void*> allocs;
     int64_t weight_bytes = 0;
     int device = 0;
-    PersistLayer* persist_layers = nullptr;   // device table for the persistent forward kernel (bf16 only)
-    bool persist_ok = false;                  // shape served by the persistent kernel, 256 CUs, cooperative launch
 };
 
 // Up to two row tiles (32 rows) the few-row kernel (every wave fetches its own operand fragments) is the faster
@@ -112,14 +109,6 @@ struct sj_kv {
     std::map<int, hipGraphExec_t> graphs;
     hipStream_t cap_stream = nullptr;
     bool use_graph = true;
-    // persistent forward kernel (at most 8 query rows): SJ_PERSIST=1 selects it, SJ_PERSIST=0 the multi-kernel path
-    bool use_persist = false;
-    bf16_t *Bx = nullptr, *Battn = nullptr, *Bact = nullptr, *knew = nullptr, *vnewT = nullptr;
-    float *ssq = nullptr, *apart = nullptr, *pqkv = nullptr;
-    PersistBar* bar = nullptr;
-    unsigned persist_epoch = 0;
-    int p_chunk_keys = 32, p_nch_max = 1;
-    unsigned long long* prof = nullptr;   // phase timestamps of the persistent kernel (SJ_PERSIST_PROF=1)
     int timing_class = 0;
     std::vector<hipEvent_t> tev;          // start/stop pairs
     size_t tev_used = 0;
@@ -275,20 +264,6 @@ extern "C" int sj_model_load(const sj_config* cfg, sj_tensor_fn provider, void* 
     if ((rc = ld.tiled(&lm_id, &lm_n, 1, -1, d, 0, &m->lm_head))) return cleanup(rc);
     if ((rc = ld.plain(SJ_T_JUDGE_W, -1, d, &m->judge_w))) return cleanup(rc);
     if ((rc = ld.plain(SJ_T_JUDGE_B, -1, 1, &m->judge_b))) return cleanup(rc);
-    if (cfg->dtype == SJ_DTYPE_BF16 && cfg->n_layers > 0 && persist_plan(md, cfg->n_layers, nullptr)) {
-        std::vector<PersistLayer> tab(cfg->n_layers);
-        for (int l = 0; l < cfg->n_layers; ++l) {
-            const LayerW& L = m->layers[l];
-            tab[l] = PersistLayer{(const u32x4*)L.wqkv, (const u32x4*)L.wo, (const u32x4*)L.wgu, (const u32x4*)L.wd,
-                                  (const bf16_t*)L.attn_norm, (const bf16_t*)L.ffn_norm};
-        }
-        if ((rc = dev_alloc(m->allocs, &m->persist_layers, sizeof(PersistLayer) * tab.size(), false))) return cleanup(rc);
-        if (hipMemcpy(m->persist_layers, tab.data(), sizeof(PersistLayer) * tab.size(), hipMemcpyHostToDevice) != hipSuccess)
-            return cleanup(fail(SJ_EHIP, "hipMemcpy of the layer table failed"));
-        hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, m->device) == hipSuccess)
-            m->persist_ok = prop.multiProcessorCount == PERSIST_WGS && prop.cooperativeLaunch != 0;
-    }
     cleanup(0);
     *out = m;
     return SJ_OK;
@@ -343,7 +318,6 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     kv->m = m;
     kv->batch = batch;
     if (const char* e = std::getenv("SJ_NO_GRAPH")) kv->use_graph = !(e[0] == '1');
-    if (const char* e = std::getenv("SJ_PERSIST")) kv->use_persist = !(e[0] == '0');
     kv->cap.assign(batch, 64);
     kv->len_upper.assign(batch, 0);
     kv->seq_off.assign(batch, 0);
@@ -435,29 +409,6 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
         ALLOC(kv->act, (size_t)3 * kv->rpad * F * m->esz);
         ALLOC(kv->cs, (size_t)R * hd * 4);
         ALLOC(kv->prefill_tok, (size_t)R * 4);
-        if (m->persist_ok && batch <= PERSIST_MAXR) {
-            // write-once slots of the persistent kernel (one per layer and producer): packed operands are K/32
-            // fragments of 1 KB
-            const size_t NLs = (size_t)c.n_layers;
-            ALLOC(kv->Bx, (2 * NLs + 1) * d * 32);
-            ALLOC(kv->Battn, NLs * Nq * 32);
-            ALLOC(kv->Bact, NLs * F * 32);
-            ALLOC(kv->ssq, (2 * NLs + 1) * PERSIST_MAXR * (d / 16) * 4);
-            ALLOC(kv->pqkv, NLs * 2 * PERSIST_MAXR * (Nq + 2 * Nk) * 4);
-            ALLOC(kv->knew, NLs * batch * c.n_kv_heads * PERSIST_MAXR * hd * 2);
-            ALLOC(kv->vnewT, NLs * batch * c.n_kv_heads * PERSIST_MAXR * hd * 2);
-            ALLOC(kv->bar, sizeof(PersistBar));
-            // attention chunks of the persistent kernel: 32 keys each, more while the 8 waves of the workgroups that
-            // serve one (sequence, kv head, query tile) would not cover the longest context in one pass
-            const int qt = (G * std::min(PERSIST_MAXR, c.max_gamma + 1) + 15) / 16;
-            const int cpg = std::max(1, PERSIST_WGS / (batch * c.n_kv_heads * qt));
-            int ck = 32;
-            while (ck < (1 << 22) && (cap_max + ck - 1) / ck > 8 * cpg) ck *= 2;
-            kv->p_chunk_keys = ck;
-            kv->p_nch_max = (cap_max + ck - 1) / ck + 1;
-            ALLOC(kv->apart, (size_t)batch * c.n_kv_heads * qt * kv->p_nch_max * PERSIST_APART * 4);
-            if (const char* e = std::getenv("SJ_PERSIST_PROF")) { if (e[0] == '1') { ALLOC(kv->prof, sizeof(unsigned long long) * 8192); } }
-        }
     }
 #undef ALLOC
     if (hipMemcpy(kv->seq_off_dev, kv->seq_off.data(), sizeof(int64_t) * batch, hipMemcpyHostToDevice) != hipSuccess ||
@@ -1125,57 +1076,10 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
 // The full step is ~200 dependent launches of a few microseconds each: it is captured once per
 // (gamma, planes) into a launch graph and replayed; only the per-call parameter block, written by a
 // tiny kernel in front of the replay, changes between calls.
-// The persistent forward kernel serves bf16 models of the shapes it is instantiated for when the whole batch fits
-// 8 query rows and the default two operand planes are in use.
-static bool persist_eligible(const sj_model* m, const sj_kv* kv, int rows, int spl) {
-    return kv->use_persist && m->persist_ok && kv->bar && spl == 2 && rows <= PERSIST_MAXR && kv->timing_class == 0;
-}
-
-static int launch_persist(const sj_model* m, sj_kv* kv, hipStream_t st) {
-    PersistArgs a{};
-    if (!persist_plan(m->md, m->cfg.n_layers, &a)) return fail(SJ_EINVAL, "internal: persistent kernel does not serve this shape");
-    a.layers = m->persist_layers;
-    a.lm_head = (const u32x4*)m->lm_head;
-    a.final_gain = (const bf16_t*)m->final_norm;
-    a.embed = (const bf16_t*)m->embed;
-    a.NL = m->cfg.n_layers;
-    a.md = m->md;
-    a.sp = kv->sp_dev;
-    a.kv.K = (bf16_t*)kv->K; a.kv.V = (bf16_t*)kv->V; a.kv.seq_off = kv->seq_off_dev; a.kv.cap = kv->cap_dev;
-    a.kv.len = kv->len_dev; a.kv.pending = kv->pending_dev; a.kv.layer_stride = kv->layer_stride;
-    a.x = kv->x; a.qkv = kv->pqkv; a.knew = kv->knew; a.vnewT = kv->vnewT; a.Bx = kv->Bx; a.Battn = kv->Battn; a.Bact = kv->Bact; a.ssq = kv->ssq;
-    a.hn32 = kv->hn32; a.logits = kv->logits; a.stats = kv->stats; a.cs = kv->cs; a.apart = kv->apart;
-    a.chunk_keys = kv->p_chunk_keys; a.nch_max = kv->p_nch_max;
-    a.bar = kv->bar;
-    a.log_base = std::log((double)m->cfg.rope_base);
-    a.prof = kv->prof;
-    if (kv->persist_epoch > 0xF0000000u) {                    // epochs are monotonic: restart well before wrap-around
-        HIPCHK(hipStreamSynchronize(st));
-        HIPCHK(hipMemset(kv->bar, 0, sizeof(PersistBar)));
-        kv->persist_epoch = 0;
-    }
-    a.epoch0 = kv->persist_epoch;
-    if (kv->persist_epoch == 0) {
-        const char* e = std::getenv("SJ_TUNE_LOG");
-        if (e && e[0] == '1') fprintf(stderr, "[sj] forward served by the persistent kernel (%d key(s) per attention task)\n", kv->p_chunk_keys);
-    }
-    HIPCHK(persist_launch(a, st));
-    kv->persist_epoch += persist_barriers(m->cfg.n_layers);
-    return SJ_OK;
-}
-
 template <typename T, int SPL>
 static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams& p, hipStream_t st, bool head_only,
                             const void* hidden) {
     int rc;
-    if (!head_only && persist_eligible(m, kv, kv->batch * (gamma + 1), SPL)) {
-        if ((rc = set_params(kv, st, p))) return rc;
-        if ((rc = launch_persist(m, kv, st))) return rc;
-        Runner<T, SPL> run{m, kv, st, kv->batch, gamma + 1, kv->batch * (gamma + 1)};
-        softmax_merge_kernel<<<run.R, 256, 0, st>>>(kv->stats, m->md.V / 16, m->md.inv_temp, kv->rowstat);
-        LAUNCHCHK("softmax_merge");
-        return run.tail(gamma);
-    }
     const bool graph = kv->use_graph && !head_only && kv->timing_class == 0;
     if (!graph) {
         if ((rc = set_params(kv, st, p))) return rc;
@@ -1468,17 +1372,6 @@ extern "C" int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, siz
         case SJ_DBG_JUDGE_SCORES: src = kv->scores; want = (size_t)kv->batch * gamma * 4; break;
         case SJ_DBG_P_AT_DRAFT: src = kv->p_at_d; want = (size_t)kv->batch * gamma * 4; break;
         case SJ_DBG_ACCEPT_BITS: src = kv->bits; want = (size_t)kv->batch * gamma * 4; break;
-        case SJ_DBG_STAGE_TIMES: {
-            // diagnostic: microseconds since the first stamp of the persistent kernel's phase stamps (workgroup 0)
-            if (!kv->prof) return fail(SJ_EINVAL, "stage times need SJ_PERSIST_PROF=1 when the cache object is created");
-            const size_t n = nbytes / sizeof(float);
-            if (n < 1 || n > 8192) return fail(SJ_EINVAL, "nbytes must cover 1..8192 floats");
-            std::vector<unsigned long long> t(n);
-            HIPCHK(hipDeviceSynchronize());
-            HIPCHK(hipMemcpy(t.data(), kv->prof, sizeof(unsigned long long) * n, hipMemcpyDeviceToHost));
-            for (size_t i = 0; i < n; ++i) ((float*)dst_host)[i] = (float)((double)(t[i] - t[0]) * 0.01);
-            return SJ_OK;
-        }
         default: return fail(SJ_EINVAL, "unknown debug item %d", what);
     }
     if (want == 0) return fail(SJ_EINVAL, "item not produced by the last call");

@@ -169,37 +169,3 @@ def test_llama8b_batch1_full_size():
         assert np.array_equal(out_k["logits"], out["logits"])               # the mode does not touch the forward
     finally:
         gpu.close()
-
-
-# The persistent whole-forward kernel serves the 8B layer shape with at most 8 query rows: compared against the
-# oracle AND against the library's own multi-kernel path (SJ_PERSIST=0), over two chained steps.
-PERSIST = synth.ModelShape("persist_bf16", "bf16", 2, 4096, 32, 8, 128, 14336, 4096 + 2048, 500000.0, weight_std=0.02)
-
-
-@pytest.mark.parametrize("batch,gamma,lens", [(1, 5, [200]), (1, 7, [1024]), (2, 3, [77, 513]), (1, 1, [0])])
-def test_persistent_kernel_matches_oracle_and_multikernel_path(batch, gamma, lens, monkeypatch):
-    shape = PERSIST.scaled(batch=batch, gamma=gamma)
-    src = synth.WeightSource(shape, seed=3, norm_jitter=0.1, judge_bias=0.2)
-    cap = [l + 64 for l in lens]
-    cfg = helpers.oracle_config(shape)
-    W = helpers.oracle_weights(src, cache_items=0)
-    outs = {}
-    for mode in ("persist", "multi"):
-        monkeypatch.setenv("SJ_PERSIST", "1" if mode == "persist" else "0")
-        gpu = G.Gpu(shape, src, cap)
-        try:
-            caches = _fill_caches(shape, gpu, cfg, lens, seed=4, capacity=cap)
-            for step in range(2):
-                draft = synth.make_draft(shape, seed=30 + step)
-                print(mode, "step", step, flush=True)
-                out, ref, stats = _compare_step(shape, gpu, cfg, W, caches, draft, 0.5, f"{mode} step {step}")
-                outs[(mode, step)] = out
-                for b, c in enumerate(caches):
-                    c.length = c.length - 1 - ref[b]["accepted_len"] + 1 + int(out["accepted_len"][b])
-                    c.pending = int(out["next_token"][b])
-        finally:
-            gpu.close()
-    for step in range(2):
-        a, b = outs[("persist", step)], outs[("multi", step)]
-        assert np.abs(a["logits"] - b["logits"]).max() < 5e-3
-        assert (a["accepted_len"] == b["accepted_len"]).all() and (a["next_token"] == b["next_token"]).all()
