@@ -183,6 +183,21 @@ int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void* hidden,
                    const int32_t* draft_tokens, const float* draft_probs, const float* uniforms,
                    float judge_threshold, int32_t* accepted_len, int32_t* next_token, void* stream);
 
+/* sj_verify_head for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same inputs, outputs and arithmetic as sj_verify_head in the default
+ * two-stage mode, but no sj_kv: the workspace is a static device array of SJ_STATIC_WORKSPACE_BYTES that every
+ * GPU the library runs on holds until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine) and launches its kernels on `stream`; outputs are valid once the stream is
+ * synchronised.  Limits: batch * (gamma + 1) <= SJ_STATIC_MAX_ROWS, and the rows' logits, softmax partials and
+ * resampling sums must fit the array (16 rows of a 128256-entry vocabulary at d_model 4096 do); anything larger
+ * is refused with SJ_EINVAL before any launch.  All calls on one GPU share the array, which keeps the previous
+ * call's contents: calls that overlap on one GPU (different streams or threads) race - serialise them. */
+#define SJ_STATIC_MAX_ROWS 32
+#define SJ_STATIC_WORKSPACE_BYTES (16u << 20)
+int sj_verify_head_static(sj_model* m, int32_t batch, int32_t gamma, const void* hidden,
+                          const int32_t* draft_tokens, const float* draft_probs, const float* uniforms,
+                          float judge_threshold, int32_t* accepted_len, int32_t* next_token, void* stream);
+
 /* Training of the judge verifier (Sec. 3.4 "Verifier Training", appendix "Training Logistic Regressor"):
  * for every C of the grid, the L2-regularised logistic regression
  *     min over (w, b) of  1/2 |w|^2 + C * sum_i log(1 + exp(-(2 y_i - 1) (w . h_i + b)))      (bias unpenalised)

@@ -69,6 +69,7 @@ def load_library() -> C.CDLL:
         "sj_prefill": (C.c_int, [vp, vp, i32, C.POINTER(i32), i32, vp]),
         "sj_verify_step": (C.c_int, [vp, vp, i32, vp, vp, vp, f32, vp, vp, vp]),
         "sj_verify_head": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, f32, vp, vp, vp]),
+        "sj_verify_head_static": (C.c_int, [vp, i32, i32, vp, vp, vp, vp, f32, vp, vp, vp]),
         "sj_draft_block": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, vp]),
         "sj_score_block": (C.c_int, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
         "sj_judge_train": (C.c_int, [vp, vp, C.c_int64, vp, vp, C.c_int64, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]),
@@ -207,6 +208,13 @@ def sj_verify_head(model: int, kv: int, gamma: int, hidden, draft_tokens, draft_
     _check(load_library().sj_verify_head(model, kv, gamma, _ptr(hidden), _ptr(draft_tokens), _ptr(draft_probs),
                                          _ptr(uniforms), float(judge_threshold), _ptr(accepted_len), _ptr(next_token),
                                          _stream(stream)))
+
+
+def sj_verify_head_static(model: int, batch: int, gamma: int, hidden, draft_tokens, draft_probs, uniforms,
+                          judge_threshold: float, accepted_len, next_token, stream=None) -> None:
+    _check(load_library().sj_verify_head_static(model, int(batch), int(gamma), _ptr(hidden), _ptr(draft_tokens),
+                                                _ptr(draft_probs), _ptr(uniforms), float(judge_threshold),
+                                                _ptr(accepted_len), _ptr(next_token), _stream(stream)))
 
 
 def sj_draft_block(model: int, kv: int, gamma: int, uniforms, feed_last: bool, draft_tokens, draft_probs, stream=None) -> None:

@@ -12,6 +12,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -1314,6 +1315,97 @@ extern "C" int sj_verify_head(sj_model* m, sj_kv* kv, int32_t gamma, const void*
     kv->last_gamma = gamma;
     kv->last_rows = kv->batch * (gamma + 1);
     return SJ_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// sj_verify_head for callers that cannot allocate: the workspace lives in a static device array.
+
+constexpr size_t SJ_STATIC_BYTES = SJ_STATIC_WORKSPACE_BYTES;  // per GPU, held until the process ends
+static __device__ __align__(256) unsigned char scratch[SJ_STATIC_BYTES];
+
+// The array's device address: looked up once per device with that device current (every GPU holds its own copy).
+static int static_scratch_base(unsigned char** out) {
+    constexpr int MAXDEV = 64;
+    static unsigned char* base[MAXDEV] = {};
+    static std::mutex mu;
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAXDEV) return fail(SJ_EINVAL, "device index %d not supported by the static workspace", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!base[dev]) {
+        void* p = nullptr;
+        HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(SJ_EHIP, "hipGetSymbolAddress returned a null address");
+        base[dev] = (unsigned char*)p;
+    }
+    *out = base[dev];
+    return SJ_OK;
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = v;
+}
+
+extern "C" int sj_verify_head_static(sj_model* m, int32_t batch, int32_t gamma, const void* hidden, const int32_t* draft_tokens,
+                                     const float* draft_probs, const float* uniforms, float judge_threshold,
+                                     int32_t* accepted_len, int32_t* next_token, void* stream) {
+    if (!m) return fail(SJ_EINVAL, "model is null");
+    if (batch < 1) return fail(SJ_EINVAL, "batch must be positive");
+    if (gamma < 1 || gamma > m->cfg.max_gamma) return fail(SJ_EINVAL, "gamma %d outside 1..%d", gamma, m->cfg.max_gamma);
+    if (!hidden || !draft_tokens || !draft_probs || !uniforms || !accepted_len || !next_token)
+        return fail(SJ_EINVAL, "null device pointer argument");
+    if (!(judge_threshold == judge_threshold)) return fail(SJ_EINVAL, "judge_threshold is NaN");
+    const int64_t R = (int64_t)batch * (gamma + 1);
+    const int d = m->cfg.d_model, V = m->cfg.vocab;
+    if (R > SJ_STATIC_MAX_ROWS) return fail(SJ_EINVAL, "batch * (gamma + 1) = %lld rows exceed the static workspace's %d", (long long)R, SJ_STATIC_MAX_ROWS);
+    unsigned char* base = nullptr;
+    int rc = static_scratch_base(&base);
+    if (rc) return rc;
+    // carve the workspace (256-byte aligned pieces); a shape that does not fit is refused
+    sj_kv kv;
+    kv.m = m;
+    kv.batch = batch;
+    kv.max_rows = (int)R;
+    kv.rpad = ((int)R + 15) / 16 * 16;
+    kv.use_graph = false;
+    kv.nslab = std::max(1, (V / 16 + 255) / 256) * 256;
+    kv.slab_len = (V + kv.nslab - 1) / kv.nslab;
+    size_t off = 0;
+    bool fits = true;
+    auto take = [&](size_t bytes) -> void* {
+        const size_t at = off;
+        off = (off + bytes + 255) / 256 * 256;
+        if (off > SJ_STATIC_BYTES) { fits = false; return (void*)base; }
+        return (void*)(base + at);
+    };
+    kv.sp_dev = (StepParams*)take(sizeof(StepParams));
+    kv.len_dev = (int32_t*)take(sizeof(int32_t) * 2 * batch);
+    kv.pending_dev = kv.len_dev + batch;
+    kv.xn = take((size_t)kv.rpad * d * m->esz);                // hidden states are in the storage type: one plane
+    kv.hn32 = (float*)take((size_t)R * d * 4);
+    kv.logits = (float*)take((size_t)R * V * 4);
+    kv.stats = (float4*)take((size_t)R * (V / 16) * sizeof(float4));
+    kv.rowstat = (float4*)take((size_t)R * sizeof(float4));
+    kv.scores = (float*)take((size_t)R * 4);
+    kv.ranks = (int32_t*)take((size_t)R * 4);
+    kv.p_at_d = (float*)take((size_t)R * 4);
+    kv.bits = (int32_t*)take((size_t)R * 4);
+    kv.nacc = (int32_t*)take((size_t)batch * 4);
+    kv.epart = (double*)take((size_t)batch * kv.nslab * 8);
+    kv.wpart = (double*)take((size_t)batch * kv.nslab * 8);
+    if (!fits)
+        return fail(SJ_EINVAL, "%lld rows of vocabulary %d, width %d need more than the %zu bytes of the static workspace", (long long)R, V, d,
+                    SJ_STATIC_BYTES);
+    hipStream_t st = (hipStream_t)stream;
+    // the resampling step adds to a length word: it starts at zero on every call (the array keeps the last call's contents)
+    fill_i32_kernel<<<1, 256, 0, st>>>(kv.len_dev, 2 * batch, 0);
+    LAUNCHCHK("fill_i32");
+    StepParams p{};
+    p.nseq = batch; p.seq_base = 0; p.rps = gamma + 1; p.gamma = gamma; p.tok_mode = 0; p.mode = SJ_MODE_TWO_STAGE; p.topk = 2;
+    p.theta = judge_threshold;
+    p.draft_tokens = draft_tokens; p.draft_probs = draft_probs; p.uniforms = uniforms;
+    p.accepted_len = accepted_len; p.next_token = next_token;
+    return dispatch_step(m, &kv, gamma, p, st, true, hidden);
 }
 
 template <typename T, int SPL>
