@@ -279,6 +279,11 @@ int sj_set_operand_planes(sj_kv* kv, int32_t planes);
 #define SJ_DBG_ACCEPT_BITS  4
 int sj_debug_fetch(const sj_kv* kv, int32_t what, void* dst_host, size_t nbytes);
 
+/* Temperature T of the target distribution p = softmax(l / T) of Eq. 2 (0 = one-hot at the lowest-index arg-max, the
+ * setting of the paper's experiments, Sec. 4.1), replacing sj_config.temperature from the next call on for every cache
+ * object of the model.  Synchronises the device.  Errors: SJ_EINVAL (null, negative or NaN). */
+int sj_set_temperature(sj_model* m, float temperature);
+
 /* Bytes of weights one step streams from HBM (all projections + LM head), for roofline math. */
 int64_t sj_model_weight_bytes(const sj_model* m);
 

@@ -69,6 +69,7 @@ def load_library() -> C.CDLL:
         "sj_prefill": (C.c_int, [vp, vp, i32, C.POINTER(i32), i32, vp]),
         "sj_verify_step": (C.c_int, [vp, vp, i32, vp, vp, vp, f32, vp, vp, vp]),
         "sj_verify_head": (C.c_int, [vp, vp, i32, vp, vp, vp, vp, f32, vp, vp, vp]),
+        "sj_set_temperature": (C.c_int, [vp, f32]),
         "sj_verify_head_static": (C.c_int, [vp, i32, i32, vp, vp, vp, vp, f32, vp, vp, vp]),
         "sj_draft_block": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, vp]),
         "sj_score_block": (C.c_int, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
@@ -208,6 +209,10 @@ def sj_verify_head(model: int, kv: int, gamma: int, hidden, draft_tokens, draft_
     _check(load_library().sj_verify_head(model, kv, gamma, _ptr(hidden), _ptr(draft_tokens), _ptr(draft_probs),
                                          _ptr(uniforms), float(judge_threshold), _ptr(accepted_len), _ptr(next_token),
                                          _stream(stream)))
+
+
+def sj_set_temperature(model: int, temperature: float) -> None:
+    _check(load_library().sj_set_temperature(model, float(temperature)))
 
 
 def sj_verify_head_static(model: int, batch: int, gamma: int, hidden, draft_tokens, draft_probs, uniforms,

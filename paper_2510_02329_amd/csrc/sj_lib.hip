@@ -12,6 +12,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <memory>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -52,6 +53,9 @@ struct LayerW {
     void *attn_norm = nullptr, *wqkv = nullptr, *wo = nullptr, *ffn_norm = nullptr, *wgu = nullptr, *wd = nullptr;
 };
 
+struct GemmPlan;
+struct TunedPlans;
+
 struct sj_model {
     sj_config cfg{};
     ModelDims md{};
@@ -61,6 +65,11 @@ struct sj_model {
     std::vector<void*> allocs;
     int64_t weight_bytes = 0;
     int device = 0;
+    unsigned temp_gen = 0;                     // bumped by sj_set_temperature: captured launch graphs carry the old value
+    // launch shapes measured for this model, keyed by (rows, operand planes): a second cache object on the same
+    // model reuses them, so two objects of one process run the same kernels (bit-identical results)
+    mutable std::mutex tuned_mu;
+    mutable std::map<std::pair<int, int>, std::shared_ptr<TunedPlans>> tuned;
 };
 
 // Up to two row tiles (32 rows) the few-row kernel (every wave fetches its own operand fragments) is the faster
@@ -74,6 +83,7 @@ constexpr int FEW_ROWS = 32;
 // the kernel is instantiated for, the one that wastes the fewest workgroup slots, every wave keeping at least
 // 8 k-steps; tune_plans then measures that choice against the other shapes on the model's own weights.
 struct GemmPlan { int nt = 4, waves = 4, split = 1, depth = 2; };
+struct TunedPlans { GemmPlan qkv, o, d, gu, lm; };
 
 struct sj_kv {
     const sj_model* m = nullptr;
@@ -108,6 +118,7 @@ struct sj_kv {
     // optional timing of one kernel class (eager launches only)
     // captured launch graphs of the full step, keyed by (gamma, planes)
     std::map<int, hipGraphExec_t> graphs;
+    unsigned graph_gen = 0;               // temp_gen of the model the graphs were captured with
     hipStream_t cap_stream = nullptr;
     bool use_graph = true;
     int timing_class = 0;
@@ -279,6 +290,17 @@ extern "C" int sj_model_free(sj_model* m) {
 
 extern "C" int64_t sj_model_weight_bytes(const sj_model* m) { return m ? m->weight_bytes : 0; }
 
+extern "C" int sj_set_temperature(sj_model* m, float temperature) {
+    if (!m) return fail(SJ_EINVAL, "model is null");
+    if (!(temperature >= 0.f)) return fail(SJ_EINVAL, "temperature must be >= 0");
+    HIPCHK(hipDeviceSynchronize());                            // no step in flight still reads the old value
+    m->cfg.temperature = temperature;
+    m->md.temperature = temperature;
+    m->md.inv_temp = temperature > 0.f ? 1.0f / temperature : 0.f;
+    ++m->temp_gen;
+    return SJ_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // kv / workspace
 
@@ -308,6 +330,22 @@ static GemmPlan plan_partial(int ntiles, int ksteps, bool one_row_tile) {
 }
 
 static int tune_plans(sj_kv* kv, int rows);
+
+// the launch shapes the rule gives (before any measurement)
+static void rule_plans(sj_kv* kv) {
+    const sj_config& c = kv->m->cfg;
+    const int d = c.d_model, hd = c.head_dim, Nq = c.n_q_heads * hd, Nk = c.n_kv_heads * hd, F = c.d_ffn;
+    const int kstep = (c.dtype == SJ_DTYPE_FP32) ? 16 : 32;
+    for (int i = 0; i < 2; ++i) {
+        kv->plan_qkv[i] = plan_partial((Nq + 2 * Nk) / 16, d / kstep, i == 0);
+        kv->plan_o[i] = plan_partial(d / 16, Nq / kstep, i == 0);
+        kv->plan_d[i] = plan_partial(d / 16, F / kstep, i == 0);
+    }
+    kv->plan_gu = GemmPlan{};
+    kv->plan_gu.nt = (2 * F / 16) % 7 == 0 ? 7 : 8;       // whole rounds of workgroups where 7 tiles give them
+    kv->plan_gu.waves = 8; kv->plan_gu.split = 1; kv->plan_gu.depth = 2;
+    kv->plan_lm = GemmPlan{8, 4, 1, 2};
+}
 
 extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* capacity, sj_kv** out) {
     if (!m || !out) return fail(SJ_EINVAL, "model / out is null");
@@ -373,17 +411,11 @@ extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* cap
     if (c.n_layers > 0) {
         const int hd = c.head_dim, Nq = c.n_q_heads * hd, Nk = c.n_kv_heads * hd, F = c.d_ffn;
         const int G = c.n_q_heads / c.n_kv_heads;
-        const int kstep = (c.dtype == SJ_DTYPE_FP32) ? 16 : 32;
         size_t part_elems = 0;
-        for (int i = 0; i < 2; ++i) {
-            kv->plan_qkv[i] = plan_partial((Nq + 2 * Nk) / 16, d / kstep, i == 0);
-            kv->plan_o[i] = plan_partial(d / 16, Nq / kstep, i == 0);
-            kv->plan_d[i] = plan_partial(d / 16, F / kstep, i == 0);
+        rule_plans(kv);
+        for (int i = 0; i < 2; ++i)
             part_elems = std::max({part_elems, (size_t)kv->plan_qkv[i].split * R * (Nq + 2 * Nk),
                                    (size_t)kv->plan_o[i].split * R * d, (size_t)kv->plan_d[i].split * R * d});
-        }
-        kv->plan_gu.nt = (2 * F / 16) % 7 == 0 ? 7 : 8;   // whole rounds of workgroups where 7 tiles give them
-        kv->plan_gu.waves = 8; kv->plan_gu.split = 1; kv->plan_gu.depth = 2;
         // room for any few-row plan the start-up measurement may pick (at most 8 K-slices of at most 32 rows)
         part_elems = std::max(part_elems, (size_t)8 * std::min(R, FEW_ROWS) * std::max(Nq + 2 * Nk, d));
         kv->mpad = (G * (c.max_gamma + 1) + 63) / 64 * 64;   // whole groups of 4 MFMA tiles
@@ -510,7 +542,19 @@ static int time_mark(sj_kv* kv, int cls, hipStream_t st) {
 extern "C" int sj_set_operand_planes(sj_kv* kv, int32_t planes) {
     if (!kv) return fail(SJ_EINVAL, "kv is null");
     if (planes < 1 || planes > 3) return fail(SJ_EINVAL, "planes must be 1, 2 or 3");
+    if (planes == kv->planes) return SJ_OK;
     kv->planes = planes;
+    // the launch shapes were chosen for the previous plane count (some exist for one or two planes only): back to
+    // the rule's shapes, then the measured ones for this count (taken from the model's record when there is one)
+    if (kv->m->cfg.n_layers > 0 && kv->m->cfg.dtype == SJ_DTYPE_BF16) {
+        HIPCHK(hipDeviceSynchronize());
+        rule_plans(kv);
+        const char* e = std::getenv("SJ_TUNE");
+        if (!(e && e[0] == '0')) {
+            const int rc = tune_plans(kv, std::min(kv->max_rows, FEW_ROWS));
+            if (rc) return rc;
+        }
+    }
     return SJ_OK;
 }
 
@@ -658,6 +702,9 @@ static int few_partial(const GemmPlan& p, hipStream_t st, const void* W, const v
         SJ_SHAPE(2, 4, 4) SJ_SHAPE(2, 4, 2) SJ_SHAPE(2, 8, 2)
     }
 #undef SJ_SHAPE
+    // a shape that is not instantiated for this plane count: the rule's shape always is
+    const GemmPlan q = plan_partial(N / 16, K / Traits<T>::KSTEP, true);
+    if (q.nt != p.nt || q.waves != p.waves || q.depth != p.depth) return few_partial<T, SPL>(q, st, W, X, xplane, ldx, K, N, rows, out);
     return fail(SJ_EINVAL, "internal: no few-row kernel for %d tiles x %d waves, ring %d", p.nt, p.waves, p.depth);
 }
 
@@ -674,6 +721,9 @@ static int few_swiglu(const GemmPlan& p, hipStream_t st, const void* W, const vo
         SJ_SHAPE(7, 8, 3) SJ_SHAPE(7, 8, 4) SJ_SHAPE(8, 8, 4)
     }
 #undef SJ_SHAPE
+    GemmPlan q;
+    q.nt = (N2 / 16) % 7 == 0 ? 7 : 8; q.waves = 8; q.split = 1; q.depth = 2;
+    if (q.nt != p.nt || q.waves != p.waves || q.depth != p.depth) return few_swiglu<T, SPL>(q, st, W, X, xplane, K, N2, rows, act, actplane);
     return fail(SJ_EINVAL, "internal: no few-row gate/up kernel for %d tiles x %d waves", p.nt, p.waves);
 }
 
@@ -687,6 +737,7 @@ static int few_logits(const GemmPlan& p, hipStream_t st, const void* W, const vo
     SJ_SHAPE(8, 4)
     if constexpr (SPL <= 2) { SJ_SHAPE(8, 8) SJ_SHAPE(4, 8) SJ_SHAPE(4, 4) }
 #undef SJ_SHAPE
+    if (p.nt != 8 || p.waves != 4) return few_logits<T, SPL>(GemmPlan{8, 4, 1, 2}, st, W, X, xplane, K, V, rows, logits, stats, inv_temp);
     return fail(SJ_EINVAL, "internal: no few-row LM-head kernel for %d tiles x %d waves", p.nt, p.waves);
 }
 
@@ -837,6 +888,16 @@ static int tune_plans(sj_kv* kv, int rows) {
     const sj_model* m = kv->m;
     const sj_config& c = m->cfg;
     const int d = c.d_model, Nq = c.n_q_heads * c.head_dim, Nk = c.n_kv_heads * c.head_dim, F = c.d_ffn;
+    const std::pair<int, int> key(rows, c.dtype == SJ_DTYPE_FP32 ? 1 : kv->planes);
+    {
+        std::lock_guard<std::mutex> lock(m->tuned_mu);
+        auto it = m->tuned.find(key);
+        if (it != m->tuned.end()) {                          // measured before on this model: same shapes again
+            const TunedPlans& t = *it->second;
+            kv->plan_qkv[0] = t.qkv; kv->plan_o[0] = t.o; kv->plan_d[0] = t.d; kv->plan_gu = t.gu; kv->plan_lm = t.lm;
+            return SJ_OK;
+        }
+    }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     HIPCHK(hipEventCreate(&e0));
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(SJ_EHIP, "hipEventCreate failed"); }
@@ -856,6 +917,12 @@ static int tune_plans(sj_kv* kv, int rows) {
 #undef SJ_TUNE3
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
+    if (!rc) {
+        auto t = std::make_shared<TunedPlans>();
+        t->qkv = kv->plan_qkv[0]; t->o = kv->plan_o[0]; t->d = kv->plan_d[0]; t->gu = kv->plan_gu; t->lm = kv->plan_lm;
+        std::lock_guard<std::mutex> lock(m->tuned_mu);
+        m->tuned.emplace(key, t);
+    }
     if (const char* e = std::getenv("SJ_TUNE_LOG")) {
         if (e[0] == '1') {
             auto show = [](const char* name, const GemmPlan& p) {
@@ -1085,6 +1152,11 @@ static int verify_step_impl(sj_model* m, sj_kv* kv, int gamma, const StepParams&
     if (!graph) {
         if ((rc = set_params(kv, st, p))) return rc;
         return enqueue_step<T, SPL>(m, kv, gamma, st, head_only, hidden);
+    }
+    if (kv->graph_gen != m->temp_gen) {                        // the temperature changed: the graphs hold the old one
+        for (auto& g : kv->graphs) (void)hipGraphExecDestroy(g.second);
+        kv->graphs.clear();
+        kv->graph_gen = m->temp_gen;
     }
     const int key = gamma * 4 + SPL;
     auto it = kv->graphs.find(key);

@@ -29,7 +29,7 @@ def _fill_caches(shape, gpu, cfg, lens, seed, capacity):
     return caches
 
 
-def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label, force_rounding=False):
+def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label, force_rounding=False, scale=1.0):
     B, gamma = draft["tokens"].shape
     L0 = [c.length for c in caches]
     out = gpu.step(draft, theta, gamma)
@@ -42,35 +42,24 @@ def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label, force_roundin
         assert flips["flips"] < 0.10 * flips["rows"]
     stats = {}
     for b in range(B):
-        stats["logits"] = G.close_enough(out["logits"][b], ref[b]["logits"], shape.dtype, f"{label} logits seq {b}")
+        lg = G.close_enough(out["logits"][b], ref[b]["logits"], shape.dtype, f"{label} logits seq {b}", scale=scale)
+        stats["logits"] = max(stats.get("logits", (0.0, 0.0)), lg, key=lambda t: t[1])
         G.close_enough(out["hn"][b], ref[b]["hn"], shape.dtype, f"{label} hidden seq {b}")
         G.close_enough(out["judge_scores"][b], ref[b]["judge_scores"], shape.dtype, f"{label} judge seq {b}")
         for l in (0, shape.n_layers - 1):
             k, v = gpu.kv_rows(b, l, L0[b], gamma + 1)
             G.close_enough(k, ref[b]["k_new"][l], shape.dtype, f"{label} appended K seq {b} layer {l}")
             G.close_enough(v, ref[b]["v_new"][l], shape.dtype, f"{label} appended V seq {b} layer {l}")
-    # decisions: exact on replay of the device's own logits; against the pure oracle a mismatch is
+    # decisions: exact on replay of the device's own logits (B); against the pure oracle (C) a mismatch is
     # excused only when the oracle's margin is inside the logit tolerance
     bad, excused = G.replay_matches(shape, out, draft, theta)
     assert not bad, bad
-    a_tol, r_tol = G.TOL[shape.dtype]
-    unexcused = 0
-    for b in range(B):
-        for j in range(gamma):
-            ra = bool(ref[b]["align_bits"][j]); ga = bool(out["bits"][b, j] & 1)
-            rj = bool(ref[b]["judge_bits"][j]); gj = bool(out["bits"][b, j] & 2)
-            d = int(draft["tokens"][b, j])
-            if ra != ga:
-                p, q, u = ref[b]["p_at_draft"][j], float(draft["probs"][b, j, d]), float(draft["uniforms"][b, j])
-                tau = a_tol + r_tol * abs(ref[b]["logits"][j, d])
-                if abs(np.log(p) - np.log(max(u * q, 1e-300))) > 2 * tau:
-                    unexcused += 1
-            if rj != gj:
-                s = ref[b]["judge_scores"][j]
-                z = np.log(s / (1 - s))
-                if abs(z - np.log(theta / (1 - theta))) > a_tol + r_tol * abs(z):
-                    unexcused += 1
-    assert unexcused == 0
+    cnt = G.decisions_vs_oracle(shape, out, ref, draft, theta)
+    print(f"{label}: replay excused {excused}; vs pure oracle: tokens equal {cnt['tokens_equal']}/{cnt['tokens']}, "
+          f"excused bits {cnt['bit_excused']} lengths {cnt['len_excused']} tokens {cnt['token_excused']}, "
+          f"unexcused {cnt['unexcused']}", flush=True)
+    assert excused == 0 and cnt["unexcused"] == 0
+    stats["decisions"] = cnt
     ln, pend = sj.sj_kv_state(gpu.kv, B)
     assert (0 <= out["accepted_len"]).all() and (out["accepted_len"] <= gamma).all()
     assert (ln == np.array(L0) + 1 + out["accepted_len"]).all()
@@ -167,5 +156,34 @@ def test_llama8b_batch1_full_size():
         assert [(int(x) >> 2) & 1 for x in out_k["bits"][0]] == [int(t) for t in tail["topk_bits"]]
         assert int(out_k["accepted_len"][0]) == tail["accepted_len"] and int(out_k["next_token"][0]) == tail["next_token"]
         assert np.array_equal(out_k["logits"], out["logits"])               # the mode does not touch the forward
+        sj.sj_set_mode(gpu.kv, sj.SJ_MODE_TWO_STAGE)
+        # peaked and greedy target distributions (same forward, so the oracle's logits are reused): here the emitted
+        # token is meaningful - on the flat T = 1 distribution almost any draw sits next to a cell boundary
+        w_j, b_j = W("judge_w"), float(np.asarray(W("judge_b")).reshape(-1)[0])
+        for T in (0.125, 0.0):
+            sj.sj_set_temperature(gpu.model, T)
+            sj.sj_kv_rewind(gpu.kv, len0.tolist(), pend0.tolist())
+            shape_T = shape.scaled(temperature=T)
+            out_T = gpu.step(draft, 0.5)
+            ref_T = dict(ref[0])
+            ref_T.update(orc.verify_tail(ref[0]["logits"], ref[0]["judge_scores"], draft["tokens"][0], draft["probs"][0],
+                                         draft["uniforms"][0], 0.5, T))
+            bad, excused = G.replay_matches(shape_T, out_T, draft, 0.5)
+            assert not bad and excused == 0, (T, bad, excused)
+            cnt = G.decisions_vs_oracle(shape_T, out_T, [ref_T], draft, 0.5)
+            print(f"8B T={T}: accepted {int(out_T['accepted_len'][0])} (oracle {ref_T['accepted_len']}), token "
+                  f"{int(out_T['next_token'][0])} (oracle {ref_T['next_token']}), {cnt}", flush=True)
+            assert cnt["unexcused"] == 0
+            assert np.array_equal(out_T["logits"], out["logits"])           # temperature does not touch the forward
+        sj.sj_set_temperature(gpu.model, shape.temperature)
+        # three operand planes on this shape with the start-up measurement on: the launch shapes are re-derived for
+        # the new plane count; the logits move closer to the oracle
+        sj.sj_set_operand_planes(gpu.kv, 3)
+        sj.sj_kv_rewind(gpu.kv, len0.tolist(), pend0.tolist())
+        out3 = gpu.step(draft, 0.5)
+        err3, worst3 = G.close_enough(out3["logits"][0], ref[0]["logits"], shape.dtype, "8B logits, three planes")
+        print("8B logits with three operand planes: max err %.3e worst err/bound %.3f (two planes: %.3f)" % (err3, worst3, stats["logits"][1]), flush=True)
+        assert worst3 <= stats["logits"][1]
+        sj.sj_set_operand_planes(gpu.kv, 2)
     finally:
         gpu.close()

@@ -159,6 +159,39 @@ def test_threshold_extremes_and_rerun_is_bit_identical():
         gpu.close()
 
 
+def test_two_cache_objects_on_one_model_are_bit_identical():
+    """The launch shapes measured when the first cache object is created are kept with the model: a second object
+    runs the same kernels in the same summation order (and a changed temperature only changes the tail)."""
+    shape = BASE
+    gpu, cfg, W, caches = _setup(shape, [50, 31])
+    try:
+        draft = synth.make_draft(shape, seed=12)
+        a = gpu.step(draft, 0.5)
+        kv2 = sj.sj_kv_create(gpu.model, shape.batch, [50 + 64, 31 + 64])
+        first = gpu.kv
+        try:
+            gpu.kv = kv2
+            cfg2 = helpers.oracle_config(shape)
+            _fill_caches(shape, gpu, cfg2, [50, 31], seed=6, capacity=[50 + 64, 31 + 64])
+            b = gpu.step(draft, 0.5)
+            for k in ("logits", "hn", "judge_scores", "p_at_draft", "bits", "accepted_len", "next_token"):
+                assert np.array_equal(a[k], b[k]), k
+            sj.sj_set_temperature(gpu.model, 0.5)
+            sj.sj_kv_rewind(kv2, [50, 31], [int(c.pending) for c in caches])
+            c2 = gpu.step(draft, 0.5)
+            assert np.array_equal(c2["logits"], a["logits"])
+            tail = [orc.verify_tail(c2["logits"][i].astype(np.float64), c2["judge_scores"][i], draft["tokens"][i], draft["probs"][i],
+                                    draft["uniforms"][i], 0.5, 0.5) for i in range(2)]
+            assert [int(x) for x in c2["accepted_len"]] == [t["accepted_len"] for t in tail]
+            assert [int(x) for x in c2["next_token"]] == [t["next_token"] for t in tail]
+            sj.sj_set_temperature(gpu.model, shape.temperature)
+        finally:
+            gpu.kv = first
+            sj.sj_kv_free(kv2)
+    finally:
+        gpu.close()
+
+
 def test_capacity_and_argument_errors():
     shape = BASE
     gpu, cfg, W, caches = _setup(shape, [60, 10], cap=[64, 64])

@@ -433,6 +433,45 @@ def test_verify_step_commits_length_and_pending():
     assert np.allclose(res["judge_scores"], expect, atol=1e-12)
 
 
+# ------------------------------------------------------------------ prefill (R6, R8)
+# Pinned against token-by-token decoding on a cache of its own (the prompt's K / V rows and the last row's logits
+# must be those of n sequential single-token steps) and against the tie rule: with two equal largest logits the
+# pending token is the lower index.
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_prefill_equals_sequential_decode_and_breaks_ties_low(seed):
+    shape, cfg, t = _tiny(seed)
+    W = helpers.dict_weights(t)
+    rng = np.random.default_rng(seed)
+    prompt = [int(x) for x in rng.integers(0, cfg.vocab, size=7)]
+    cache = orc.SeqCache(cfg, 16)
+    pend = orc.prefill(cfg, W, cache, prompt)
+    seq = orc.SeqCache(cfg, 16)
+    last = None
+    for tok in prompt:                                   # one token at a time, each on top of the rows before it
+        last = orc.block_forward(cfg, W, [seq], [[tok]])[0]["logits"][0]
+        seq.length += 1
+    assert cache.length == len(prompt) == seq.length
+    for l in range(cfg.n_layers):
+        assert np.allclose(cache.k[l][:, :7], seq.k[l][:, :7], atol=1e-12)
+        assert np.allclose(cache.v[l][:, :7], seq.v[l][:, :7], atol=1e-12)
+    k = int(np.argmax(last))
+    assert pend == k == cache.pending
+    # tie: give a lower-index vocabulary entry the same LM-head row as the winner (or a higher one when k = 0)
+    t2 = dict(t)
+    lm = t[("lm_head", -1)].copy()
+    other = k - 1 if k > 0 else k + 1
+    lm[other] = lm[k]
+    t2[("lm_head", -1)] = lm
+    c2 = orc.SeqCache(cfg, 16)
+    assert orc.prefill(cfg, helpers.dict_weights(t2), c2, prompt) == min(k, other)
+    # all logits equal: index 0
+    t3 = dict(t)
+    t3[("lm_head", -1)] = np.zeros_like(lm)
+    assert orc.prefill(cfg, helpers.dict_weights(t3), orc.SeqCache(cfg, 16), prompt) == 0
+
+
 # ------------------------------------------------------------------ P8: draft proposal (Eq. 1)
 # The draft block is gamma single-token decodes.  Pinned against things it does not compute itself:
 # a from-scratch forward of the whole sequence (positions, caching, which token is fed), the verification
