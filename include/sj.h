@@ -252,7 +252,8 @@ int sj_kv_rewind(sj_kv* kv, const int32_t* len_host, const int32_t* pending_host
  * a captured graph).  sj_get_kernel_timing synchronises, returns the summed duration and launch count since the
  * last call, and clears them.  0 switches it off. */
 int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class);
-/* Launches the projection kernel of class 1..4 `launches` times back to back on `stream`, cycling through
+/* Launches the projection kernel of class 1..4, or 5 = the LM-head product with its softmax partials,
+ * `launches` times back to back on `stream`, cycling through
  * the layers' weights (so nothing is re-read from cache) with the operands left by the last step, and
  * returns the elapsed time between two HIP events around the whole series.  Synchronises `stream`. */
 int sj_time_kernel_class(sj_model* m, sj_kv* kv, int32_t kernel_class, int32_t launches, void* stream, double* total_ms);

@@ -222,6 +222,11 @@ constexpr int R4_LW = 4;           // loader waves: two for the weights, two for
 
 // NT = n-tiles per workgroup: 8, or 7 where that makes the number of workgroups a multiple of the CU count
 // (gate/up projection of the 8B shape: 1792 n-tiles = 256 x 7).
+// Several row groups in ONE launch (a.rgroups > 1): the weights should come from HBM once for all of them, so the
+// workgroups that share an n-tile group must run at the same time on compute units that share a cache.  Workgroups
+// are handed to the 8 XCDs (each with an L2 of its own) round robin by index, so workgroup i works for XCD i % 8;
+// within an XCD consecutive workgroups take the row groups of one n-tile group, then the next n-tile group: the first
+// of them pulls a weight tile from HBM, the others find it in their L2 a moment later.
 template <typename T, int EPI, int SPL, int NT = R2_NT>
 __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmArgs a, int mt) {
     static_assert(SPL <= 2, "three operand planes do not fit");
@@ -232,7 +237,21 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g = lane >> 4;
     const int KS = a.K / KSTEP, ntiles = a.N / 16;
-    const int nt0 = blockIdx.x * NT;
+    int bx = blockIdx.x;
+    if (a.rgroups > 1) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        const int rg = j % a.rgroups;
+        bx = (j / a.rgroups) * 8 + xcd;
+        if (bx * NT >= ntiles) return;                 // padding of the grid to whole XCD rounds (uniform)
+        const int row0 = rg * (ROWS_MT * 16), nr = min(ROWS_MT * 16, a.R - row0);
+        a.X = reinterpret_cast<const char*>(a.X) + (size_t)row0 * a.ldx * sizeof(T);
+        if (EPI == EPI_SWIGLU) a.act = reinterpret_cast<char*>(a.act) + (size_t)row0 * (a.N / 2) * sizeof(T);
+        else a.out += (size_t)row0 * a.N;
+        if (EPI == EPI_LOGITS) a.stats += (size_t)row0 * ntiles;
+        a.R = nr;
+        mt = (nr + 15) / 16;
+    }
+    const int nt0 = bx * NT;
     const int ks0 = (int)((long long)blockIdx.y * KS / gridDim.y), ks1 = (int)((long long)(blockIdx.y + 1) * KS / gridDim.y);
     const int nks = ks1 - ks0;
     if (nks <= 0) return;                              // uniform for the workgroup

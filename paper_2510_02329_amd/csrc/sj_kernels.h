@@ -195,6 +195,8 @@ struct GemmArgs {
     float inv_temp;     // 1/T, 0 when T = 0
     int32_t x_tks;      // 0: X planes are row-major; else K / KSTEP: fragment-tiled planes (opnd_off)
     int32_t act_tks;    // same for act (its K is N/2)
+    int32_t rgroups;    // many-row kernel: row groups of one launch (0 or 1: the launch is one group of R rows); with
+                        // more, R is the total row count and every workgroup derives its group's rows and pointers
 };
 
 #ifdef SJ_GEMM_PROF

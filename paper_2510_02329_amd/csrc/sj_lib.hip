@@ -944,8 +944,8 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
     const int ntiles = N / 16;
     // fragment-tiled operand planes: a group of 144 rows starts row0 * K elements into the plane in either layout
     if (tiled && ldx != K) return fail(SJ_EINVAL, "a tiled operand has no padding between rows");
-    for (int row0 = 0; row0 < rows; row0 += ROWS_MT * 16) {
-        const int nr = std::min(ROWS_MT * 16, rows - row0);
+    const int group_rows = ROWS_MT * 16;
+    auto args_of = [&](int row0, int nr) {
         GemmArgs a{};
         a.Wt = Wt;
         a.X = (const char*)X + (size_t)row0 * ldx * sizeof(T);
@@ -958,19 +958,32 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
         if (EPI == EPI_PARTIAL) a.out = out + (size_t)row0 * N;            // [split][rows][N]
         else if (EPI == EPI_LOGITS) { a.out = out + (size_t)row0 * N; a.stats = stats + (size_t)row0 * ntiles; }
         else a.act = (char*)act + (size_t)row0 * (N / 2) * sizeof(T);
-        const dim3 grid((ntiles + R2_NT - 1) / R2_NT, EPI == EPI_PARTIAL ? split : 1);
-        if constexpr (SPL <= 2) {
-            // 7 n-tiles per workgroup where that fills whole rounds of the chip and 8 do not (gate/up of the 8B shape:
-            // 256 workgroups instead of 224), from 8 row tiles on (below that the lighter weight stream per CU loses)
-            const int mt = (nr + 15) / 16;
-            if (EPI == EPI_SWIGLU && mt >= 8 && ntiles % 7 == 0 && (ntiles / 7) % 256 == 0 && ((ntiles + 7) / 8) % 256 != 0)
-                gemm_rows4_kernel<T, EPI, SPL, 7><<<dim3(ntiles / 7, 1), (R2_CW + R4_LW) * 64, 0, st>>>(a, mt);
-            else
-                gemm_rows4_kernel<T, EPI, SPL><<<grid, (R2_CW + R4_LW) * 64, 0, st>>>(a, mt);
-        } else {
-            gemm_rows2_kernel<T, EPI, SPL><<<grid, (R2_CW + R2_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
-        }
+        return a;
+    };
+    if constexpr (SPL <= 2) {
+        // one launch for all row groups: the workgroups of an n-tile group run side by side on one XCD, so the
+        // weights are fetched from HBM once for all rows (gemm_rows4_kernel).  7 n-tiles per workgroup where that
+        // fills whole rounds of the chip and 8 do not (gate/up of the 8B shape: 256 workgroups instead of 224), from
+        // 8 row tiles on (below that the lighter weight stream per CU loses)
+        const int rgroups = (rows + group_rows - 1) / group_rows;
+        const int mt = (std::min(rows, group_rows) + 15) / 16;
+        GemmArgs a = args_of(0, rgroups > 1 ? rows : std::min(rows, group_rows));
+        a.rgroups = rgroups;
+        const bool seven = EPI == EPI_SWIGLU && mt >= 8 && ntiles % 7 == 0 && (ntiles / 7) % 256 == 0 && ((ntiles + 7) / 8) % 256 != 0;
+        const int per = seven ? 7 : R2_NT, ngroups = (ntiles + per - 1) / per;
+        const int gx = rgroups > 1 ? (ngroups + 7) / 8 * 8 * rgroups : ngroups;
+        const dim3 grid(gx, EPI == EPI_PARTIAL ? split : 1);
+        if (seven) gemm_rows4_kernel<T, EPI, SPL, 7><<<grid, (R2_CW + R4_LW) * 64, 0, st>>>(a, mt);
+        else gemm_rows4_kernel<T, EPI, SPL><<<grid, (R2_CW + R4_LW) * 64, 0, st>>>(a, mt);
         LAUNCHCHK("gemm_rows");
+    } else {
+        for (int row0 = 0; row0 < rows; row0 += group_rows) {
+            const int nr = std::min(group_rows, rows - row0);
+            const GemmArgs a = args_of(row0, nr);
+            const dim3 grid((ntiles + R2_NT - 1) / R2_NT, EPI == EPI_PARTIAL ? split : 1);
+            gemm_rows2_kernel<T, EPI, SPL><<<grid, (R2_CW + R2_LW) * 64, 0, st>>>(a, (nr + 15) / 16);
+            LAUNCHCHK("gemm_rows");
+        }
     }
     return SJ_OK;
 }
@@ -1074,9 +1087,9 @@ struct Runner {
 
     // LM head -> logits + softmax statistics of every row (Eq. 2's p, kept as (max, Z, arg-max)).
     // Hidden states handed in by the caller are already in the storage dtype: one plane suffices then.
-    int lm_head(bool exact_operand) {
+    int lm_gemm(bool exact_operand, int& nblk) {
         const ModelDims& md = m->md;
-        int rc, nblk;
+        int rc;
         if (R > FEW_ROWS) {
             rc = exact_operand
                 ? gemm_rows<T, EPI_LOGITS, 1>(st, m->lm_head, kv->xn, plane(md.d), md.d, md.d, md.V, R, 1, kv->logits, nullptr, 0, kv->stats, md.inv_temp, true)
@@ -1088,8 +1101,13 @@ struct Runner {
                 : few_logits<T, SPL>(kv->plan_lm, st, m->lm_head, kv->xn, plane(md.d), md.d, md.V, R, kv->logits, kv->stats, md.inv_temp);
             nblk = md.V / 16 / kv->plan_lm.nt;
         }
+        return rc;
+    }
+    int lm_head(bool exact_operand) {
+        int nblk = 0;
+        const int rc = lm_gemm(exact_operand, nblk);
         if (rc) return rc;
-        softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, md.inv_temp, kv->rowstat);
+        softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, m->md.inv_temp, kv->rowstat);
         LAUNCHCHK("softmax_merge");
         return SJ_OK;
     }
@@ -1200,6 +1218,11 @@ static int time_kernel_impl(sj_model* m, sj_kv* kv, int cls, int launches, int g
     int rc = SJ_OK;
     HIPCHK(hipEventRecord(e0, st));
     for (int i = 0; i < launches && !rc; ++i) {
+        if (cls == 5) {                                          // LM head (1 GB at the paper's vocabulary: no reuse either)
+            int nblk = 0;
+            rc = run.lm_gemm(m->cfg.n_layers == 0, nblk);
+            continue;
+        }
         const LayerW& L = m->layers[i % m->cfg.n_layers];        // a different layer each time: no cache reuse
         switch (cls) {
             case 1: rc = run.partial_gemm(L.wqkv, kv->xn, d, d, Nq + 2 * Nk, kv->plan_qkv); break;
@@ -1222,8 +1245,9 @@ static int time_kernel_impl(sj_model* m, sj_kv* kv, int cls, int launches, int g
 
 extern "C" int sj_time_kernel_class(sj_model* m, sj_kv* kv, int32_t kernel_class, int32_t launches, void* stream, double* total_ms) {
     if (!m || !kv || !total_ms) return fail(SJ_EINVAL, "null argument");
-    if (kv->m != m || m->cfg.n_layers == 0) return fail(SJ_EINVAL, "needs a decoder model and its kv");
-    if (kernel_class < 1 || kernel_class > 4 || launches < 1) return fail(SJ_EINVAL, "kernel_class must be 1..4, launches >= 1");
+    if (kv->m != m) return fail(SJ_EINVAL, "kv was created for a different model");
+    if (kernel_class < 1 || kernel_class > 5 || launches < 1) return fail(SJ_EINVAL, "kernel_class must be 1..5, launches >= 1");
+    if (kernel_class != 5 && m->cfg.n_layers == 0) return fail(SJ_EINVAL, "a head-only model has only the LM head (class 5)");
     if (kv->last_gamma < 1) return fail(SJ_EINVAL, "run a verification step first (the operands of the last step are reused)");
     hipStream_t st = (hipStream_t)stream;
     if (m->cfg.dtype == SJ_DTYPE_FP32) return time_kernel_impl<float, 1>(m, kv, kernel_class, launches, kv->last_gamma, st, total_ms);

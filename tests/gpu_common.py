@@ -13,19 +13,7 @@ from tests import helpers
 TOL = {"fp32": (1e-4, 1e-4), "bf16": (1e-2, 2e-2)}      # (abs, rel) of the spec parity bar
 
 
-def sj_config(shape: synth.ModelShape, max_gamma: int | None = None) -> sj.SJConfig:
-    return sj.SJConfig(n_layers=shape.n_layers, d_model=shape.d_model, n_q_heads=shape.n_q_heads,
-                       n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, d_ffn=shape.d_ffn, vocab=shape.vocab,
-                       dtype=0 if shape.dtype == "fp32" else 1, rope_base=shape.rope_base, rms_eps=shape.rms_eps,
-                       temperature=shape.temperature, max_gamma=max_gamma or shape.gamma)
-
-
-def load_model(shape: synth.ModelShape, src: synth.WeightSource, max_gamma: int | None = None) -> int:
-    def provider(name, layer):
-        if name == "wq" and layer % 8 == 0 and shape.n_layers > 40:
-            print(f"  loading layer {layer}/{shape.n_layers}", flush=True)       # long loads must show progress
-        return src.tensor(name, layer)
-    return sj.sj_model_load(sj_config(shape, max_gamma), provider)
+from synth.device import load_model, sj_config  # noqa: E402,F401  (shared with the benchmark)
 
 
 class Gpu:
