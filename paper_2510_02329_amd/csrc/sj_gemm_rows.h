@@ -38,9 +38,6 @@ constexpr int R2_NB = 4;           // LDS stage buffers
 constexpr int R2_MTW = 3;          // row tiles per compute wave (4 waves x 3 >= 9 row tiles)
 constexpr int R2_RING = 4;         // operand ring (k-steps) = k-steps per stage
 
-// s_waitcnt vmcnt(n) with the other counters left alone (vmcnt sits in bits 3:0 and 15:14)
-constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
-
 // Epilogue of the many-row kernels from the accumulators: lane holds columns nt*16 + 4g .. +3 of row
 // m*16 + r; wave w owns row tiles w, w + 4, w + 8.
 template <typename T, int EPI, int NT = R2_NT>

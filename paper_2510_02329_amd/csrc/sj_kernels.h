@@ -199,6 +199,57 @@ struct GemmArgs {
                         // more, R is the total row count and every workgroup derives its group's rows and pointers
 };
 
+// Epilogue of the few-row kernels for one (row, column en of every tile) position: v[t] is the finished sum of tile
+// nt0 + t.  Every thread of the first 256 of the workgroup calls it (16 consecutive lanes share a row; rows >= R
+// take part in the shuffles and store nothing).
+template <typename T, int NT, int EPI>
+__device__ __forceinline__ void few_epilogue(const GemmArgs& a, const float (&v)[NT], int row, int en, int nt0) {
+    if constexpr (EPI == EPI_PARTIAL) {
+        if (row < a.R) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                a.out[((size_t)blockIdx.y * a.slice_rows + row) * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
+        }
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // tile column en < 8 is gate of FFN column 8*tile + en, column en + 8 its up projection
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const float up = __shfl_down(v[t], 8, 64);
+            if (row < a.R && en < 8) {
+                const float gate = v[t];
+                const float y = gate / (1.0f + expf(-gate)) * up;
+                Traits<T>::store_split(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)(nt0 + t) * 8 + en,
+                                       a.actplane, y);
+            }
+        }
+    } else {
+        // logits + this workgroup's softmax partial for the row (16 lanes share a row)
+        float mx = v[0];
+        int arg = nt0 * 16 + en;
+#pragma unroll
+        for (int t = 1; t < NT; ++t)
+            if (v[t] > mx) { mx = v[t]; arg = (nt0 + t) * 16 + en; }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+            const float omx = __shfl_xor(mx, o, 64);
+            const int oarg = __shfl_xor(arg, o, 64);
+            if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+        }
+        float se = 0.f;
+        if (a.inv_temp > 0.f) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) se += expf((v[t] - mx) * a.inv_temp);
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) se += __shfl_xor(se, o, 64);
+        }
+        if (row < a.R) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) a.out[(size_t)row * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
+            if (en == 0) a.stats[(size_t)row * gridDim.x + blockIdx.x] = float4{mx, se, __int_as_float(arg), 0.f};
+        }
+    }
+}
+
 #ifdef SJ_GEMM_PROF
 __device__ unsigned long long gemm_prof[8192 * 8];
 #define GEMM_STAMP(k) do { if ((threadIdx.x & 63) == 0) gemm_prof[(((blockIdx.y * gridDim.x + blockIdx.x) * WAVES + (threadIdx.x >> 6)) & 8191) * 8 + (k)] = wall_clock64(); } while (0)
@@ -296,50 +347,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
             for (int ww = 1; ww < WAVES; ++ww) sum += red[ww][t * MT + m][tid];
             v[t] = sum;
         }
-        if constexpr (EPI == EPI_PARTIAL) {
-            if (row < a.R) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    a.out[((size_t)blockIdx.y * a.slice_rows + row) * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
-            }
-        } else if constexpr (EPI == EPI_SWIGLU) {
-            // tile column en < 8 is gate of FFN column 8*tile + en, column en + 8 its up projection
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float up = __shfl_down(v[t], 8, 64);
-                if (row < a.R && en < 8) {
-                    const float gate = v[t];
-                    const float y = gate / (1.0f + expf(-gate)) * up;
-                    Traits<T>::store_split(reinterpret_cast<T*>(a.act) + (size_t)row * (a.N / 2) + (size_t)(nt0 + t) * 8 + en,
-                                           a.actplane, y);
-                }
-            }
-        } else {
-            // logits + this workgroup's softmax partial for the row (16 lanes share a row)
-            float mx = v[0];
-            int arg = nt0 * 16 + en;
-#pragma unroll
-            for (int t = 1; t < NT; ++t)
-                if (v[t] > mx) { mx = v[t]; arg = (nt0 + t) * 16 + en; }
-#pragma unroll
-            for (int o = 1; o < 16; o <<= 1) {
-                const float omx = __shfl_xor(mx, o, 64);
-                const int oarg = __shfl_xor(arg, o, 64);
-                if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
-            }
-            float se = 0.f;
-            if (a.inv_temp > 0.f) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t) se += expf((v[t] - mx) * a.inv_temp);
-#pragma unroll
-                for (int o = 1; o < 16; o <<= 1) se += __shfl_xor(se, o, 64);
-            }
-            if (row < a.R) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t) a.out[(size_t)row * a.N + (size_t)(nt0 + t) * 16 + en] = v[t];
-                if (en == 0) a.stats[(size_t)row * gridDim.x + blockIdx.x] = float4{mx, se, __int_as_float(arg), 0.f};
-            }
-        }
+        few_epilogue<T, NT, EPI>(a, v, row, en, nt0);
     }
 }
 

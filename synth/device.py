@@ -15,14 +15,14 @@ def sj_config(shape: ModelShape, max_gamma: int | None = None):
                        temperature=shape.temperature, max_gamma=max_gamma or shape.gamma)
 
 
-def load_model(shape: ModelShape, src: WeightSource, max_gamma: int | None = None) -> int:
+def load_model(shape: ModelShape, src: WeightSource, max_gamma: int | None = None, log=print) -> int:
     """sj_model_load with the generator as the tensor provider (one layer at a time: a 70B-shaped model never sits
-    in host memory)."""
+    in host memory).  `log` receives a progress line every few layers of a deep model."""
     import paper_2510_02329_amd as sj
 
     def provider(name, layer):
         if name == "wq" and layer % 8 == 0 and shape.n_layers > 40:
-            print(f"  loading layer {layer}/{shape.n_layers}", flush=True)       # long loads must show progress
+            log(f"  loading layer {layer}/{shape.n_layers}")             # long loads must show progress
         return src.tensor(name, layer)
     return sj.sj_model_load(sj_config(shape, max_gamma), provider)
 

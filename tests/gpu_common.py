@@ -9,6 +9,7 @@ import paper_2510_02329_amd as sj
 import synth
 from oracle import selfjudge_oracle as orc
 from tests import helpers
+from tests.progress import say
 
 TOL = {"fp32": (1e-4, 1e-4), "bf16": (1e-2, 2e-2)}      # (abs, rel) of the spec parity bar
 
@@ -21,7 +22,7 @@ class Gpu:
 
     def __init__(self, shape, src, capacity, max_gamma=None):
         self.shape = shape
-        self.model = load_model(shape, src, max_gamma)
+        self.model = load_model(shape, src, max_gamma, log=say)
         self.kv = sj.sj_kv_create(self.model, shape.batch, capacity)
         self.dev = torch.device("cuda:0")
 

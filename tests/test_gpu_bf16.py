@@ -9,6 +9,7 @@ import synth
 from oracle import selfjudge_oracle as orc
 from tests import gpu_common as G
 from tests import helpers
+from tests.progress import say
 
 pytestmark = pytest.mark.gpu
 
@@ -23,6 +24,8 @@ def _fill_caches(shape, gpu, cfg, lens, seed, capacity):
             sj.sj_kv_set_layer(gpu.kv, b, l, k, v, int(lens[b]))
             c.k[l][:, :lens[b]] = synth.to_f64(k)
             c.v[l][:, :lens[b]] = synth.to_f64(v)
+        if shape.n_layers > 40:
+            say(f"  cache of sequence {b} filled")
         c.length, c.pending = int(lens[b]), int(pend[b])
         sj.sj_kv_set_state(gpu.kv, b, int(lens[b]), int(pend[b]))
         caches.append(c)
@@ -38,7 +41,7 @@ def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label, force_roundin
         G.force_device_rounding(gpu, caches, gamma, flips)
     ref = orc.verify_step(cfg, W, caches, draft["tokens"], draft["probs"], draft["uniforms"], theta)
     if force_rounding:
-        print(f"{label}: {flips['flips']} of {flips['rows']} stored K/V elements took the other bf16 neighbour", flush=True)
+        say(f"{label}: {flips['flips']} of {flips['rows']} stored K/V elements took the other bf16 neighbour")
         assert flips["flips"] < 0.10 * flips["rows"]
     stats = {}
     for b in range(B):
@@ -55,9 +58,9 @@ def _compare_step(shape, gpu, cfg, W, caches, draft, theta, label, force_roundin
     bad, excused = G.replay_matches(shape, out, draft, theta)
     assert not bad, bad
     cnt = G.decisions_vs_oracle(shape, out, ref, draft, theta)
-    print(f"{label}: replay excused {excused}; vs pure oracle: tokens equal {cnt['tokens_equal']}/{cnt['tokens']}, "
+    say(f"{label}: replay excused {excused}; vs pure oracle: tokens equal {cnt['tokens_equal']}/{cnt['tokens']}, "
           f"excused bits {cnt['bit_excused']} lengths {cnt['len_excused']} tokens {cnt['token_excused']}, "
-          f"unexcused {cnt['unexcused']}", flush=True)
+          f"unexcused {cnt['unexcused']}")
     assert excused == 0 and cnt["unexcused"] == 0
     stats["decisions"] = cnt
     ln, pend = sj.sj_kv_state(gpu.kv, B)
@@ -121,7 +124,7 @@ def test_llama8b_batch1_full_size():
     shape = synth.CONFIGS[2]
     src = synth.WeightSource(shape, seed=0)
     cap = [1024 + 64]
-    print("loading 8B-shaped model", flush=True)
+    say("loading 8B-shaped model")
     gpu = G.Gpu(shape, src, cap)
     try:
         cfg = helpers.oracle_config(shape)
@@ -137,15 +140,15 @@ def test_llama8b_batch1_full_size():
         sj.sj_score_block(gpu.model, gpu.kv, gamma + 1, torch.from_numpy(ins).to(dev), torch.from_numpy(tgt).to(dev), lp)
         torch.cuda.synchronize()
         assert (np.array(sj.sj_kv_state(gpu.kv, 1)) == np.array([len0, pend0])).all()
-        print("step", flush=True)
+        say("step")
         out, ref, stats = _compare_step(shape, gpu, cfg, W, caches, draft, 0.5, "8B")
-        print("8B logits max err %.3e worst err/bound %.2f" % stats["logits"], flush=True)
+        say("8B logits max err %.3e worst err/bound %.2f" % stats["logits"])
         lg = ref[0]["logits"] / shape.temperature
         lse = np.log(np.exp(lg - lg.max(axis=1, keepdims=True)).sum(axis=1)) + lg.max(axis=1)
         lp_ref = lg[np.arange(gamma + 1), tgt[0]] - lse
         a_tol, r_tol = G.TOL["bf16"]
         lp_err = np.abs(lp.cpu().numpy()[0] - lp_ref).max()
-        print("8B teacher-forced log-probabilities max err %.3e" % lp_err, flush=True)
+        say("8B teacher-forced log-probabilities max err %.3e" % lp_err)
         assert lp_err <= 2 * (a_tol + r_tol * np.abs(ref[0]["logits"]).max())
         # top-k verification on the same state: decisions replayed by the oracle's tail on the device's logits
         sj.sj_kv_rewind(gpu.kv, len0.tolist(), pend0.tolist())
@@ -171,8 +174,8 @@ def test_llama8b_batch1_full_size():
             bad, excused = G.replay_matches(shape_T, out_T, draft, 0.5)
             assert not bad and excused == 0, (T, bad, excused)
             cnt = G.decisions_vs_oracle(shape_T, out_T, [ref_T], draft, 0.5)
-            print(f"8B T={T}: accepted {int(out_T['accepted_len'][0])} (oracle {ref_T['accepted_len']}), token "
-                  f"{int(out_T['next_token'][0])} (oracle {ref_T['next_token']}), {cnt}", flush=True)
+            say(f"8B T={T}: accepted {int(out_T['accepted_len'][0])} (oracle {ref_T['accepted_len']}), token "
+                  f"{int(out_T['next_token'][0])} (oracle {ref_T['next_token']}), {cnt}")
             assert cnt["unexcused"] == 0
             assert np.array_equal(out_T["logits"], out["logits"])           # temperature does not touch the forward
         sj.sj_set_temperature(gpu.model, shape.temperature)
@@ -182,7 +185,7 @@ def test_llama8b_batch1_full_size():
         sj.sj_kv_rewind(gpu.kv, len0.tolist(), pend0.tolist())
         out3 = gpu.step(draft, 0.5)
         err3, worst3 = G.close_enough(out3["logits"][0], ref[0]["logits"], shape.dtype, "8B logits, three planes")
-        print("8B logits with three operand planes: max err %.3e worst err/bound %.3f (two planes: %.3f)" % (err3, worst3, stats["logits"][1]), flush=True)
+        say("8B logits with three operand planes: max err %.3e worst err/bound %.3f (two planes: %.3f)" % (err3, worst3, stats["logits"][1]))
         assert worst3 <= stats["logits"][1]
         sj.sj_set_operand_planes(gpu.kv, 2)
     finally:

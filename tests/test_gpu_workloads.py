@@ -12,6 +12,7 @@ import synth
 from oracle import selfjudge_oracle as orc
 from tests import gpu_common as G
 from tests import helpers
+from tests.progress import say
 from tests.test_gpu_bf16 import _compare_step, _fill_caches
 
 pytestmark = pytest.mark.gpu
@@ -28,7 +29,7 @@ def test_verify_head_microbenchmark():
         hidden = synth.make_hidden(shape, seed=0)                       # [R, d] bf16 bits
         draft = synth.make_draft(shape, seed=0)
         hid_dev = torch.from_numpy(hidden.view(np.int16)).to(gpu.dev)
-        print("head step", flush=True)
+        say("head step")
         out = gpu.step(draft, 0.5, gamma, head_hidden=hid_dev)
         h64 = synth.to_f64(hidden)
         logits = np.empty((B * (gamma + 1), V))
@@ -38,7 +39,7 @@ def test_verify_head_microbenchmark():
         logits = logits.reshape(B, gamma + 1, V)
         w, bias = synth.to_f64(src.tensor("judge_w")), float(synth.to_f64(src.tensor("judge_b"))[0])
         err, worst = G.close_enough(out["logits"], logits, "bf16", "head logits")
-        print("head logits max err %.3e (%.3f of the bound)" % (err, worst), flush=True)
+        say("head logits max err %.3e (%.3f of the bound)" % (err, worst))
         n_acc = []
         for b in range(B):
             scores = np.array([orc.judge_score(w, bias, h64[b * (gamma + 1) + j]) for j in range(1, gamma + 1)])
@@ -66,7 +67,7 @@ def test_verify_head_microbenchmark():
 def llama8b():
     shape = synth.CONFIGS[3]
     src = synth.WeightSource(shape, seed=0)
-    print("loading 8B-shaped model", flush=True)
+    say("loading 8B-shaped model")
     model = G.load_model(shape, src)
     yield shape, src, model
     sj.sj_model_free(model)
@@ -83,12 +84,12 @@ def test_llama8b_batch16_ragged(llama8b):
     try:
         cfg = helpers.oracle_config(shape)
         W = helpers.oracle_weights(src, cache_items=0)
-        print("filling caches", lens.tolist(), flush=True)
+        say("filling caches", lens.tolist())
         caches = _fill_caches(shape, gpu, cfg, lens, seed=0, capacity=cap)
         draft = synth.make_draft(shape, seed=0)
-        print("step", flush=True)
+        say("step")
         out, ref, stats = _compare_step(shape, gpu, cfg, W, caches, draft, 0.5, "8B b16")
-        print("8B b16 logits max err %.3e worst err/bound %.2f" % stats["logits"], flush=True)
+        say("8B b16 logits max err %.3e worst err/bound %.2f" % stats["logits"])
     finally:
         sj.sj_kv_free(gpu.kv)
 
@@ -98,7 +99,7 @@ def _llama70b(force_rounding, scale):
     src = synth.WeightSource(shape, seed=0)
     lens = shape.kv_lengths(0)
     cap = [int(l) + 64 for l in lens]
-    print("loading 70B-shaped model", flush=True)
+    say("loading 70B-shaped model")
     gpu = G.Gpu(shape, src, cap)
     try:
         cfg = helpers.oracle_config(shape)
@@ -106,15 +107,15 @@ def _llama70b(force_rounding, scale):
 
         def W(name, layer=-1, rows=None):
             if name == "wq" and layer % 4 == 0:
-                print(f"  oracle layer {layer}/{shape.n_layers}", flush=True)
+                say(f"  oracle layer {layer}/{shape.n_layers}")
             return W0(name, layer, rows)
 
         caches = _fill_caches(shape, gpu, cfg, lens, seed=0, capacity=cap)
         draft = synth.make_draft(shape, seed=0)
-        print("step", flush=True)
+        say("step")
         out, ref, stats = _compare_step(shape, gpu, cfg, W, caches, draft, 0.5, "70B", force_rounding=force_rounding, scale=scale)
-        print("70B %s: logits max err %.3e worst err/bound %.3f" % ("replay on the device's stored rows" if force_rounding else
-                                                                   "against the pure oracle", *stats["logits"]), flush=True)
+        say("70B %s: logits max err %.3e worst err/bound %.3f" % ("replay on the device's stored rows" if force_rounding else
+                                                                   "against the pure oracle", *stats["logits"]))
         return stats
     finally:
         gpu.close()
