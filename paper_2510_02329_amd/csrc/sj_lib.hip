@@ -4,6 +4,7 @@
 #include "sj_kernels.h"
 #include "sj_attn.h"
 #include "sj_gemm_rows.h"
+#include "sj_gemm_ring.h"
 
 #include <algorithm>
 #include <cmath>
@@ -15,6 +16,7 @@
 #include <memory>
 #include <mutex>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 using namespace sj;
@@ -82,7 +84,12 @@ constexpr int FEW_ROWS = 32;
 // multiple of 256 leaves CUs idle for its whole duration: plan_partial takes, among the first tile groupings
 // the kernel is instantiated for, the one that wastes the fewest workgroup slots, every wave keeping at least
 // 8 k-steps; tune_plans then measures that choice against the other shapes on the model's own weights.
+// waves == RING_WAVES selects the LDS-ring kernel (8 compute + 2 loader waves); `depth` is then its ring depth in
+// stages (4 or 8).
 struct GemmPlan { int nt = 4, waves = 4, split = 1, depth = 2; };
+constexpr int RING_WAVES = RING_CW + RING_LW;
+constexpr int RING_ROWS = 16;                  // one MFMA row tile
+constexpr int RING_PACK_ROWS = 8;              // both operand planes in one product
 struct TunedPlans { GemmPlan qkv, o, d, gu, lm; };
 
 struct sj_kv {
@@ -304,6 +311,39 @@ extern "C" int sj_set_temperature(sj_model* m, float temperature) {
 // ------------------------------------------------------------------------------------------------
 // kv / workspace
 
+// Can the LDS-ring kernel run this product in this launch shape?  bf16 with one or two operand planes, one row tile,
+// whole groups of n-tiles, K-slices of whole 8-k-step stages, and at least `depth` stages per workgroup.
+static bool ring_fits(const GemmPlan& p, int ntiles, int ksteps, int rows, int planes, bool bf16) {
+    if (p.waves != RING_WAVES || !bf16 || planes > 2 || rows > RING_ROWS) return false;
+    if (p.nt < 1 || p.split < 1 || ntiles % p.nt || ksteps % (RING_CW * p.split)) return false;
+    const int nstages = ksteps / RING_CW / p.split * p.nt;
+    return (p.depth == 4 || p.depth == 8) && nstages >= p.depth;
+}
+
+// Rule shape of a split-K projection on the LDS-ring kernel (rows <= 8, two planes: the measured case), or waves = 0
+// when no shape fits.  Fewest idle workgroup slots first (256 CUs, one round); among those at least two n-tiles per
+// workgroup (with one, the operand is as much traffic as the weights) and two K-slices, else four, else one, else
+// eight (measured on 4096 x 4096, 4096 x 14336 and 6144 x 4096: the middle of the range wins, and fewer slices are
+// less work for the kernel that adds them).
+static GemmPlan ring_rule_partial(int ntiles, int ksteps) {
+    static const int nts[] = {2, 3, 4, 8, 1}, splits[] = {2, 4, 1, 8};
+    GemmPlan best;
+    best.waves = 0;
+    double best_waste = 1e30;
+    for (int split : splits)
+        for (int nt : nts) {
+            GemmPlan p;
+            p.nt = nt; p.waves = RING_WAVES; p.split = split;
+            const int nstages = (ksteps / RING_CW / split) * nt;
+            p.depth = nstages >= 16 ? 8 : 4;
+            if (!ring_fits(p, ntiles, ksteps, 1, 2, true)) continue;
+            const int wgs = ntiles / nt * split;
+            const double waste = (double)((wgs + 255) / 256 * 256) / wgs + (nt == 1 ? 0.25 : 0.0);
+            if (waste < best_waste - 1e-9) { best = p; best_waste = waste; }
+        }
+    return best;
+}
+
 static GemmPlan plan_partial(int ntiles, int ksteps, bool one_row_tile) {
     static const int cand[3][2] = {{4, 4}, {3, 8}, {6, 4}};
     GemmPlan best;
@@ -345,6 +385,20 @@ static void rule_plans(sj_kv* kv) {
     kv->plan_gu.nt = (2 * F / 16) % 7 == 0 ? 7 : 8;       // whole rounds of workgroups where 7 tiles give them
     kv->plan_gu.waves = 8; kv->plan_gu.split = 1; kv->plan_gu.depth = 2;
     kv->plan_lm = GemmPlan{8, 4, 1, 2};
+    // at most 8 rows with two bf16 planes: the LDS-ring kernel where a shape of it fits (3 - 8 % faster on the
+    // 8B-shaped projections at 6 rows; the start-up measurement may still prefer another shape)
+    if (c.dtype == SJ_DTYPE_BF16 && kv->planes == 2 && kv->max_rows <= RING_PACK_ROWS) {
+        const GemmPlan rq = ring_rule_partial((Nq + 2 * Nk) / 16, d / kstep), ro = ring_rule_partial(d / 16, Nq / kstep),
+                       rd = ring_rule_partial(d / 16, F / kstep);
+        if (rq.waves) kv->plan_qkv[0] = rq;
+        if (ro.waves) kv->plan_o[0] = ro;
+        if (rd.waves) kv->plan_d[0] = rd;
+        GemmPlan g = kv->plan_gu;
+        g.waves = RING_WAVES; g.depth = 8;
+        if (ring_fits(g, 2 * F / 16, d / kstep, 1, 2, true)) kv->plan_gu = g;
+        GemmPlan l{8, RING_WAVES, 1, 4};
+        if (ring_fits(l, c.vocab / 16, d / kstep, 1, 2, true)) kv->plan_lm = l;
+    }
 }
 
 extern "C" int sj_kv_create(const sj_model* m, int32_t batch, const int32_t* capacity, sj_kv** out) {
@@ -688,11 +742,41 @@ static int gemm(hipStream_t st, const void* Wt, const void* X, size_t xplane, in
     return SJ_OK;
 }
 
+// The same product on the LDS-ring kernel (bf16, at most two planes, at most 16 rows; ring_fits has been checked).
+template <typename T, int NT, int EPI, int SPL, int NSA>
+static int gemm_ring(hipStream_t st, const void* Wt, const void* X, size_t xplane, int ldx, int K, int N, int rows, int split,
+                     float* out, void* act, size_t actplane, float4* stats, float inv_temp) {
+    GemmArgs a{};
+    a.Wt = Wt; a.X = X; a.xplane = xplane; a.actplane = actplane;
+    a.ldx = ldx; a.K = K; a.N = N; a.R = rows; a.slice_rows = rows;
+    a.inv_temp = inv_temp;
+    a.out = out; a.stats = stats; a.act = act;
+    const dim3 grid(N / 16 / NT, split);
+    if (SPL == 2 && rows <= RING_PACK_ROWS) gemm_ring_kernel<T, NT, EPI, 2, true, NSA><<<grid, RING_THREADS, 0, st>>>(a);
+    else gemm_ring_kernel<T, NT, EPI, SPL, false, NSA><<<grid, RING_THREADS, 0, st>>>(a);
+    LAUNCHCHK("gemm_ring");
+    return SJ_OK;
+}
+
 // The few-row split-K projection in the launch shape of a plan.  Shapes beyond the first four exist for the
 // default two-plane / one-plane operands only (they are what the start-up measurement may pick).
 template <typename T, int SPL>
 static int few_partial(const GemmPlan& p, hipStream_t st, const void* W, const void* X, size_t xplane, int ldx, int K, int N,
                        int rows, float* out) {
+    if (p.waves == RING_WAVES) {
+        if constexpr (std::is_same<T, bf16_t>::value && SPL <= 2) {
+            if (ring_fits(p, N / 16, K / Traits<T>::KSTEP, rows, SPL, true)) {
+#define SJ_RING(NT, NSA)                                                                                            \
+    if (p.nt == NT && p.depth == NSA)                                                                               \
+        return gemm_ring<T, NT, EPI_PARTIAL, SPL, NSA>(st, W, X, xplane, ldx, K, N, rows, p.split, out, nullptr, 0, nullptr, 0.f);
+                SJ_RING(1, 8) SJ_RING(2, 8) SJ_RING(3, 8) SJ_RING(4, 8) SJ_RING(8, 8)
+                SJ_RING(1, 4) SJ_RING(2, 4) SJ_RING(3, 4) SJ_RING(4, 4)
+#undef SJ_RING
+            }
+        }
+        // more rows than the kernel takes, or a shape that is not instantiated: the register-ring kernel's rule shape
+        return few_partial<T, SPL>(plan_partial(N / 16, K / Traits<T>::KSTEP, true), st, W, X, xplane, ldx, K, N, rows, out);
+    }
 #define SJ_SHAPE(NT, WV, D)                                                                                         \
     if (p.nt == NT && p.waves == WV && p.depth == D)                                                                \
         return gemm<T, NT, EPI_PARTIAL, SPL, WV, D>(st, W, X, xplane, ldx, K, N, rows, p.split, out, nullptr, 0, nullptr, 0.f);
@@ -712,6 +796,20 @@ static int few_partial(const GemmPlan& p, hipStream_t st, const void* W, const v
 template <typename T, int SPL>
 static int few_swiglu(const GemmPlan& p, hipStream_t st, const void* W, const void* X, size_t xplane, int K, int N2, int rows,
                       void* act, size_t actplane) {
+    if (p.waves == RING_WAVES) {
+        if constexpr (std::is_same<T, bf16_t>::value && SPL <= 2) {
+            if (ring_fits(p, N2 / 16, K / Traits<T>::KSTEP, rows, SPL, true)) {
+#define SJ_RING(NT, NSA)                                                                                            \
+    if (p.nt == NT && p.depth == NSA)                                                                               \
+        return gemm_ring<T, NT, EPI_SWIGLU, SPL, NSA>(st, W, X, xplane, K, K, N2, rows, 1, nullptr, act, actplane, nullptr, 0.f);
+                SJ_RING(7, 8) SJ_RING(8, 8) SJ_RING(4, 8) SJ_RING(2, 8) SJ_RING(7, 4) SJ_RING(8, 4) SJ_RING(4, 4)
+#undef SJ_RING
+            }
+        }
+        GemmPlan q;
+        q.nt = (N2 / 16) % 7 == 0 ? 7 : 8; q.waves = 8; q.split = 1; q.depth = 2;
+        return few_swiglu<T, SPL>(q, st, W, X, xplane, K, N2, rows, act, actplane);
+    }
 #define SJ_SHAPE(NT, WV, D)                                                                                         \
     if (p.nt == NT && p.waves == WV && p.depth == D)                                                                \
         return gemm<T, NT, EPI_SWIGLU, SPL, WV, D>(st, W, X, xplane, K, K, N2, rows, 1, nullptr, act, actplane, nullptr, 0.f);
@@ -731,6 +829,23 @@ static int few_swiglu(const GemmPlan& p, hipStream_t st, const void* W, const vo
 template <typename T, int SPL>
 static int few_logits(const GemmPlan& p, hipStream_t st, const void* W, const void* X, size_t xplane, int K, int V, int rows,
                       float* logits, float4* stats, float inv_temp) {
+    if (p.waves == RING_WAVES) {
+        if constexpr (std::is_same<T, bf16_t>::value && SPL <= 2) {
+            if (ring_fits(p, V / 16, K / Traits<T>::KSTEP, rows, SPL, true)) {
+#define SJ_RING(NT, NSA)                                                                                            \
+    if (p.nt == NT && p.depth == NSA)                                                                               \
+        return gemm_ring<T, NT, EPI_LOGITS, SPL, NSA>(st, W, X, xplane, K, K, V, rows, 1, logits, nullptr, 0, stats, inv_temp);
+                SJ_RING(8, 4) SJ_RING(8, 8) SJ_RING(4, 8)
+#undef SJ_RING
+            }
+        }
+        // the statistics are laid out for p.nt tiles per workgroup: only a kernel with the same count may stand in
+        if (p.nt == 8) return few_logits<T, SPL>(GemmPlan{8, 4, 1, 2}, st, W, X, xplane, K, V, rows, logits, stats, inv_temp);
+        if (p.nt == 4) {
+            if constexpr (SPL <= 2) return few_logits<T, SPL>(GemmPlan{4, 8, 1, 2}, st, W, X, xplane, K, V, rows, logits, stats, inv_temp);
+        }
+        return fail(SJ_EINVAL, "internal: no few-row LM-head kernel for %d tiles per workgroup", p.nt);
+    }
 #define SJ_SHAPE(NT, WV)                                                                                            \
     if (p.nt == NT && p.waves == WV)                                                                                \
         return gemm<T, NT, EPI_LOGITS, SPL, WV>(st, W, X, xplane, K, K, V, rows, 1, logits, nullptr, 0, stats, inv_temp);
@@ -814,6 +929,17 @@ static int tune_one(sj_kv* kv, GemmPlan& plan, void* LayerW::*which, const void*
             cands.push_back(p);
         }
     }
+    // the LDS-ring kernel's shapes
+    for (int nt : {1, 2, 3, 4, 8})
+        for (int split = 1; split <= 8; split *= 2)
+            for (int depth : {8, 4}) {
+                GemmPlan p;
+                p.nt = nt; p.waves = RING_WAVES; p.split = split; p.depth = depth;
+                if (!ring_fits(p, ntiles, ksteps, rows, SPL, std::is_same<T, bf16_t>::value)) continue;
+                const long long wgs = (long long)ntiles / nt * split;
+                if (wgs < 128 || wgs > 4096) continue;
+                cands.push_back(p);
+            }
     return pick_plan(plan, cands, time_plan);
 }
 
@@ -848,6 +974,14 @@ static int tune_gate_up(sj_kv* kv, int rows, hipEvent_t e0, hipEvent_t e1) {
         p.nt = nt; p.waves = wv; p.split = 1; p.depth = shapes[i][2];
         cands.push_back(p);
     }
+    for (int nt : {7, 8, 4, 2})
+        for (int depth : {8, 4}) {
+            GemmPlan p;
+            p.nt = nt; p.waves = RING_WAVES; p.split = 1; p.depth = depth;
+            if (nt == 2 && depth == 4) continue;                 // not instantiated
+            if (!ring_fits(p, ntiles, d / Traits<T>::KSTEP, rows, SPL, std::is_same<T, bf16_t>::value) || ntiles / nt < 128) continue;
+            cands.push_back(p);
+        }
     return pick_plan(kv->plan_gu, cands, time_plan);
 }
 
@@ -880,6 +1014,12 @@ static int tune_lm_head(sj_kv* kv, int rows, hipEvent_t e0, hipEvent_t e1) {
         GemmPlan p;
         p.nt = nt; p.waves = wv; p.split = 1; p.depth = 2;
         cands.push_back(p);
+    }
+    static const int ring_shapes[][2] = {{8, 4}, {8, 8}, {4, 8}};
+    for (const auto& rs : ring_shapes) {
+        GemmPlan p;
+        p.nt = rs[0]; p.waves = RING_WAVES; p.split = 1; p.depth = rs[1];
+        if (ring_fits(p, V / 16, d / Traits<T>::KSTEP, rows, SPL, std::is_same<T, bf16_t>::value)) cands.push_back(p);
     }
     return pick_plan(kv->plan_lm, cands, time_plan);
 }
