@@ -480,7 +480,7 @@ def main() -> int:
         "step_hbm": {"algorithmic_bytes": ab["total"], "achieved_gbps": round(step_gbps, 1),
                      "frac_of_8TBps": round(step_gbps / HBM_PEAK_GBPS, 4),
                      "frac_of_copy_ceiling": round(step_gbps / ceiling, 4)},
-        "roofline": {"kernel": ("gemm_skinny" if B * (gamma + 1) <= 32 else "gemm_rows4") + " (gate/up projection + SwiGLU epilogue)", "bound": "hbm",
+        "roofline": {"kernel": "gate/up projection + SwiGLU epilogue, " + sj.sj_kernel_class_shape(kv, 3, B * (gamma + 1)), "bound": "hbm",
                      "achieved": round(k_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(k_gbps / HBM_PEAK_GBPS, 4), "frac_of_copy_ceiling": round(k_gbps / ceiling, 4),
                      "traffic": traffic, "traffic_source": traffic_source,

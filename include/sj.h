@@ -258,6 +258,10 @@ int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class);
  * returns the elapsed time between two HIP events around the whole series.  Synchronises `stream`. */
 int sj_time_kernel_class(sj_model* m, sj_kv* kv, int32_t kernel_class, int32_t launches, void* stream, double* total_ms);
 int sj_get_kernel_timing(sj_kv* kv, double* total_ms, int64_t* launches);
+/* Writes into buf (host, buf_len bytes, always terminated) the name and launch shape of the kernel that a step of
+ * `rows` = batch * (gamma + 1) rows on this cache object uses for kernel class 1..5 (as above): the shape comes from
+ * the rule or from the start-up measurement, so a report of a timing can say what was timed. */
+int sj_kernel_class_shape(const sj_kv* kv, int32_t kernel_class, int32_t rows, char* buf, int32_t buf_len);
 
 /* bf16 models only: how many bf16 planes carry the fp32 activations (the few-row operand of every
  * matrix product) into the matrix cores.  1 = activations rounded to bf16 at each product

@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
         "sj_kv_rewind": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
         "sj_set_kernel_timing": (C.c_int, [vp, i32]),
         "sj_get_kernel_timing": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+        "sj_kernel_class_shape": (C.c_int, [vp, C.c_int32, C.c_int32, C.c_char_p, C.c_int32]),
         "sj_time_kernel_class": (C.c_int, [vp, vp, i32, i32, vp, C.POINTER(C.c_double)]),
         "sj_debug_fetch": (C.c_int, [vp, i32, vp, sz]),
         "sj_last_error": (C.c_char_p, []),
@@ -269,6 +270,12 @@ def sj_kv_rewind(kv: int, lengths: Sequence[int], pending: Sequence[int], stream
 
 def sj_set_kernel_timing(kv: int, kernel_class: int) -> None:
     _check(load_library().sj_set_kernel_timing(kv, kernel_class))
+
+
+def sj_kernel_class_shape(kv: int, kernel_class: int, rows: int) -> str:
+    buf = C.create_string_buffer(256)
+    _check(load_library().sj_kernel_class_shape(kv, kernel_class, rows, buf, 256))
+    return buf.value.decode()
 
 
 def sj_get_kernel_timing(kv: int):

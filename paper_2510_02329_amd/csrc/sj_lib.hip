@@ -565,6 +565,30 @@ extern "C" int sj_set_kernel_timing(sj_kv* kv, int32_t kernel_class) {
     return SJ_OK;
 }
 
+extern "C" int sj_kernel_class_shape(const sj_kv* kv, int32_t kernel_class, int32_t rows, char* buf, int32_t buf_len) {
+    if (!kv || !buf || buf_len < 1) return fail(SJ_EINVAL, "kv / buf is null");
+    if (kernel_class < 1 || kernel_class > 5) return fail(SJ_EINVAL, "kernel_class must be in 1..5");
+    if (rows < 1) return fail(SJ_EINVAL, "rows must be positive");
+    if (rows > FEW_ROWS) {
+        const GemmPlan* p = kernel_class == 1 ? &kv->plan_qkv[1] : kernel_class == 2 ? &kv->plan_o[1] : kernel_class == 4 ? &kv->plan_d[1] : nullptr;
+        snprintf(buf, (size_t)buf_len, "gemm_rows%s: row groups of 144 in one launch, 8 or 7 n-tiles per workgroup, %d K-slice(s)",
+                 kv->planes == 3 ? "2" : "4", p ? p->split : 1);
+        return SJ_OK;
+    }
+    const GemmPlan& p = kernel_class == 1 ? kv->plan_qkv[0] : kernel_class == 2 ? kv->plan_o[0] : kernel_class == 3 ? kv->plan_gu
+                        : kernel_class == 4 ? kv->plan_d[0] : kv->plan_lm;
+    const bool ring = p.waves == RING_WAVES && rows <= RING_ROWS && kv->planes <= 2 && kv->m->cfg.dtype == SJ_DTYPE_BF16;
+    if (ring)
+        snprintf(buf, (size_t)buf_len, "gemm_ring: %d n-tiles per workgroup, 8 compute + 2 loader waves, %d K-slice(s), LDS ring of %d stages",
+                 p.nt, p.split, p.depth);
+    else if (p.waves == RING_WAVES)
+        snprintf(buf, (size_t)buf_len, "gemm_skinny: rule shape (the LDS-ring plan does not take %d rows)", rows);
+    else
+        snprintf(buf, (size_t)buf_len, "gemm_skinny: %d n-tiles x %d waves per workgroup, %d K-slice(s), register ring of %d", p.nt, p.waves,
+                 p.split, p.depth);
+    return SJ_OK;
+}
+
 extern "C" int sj_get_kernel_timing(sj_kv* kv, double* total_ms, int64_t* launches) {
     if (!kv || !total_ms || !launches) return fail(SJ_EINVAL, "null argument");
     HIPCHK(hipDeviceSynchronize());
