@@ -387,7 +387,11 @@ static void rule_plans(sj_kv* kv) {
     kv->plan_lm = GemmPlan{8, 4, 1, 2};
     // at most 8 rows with two bf16 planes: the LDS-ring kernel where a shape of it fits (3 - 8 % faster on the
     // 8B-shaped projections at 6 rows; the start-up measurement may still prefer another shape)
-    if (c.dtype == SJ_DTYPE_BF16 && kv->planes == 2 && kv->max_rows <= RING_PACK_ROWS) {
+    // (SJ_RING_ROWS = 0..16 moves the row limit of this rule; from 9 rows on, and with one plane, the kernel takes one
+    // product per plane and measures equal to the register-ring kernel)
+    int ring_rows = RING_PACK_ROWS;
+    if (const char* e = std::getenv("SJ_RING_ROWS")) ring_rows = std::min(std::max(std::atoi(e), 0), RING_ROWS);
+    if (c.dtype == SJ_DTYPE_BF16 && kv->planes <= 2 && kv->max_rows <= ring_rows) {
         const GemmPlan rq = ring_rule_partial((Nq + 2 * Nk) / 16, d / kstep), ro = ring_rule_partial(d / 16, Nq / kstep),
                        rd = ring_rule_partial(d / 16, F / kstep);
         if (rq.waves) kv->plan_qkv[0] = rq;

@@ -245,3 +245,40 @@ def test_three_plane_operand_is_closer_than_one():
             gpu.close()
     assert errs[3] < errs[2] < errs[1], errs
     assert errs[3] < 1e-4 and errs[1] > 10 * errs[2], errs
+
+
+RING = synth.ModelShape("ring_bf16", "bf16", 2, 512, 8, 2, 128, 1536, 4992, 10000.0, batch=1, gamma=3, weight_std=0.06)
+
+
+@pytest.mark.parametrize("gamma,planes", [(3, 2), (7, 2), (8, 2), (15, 2), (5, 1)])
+def test_lds_ring_projections(gamma, planes, monkeypatch):
+    """Every projection of this shape fits the LDS-ring kernel.  Up to 8 rows both operand planes ride in one product,
+    from 9 rows on (and with a single plane) there is one product per plane: both layouts against the oracle and
+    against the register-ring kernel on the same inputs.  SJ_TUNE=0 pins the rule's launch shapes; SJ_RING_ROWS moves
+    the row limit of the rule (16: ring everywhere, 0: never)."""
+    shape = RING.scaled(gamma=gamma)
+    draft = synth.make_draft(shape, seed=gamma)
+    logits = {}
+    for ring_rows in (16, 0):
+        monkeypatch.setenv("SJ_TUNE", "0")
+        monkeypatch.setenv("SJ_RING_ROWS", str(ring_rows))
+        gpu, cfg, W, caches = _setup(shape, [150], max_gamma=15)
+        try:
+            if planes != 2:
+                sj.sj_set_operand_planes(gpu.kv, planes)
+            names = [sj.sj_kernel_class_shape(gpu.kv, c, gamma + 1) for c in (1, 2, 3, 4, 5)]
+            assert all(n.startswith("gemm_ring" if ring_rows else "gemm_skinny") for n in names), names
+            out = gpu.step(draft, 0.5, gamma)
+            logits[ring_rows] = out["logits"][0].copy()
+            if planes == 2:
+                ref = _oracle(cfg, W, caches, draft, 0.5)
+                G.close_enough(out["logits"][0], ref[0]["logits"], "bf16", f"logits, ring rows {ring_rows}")
+                _same_decisions(out, ref, 1)
+        finally:
+            gpu.close()
+    # the two kernels add in different orders; with a single plane every product input is then rounded to bf16 (2^-9),
+    # so last-bit differences of an fp32 sum surface as whole bf16 ulps further on
+    diff = np.abs(logits[16] - logits[0])
+    abs_tol, rel_tol = (5e-3, 1e-2) if planes == 2 else (5e-2, 5e-2)
+    print(f"ring vs register-ring kernel, {planes} plane(s), {gamma + 1} rows: max |diff| {float(diff.max()):.3e}")
+    assert (diff <= abs_tol + rel_tol * np.abs(logits[0])).all(), float(diff.max())
