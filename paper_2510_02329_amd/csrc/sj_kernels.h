@@ -354,12 +354,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmArgs a) {
 // ---------------------------------------------------------------------------------------------
 // Vocabulary softmax statistics of each row from the LM-head workgroups' partials:
 // row max, Z = sum exp((l - max)/T), lowest-index arg-max.  One workgroup per row.
-__global__ __launch_bounds__(256) void softmax_merge_kernel(const float4* __restrict__ stats, int nblk, float inv_temp,
-                                                            float4* __restrict__ rowstat) {
+__device__ __forceinline__ void softmax_merge_row(int r, const float4* __restrict__ stats, int nblk, float inv_temp,
+                                                  float4* __restrict__ rowstat) {
     __shared__ float smx[4];
     __shared__ int sarg[4];
     __shared__ float red[4];
-    const int r = blockIdx.x;
     const float4* s = stats + (size_t)r * nblk;
     float mx = -INFINITY;
     int arg = 0x7fffffff;
@@ -389,6 +388,11 @@ __global__ __launch_bounds__(256) void softmax_merge_kernel(const float4* __rest
     if (threadIdx.x == 0) rowstat[r] = float4{mx, z, __int_as_float(arg), 0.f};
 }
 
+__global__ __launch_bounds__(256) void softmax_merge_kernel(const float4* __restrict__ stats, int nblk, float inv_temp,
+                                                            float4* __restrict__ rowstat) {
+    softmax_merge_row(blockIdx.x, stats, nblk, inv_temp, rowstat);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Judge verifier (Eq. 5): score = sigmoid(w . h + b) on the final, normed hidden state of the row
 // whose input is the draft token.  One workgroup per (sequence, draft position); entry j scores
@@ -396,14 +400,14 @@ __global__ __launch_bounds__(256) void softmax_merge_kernel(const float4* __rest
 // In the top-k mode (the relaxed baseline of Sec. 4.1) the workgroup also ranks d_{j+1} in the target's
 // row j: the number of vocabulary entries with a larger logit, or an equal one at a lower index.
 template <typename T>
-__global__ __launch_bounds__(256) void judge_kernel(const StepParams* __restrict__ sp, int d,
-                                                    const float* __restrict__ hn32, const float* __restrict__ row_scale,
-                                                    const T* __restrict__ w, const T* __restrict__ bias,
-                                                    float* __restrict__ scores, int V, const float* __restrict__ logits,
-                                                    int32_t* __restrict__ ranks) {
+__device__ __forceinline__ void judge_token(int blk, const StepParams* __restrict__ sp, int d,
+                                            const float* __restrict__ hn32, const float* __restrict__ row_scale,
+                                            const T* __restrict__ w, const T* __restrict__ bias,
+                                            float* __restrict__ scores, int V, const float* __restrict__ logits,
+                                            int32_t* __restrict__ ranks) {
     __shared__ float red[4];
     const int gamma = sp->gamma;
-    const int bi = blockIdx.x / gamma, j = blockIdx.x % gamma;
+    const int bi = blk / gamma, j = blk % gamma;
     const int row = bi * (gamma + 1) + j + 1;
     if (sp->mode == 3) {                                   // uniform for the launch
         const float* l = logits + (size_t)(row - 1) * V;
@@ -416,7 +420,7 @@ __global__ __launch_bounds__(256) void judge_kernel(const StepParams* __restrict
                    (v.z > ref || (v.z == ref && c + 2 < tok)) + (v.w > ref || (v.w == ref && c + 3 < tok));
         }
         const float total = block_sum_256((float)cnt, red);   // exact: counts stay below 2^24
-        if (threadIdx.x == 0) ranks[blockIdx.x] = (int)total;
+        if (threadIdx.x == 0) ranks[blk] = (int)total;
         __syncthreads();
     }
     const float* h = hn32 + (size_t)row * d;
@@ -426,21 +430,41 @@ __global__ __launch_bounds__(256) void judge_kernel(const StepParams* __restrict
     if (threadIdx.x == 0) {
         // row_scale: the hidden state was stored without its 1/rms factor (applied here)
         const float z = acc * (row_scale ? row_scale[row] : 1.0f) + Traits<T>::load(bias);
-        scores[blockIdx.x] = 1.0f / (1.0f + expf(-z));
+        scores[blk] = 1.0f / (1.0f + expf(-z));
     }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void judge_kernel(const StepParams* __restrict__ sp, int d,
+                                                    const float* __restrict__ hn32, const float* __restrict__ row_scale,
+                                                    const T* __restrict__ w, const T* __restrict__ bias,
+                                                    float* __restrict__ scores, int V, const float* __restrict__ logits,
+                                                    int32_t* __restrict__ ranks) {
+    judge_token<T>(blockIdx.x, sp, d, hn32, row_scale, w, bias, scores, V, logits, ranks);
+}
+
+// The two of them in one launch (they do not depend on each other: the judge reads hidden states, and in the top-k
+// mode raw logits): workgroups [0, R) merge the softmax statistics of a row, the others score one draft token each.
+template <typename T>
+__global__ __launch_bounds__(256) void merge_judge_kernel(int R, const float4* __restrict__ stats, int nblk, float inv_temp,
+                                                          float4* __restrict__ rowstat, const StepParams* __restrict__ sp, int d,
+                                                          const float* __restrict__ hn32, const T* __restrict__ w,
+                                                          const T* __restrict__ bias, float* __restrict__ scores, int V,
+                                                          const float* __restrict__ logits, int32_t* __restrict__ ranks) {
+    if ((int)blockIdx.x < R) softmax_merge_row(blockIdx.x, stats, nblk, inv_temp, rowstat);
+    else judge_token<T>(blockIdx.x - R, sp, d, hn32, nullptr, w, bias, scores, V, logits, ranks);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Ratio test (Eq. 3), OR with the judge (Sec. 3.2), first-rejection scan (Sec. 3.1): one wave per
 // sequence, lane j handles draft d_{j+1}:  accept iff u*q(d) < p(d)  with p(d) read from block row j,
 // or score > theta.  accepted_len = number of leading accepted lanes (ballot + count trailing ones).
-__global__ __launch_bounds__(64) void accept_scan_kernel(const StepParams* __restrict__ sp, int V, float inv_temp,
-                                                         const float* __restrict__ logits,
-                                                         const float4* __restrict__ rowstat,
-                                                         const float* __restrict__ scores,
-                                                         float* __restrict__ p_at_d, int32_t* __restrict__ bits,
-                                                         int32_t* __restrict__ nacc, const int32_t* __restrict__ ranks) {
-    const int bi = blockIdx.x, j = threadIdx.x;
+// One wave, lane j; returns accepted_len to every lane; `write` says whether this wave stores the results.
+__device__ __forceinline__ int accept_scan_seq(int bi, int j, bool write, const StepParams* __restrict__ sp, int V, float inv_temp,
+                                               const float* __restrict__ logits, const float4* __restrict__ rowstat,
+                                               const float* __restrict__ scores, float* __restrict__ p_at_d,
+                                               int32_t* __restrict__ bits, int32_t* __restrict__ nacc,
+                                               const int32_t* __restrict__ ranks) {
     const int gamma = sp->gamma;
     bool ok = false;
     if (j < gamma) {
@@ -457,15 +481,27 @@ __global__ __launch_bounds__(64) void accept_scan_kernel(const StepParams* __res
         const bool jd = scores[bi * gamma + j] > sp->theta;
         const bool tk = (sp->mode == 3) && ranks[bi * gamma + j] < sp->topk;
         ok = (sp->mode == 1) ? a : (sp->mode == 2) ? jd : (sp->mode == 3) ? tk : (a || jd);
-        p_at_d[bi * gamma + j] = p;
-        bits[bi * gamma + j] = (a ? 1 : 0) | (jd ? 2 : 0) | (tk ? 4 : 0);
+        if (write) {
+            p_at_d[bi * gamma + j] = p;
+            bits[bi * gamma + j] = (a ? 1 : 0) | (jd ? 2 : 0) | (tk ? 4 : 0);
+        }
     }
     const unsigned long long mask = __ballot(ok);
-    if (j == 0) {
-        const int n = __builtin_ctzll(~mask);      // lanes >= gamma vote false, so n <= gamma
+    const int n = __builtin_ctzll(~mask);          // lanes >= gamma vote false, so n <= gamma
+    if (write && j == 0) {
         nacc[bi] = n;
         sp->accepted_len[bi] = n;
     }
+    return n;
+}
+
+__global__ __launch_bounds__(64) void accept_scan_kernel(const StepParams* __restrict__ sp, int V, float inv_temp,
+                                                         const float* __restrict__ logits,
+                                                         const float4* __restrict__ rowstat,
+                                                         const float* __restrict__ scores,
+                                                         float* __restrict__ p_at_d, int32_t* __restrict__ bits,
+                                                         int32_t* __restrict__ nacc, const int32_t* __restrict__ ranks) {
+    accept_scan_seq(blockIdx.x, threadIdx.x, true, sp, V, inv_temp, logits, rowstat, scores, p_at_d, bits, nacc, ranks);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -492,10 +528,11 @@ __device__ __forceinline__ double e_of(float logit, float mx, float inv_temp) {
     return exp(((double)logit - (double)mx) * (double)inv_temp);
 }
 
-__global__ __launch_bounds__(256) void resample_e_kernel(const StepParams* __restrict__ sp, ResampleArgs a) {
+// pass 1 of the draw for the row after `n` accepted tokens
+__device__ __forceinline__ void resample_e_slab(const StepParams* __restrict__ sp, const ResampleArgs& a, int n) {
     const int bi = blockIdx.y, slab = blockIdx.x * 256 + threadIdx.x;
     const int gamma = sp->gamma;
-    const int row = bi * (gamma + 1) + a.nacc[bi];
+    const int row = bi * (gamma + 1) + n;
     const float mx = a.rowstat[row].x;
     const float* l = a.logits + (size_t)row * a.V;
     const int k0 = slab * a.slab_len, k1 = min(a.V, k0 + a.slab_len);
@@ -512,6 +549,27 @@ __global__ __launch_bounds__(256) void resample_e_kernel(const StepParams* __res
         for (int k = k0; k < k1; ++k) s += e_of(l[k], mx, a.inv_temp);
     }
     a.epart[(size_t)bi * a.nslab + slab] = s;
+}
+
+__global__ __launch_bounds__(256) void resample_e_kernel(const StepParams* __restrict__ sp, ResampleArgs a) {
+    resample_e_slab(sp, a, a.nacc[blockIdx.y]);
+}
+
+// Scan and pass 1 in one launch: pass 1 only needs accepted_len to know its row, and the scan is a handful of loads,
+// so the first wave of EVERY workgroup repeats it for the workgroup's sequence (same inputs, same arithmetic, same
+// result) and the workgroups with blockIdx.x == 0 store it.
+__global__ __launch_bounds__(256) void scan_resample_e_kernel(const StepParams* __restrict__ sp, ResampleArgs a,
+                                                              const float* __restrict__ scores, float* __restrict__ p_at_d,
+                                                              int32_t* __restrict__ bits, int32_t* __restrict__ nacc,
+                                                              const int32_t* __restrict__ ranks) {
+    __shared__ int n_sh;
+    if (threadIdx.x < 64) {
+        const int n = accept_scan_seq(blockIdx.y, threadIdx.x, blockIdx.x == 0, sp, a.V, a.inv_temp, a.logits, a.rowstat, scores,
+                                      p_at_d, bits, nacc, ranks);
+        if (threadIdx.x == 0) n_sh = n;
+    }
+    __syncthreads();
+    resample_e_slab(sp, a, n_sh);
 }
 
 // sum of n slab sums by a 256-thread block: 8 independent loads per thread and batch (index clamped,

@@ -1271,35 +1271,46 @@ struct Runner {
         }
         return rc;
     }
-    int lm_head(bool exact_operand) {
+    // judge_gamma > 0: the judge scores of the gamma draft tokens per sequence (Eq. 5) are computed by the same launch
+    // that merges the softmax statistics (tail() is then told that they exist)
+    int lm_head(bool exact_operand, int judge_gamma = 0) {
         int nblk = 0;
         const int rc = lm_gemm(exact_operand, nblk);
         if (rc) return rc;
-        softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, m->md.inv_temp, kv->rowstat);
-        LAUNCHCHK("softmax_merge");
+        const ModelDims& md = m->md;
+        if (judge_gamma > 0) {
+            merge_judge_kernel<T><<<R + nseq * judge_gamma, 256, 0, st>>>(R, kv->stats, nblk, md.inv_temp, kv->rowstat, kv->sp_dev, md.d, kv->hn32,
+                                                                          (const T*)m->judge_w, (const T*)m->judge_b, kv->scores, md.V,
+                                                                          kv->logits, kv->ranks);
+            LAUNCHCHK("merge_judge");
+        } else {
+            softmax_merge_kernel<<<R, 256, 0, st>>>(kv->stats, nblk, md.inv_temp, kv->rowstat);
+            LAUNCHCHK("softmax_merge");
+        }
         return SJ_OK;
     }
 
     // Eq. 3, Eq. 5, scan, extra token, state commit
-    int tail(int gamma, const float* row_scale = nullptr) {
+    int tail(int gamma, bool judged) {
         const ModelDims& md = m->md;
-        if (gamma > 0) {                                   // gamma = 0: a plain decode step (draft proposal)
-            judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, row_scale, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores,
+        if (gamma > 0 && !judged) {                        // gamma = 0: a plain decode step (draft proposal)
+            judge_kernel<T><<<nseq * gamma, 256, 0, st>>>(kv->sp_dev, md.d, kv->hn32, nullptr, (const T*)m->judge_w, (const T*)m->judge_b, kv->scores,
                                                              md.V, kv->logits, kv->ranks);
             LAUNCHCHK("judge");
         }
-        accept_scan_kernel<<<nseq, 64, 0, st>>>(kv->sp_dev, md.V, md.inv_temp, kv->logits, kv->rowstat, kv->scores, kv->p_at_d,
-                                                 kv->bits, kv->nacc, kv->ranks);
-        LAUNCHCHK("accept_scan");
         ResampleArgs ra{};
         ra.V = md.V; ra.nslab = kv->nslab; ra.slab_len = kv->slab_len; ra.inv_temp = md.inv_temp;
         ra.logits = kv->logits; ra.rowstat = kv->rowstat; ra.nacc = kv->nacc; ra.epart = kv->epart; ra.wpart = kv->wpart;
         if (md.inv_temp > 0.f) {
             dim3 g(kv->nslab / 256, nseq);
-            resample_e_kernel<<<g, 256, 0, st>>>(kv->sp_dev, ra);
-            LAUNCHCHK("resample_e");
+            scan_resample_e_kernel<<<g, 256, 0, st>>>(kv->sp_dev, ra, kv->scores, kv->p_at_d, kv->bits, kv->nacc, kv->ranks);
+            LAUNCHCHK("scan_resample_e");
             resample_w_kernel<<<g, 256, 0, st>>>(kv->sp_dev, ra);
             LAUNCHCHK("resample_w");
+        } else {
+            accept_scan_kernel<<<nseq, 64, 0, st>>>(kv->sp_dev, md.V, md.inv_temp, kv->logits, kv->rowstat, kv->scores, kv->p_at_d,
+                                                     kv->bits, kv->nacc, kv->ranks);
+            LAUNCHCHK("accept_scan");
         }
         resample_pick_kernel<<<nseq, 256, 0, st>>>(kv->sp_dev, ra, kv->len_dev, kv->pending_dev);
         LAUNCHCHK("resample_pick");
@@ -1323,8 +1334,8 @@ static int enqueue_step(sj_model* m, sj_kv* kv, int gamma, hipStream_t st, bool 
     } else {
         if ((rc = run.layers())) return rc;
     }
-    if ((rc = run.lm_head(head_only))) return rc;
-    return run.tail(gamma);
+    if ((rc = run.lm_head(head_only, gamma))) return rc;
+    return run.tail(gamma, gamma > 0);
 }
 
 // The full step is ~200 dependent launches of a few microseconds each: it is captured once per
