@@ -67,7 +67,7 @@ struct AttnSmem {
 // floats per published partial of one workgroup
 template <int HD, int MQ> constexpr int attn_partial_floats() { return (HD / 16 * MQ * 4 + 2 * MQ) * 64; }
 
-template <typename T, int HD, int MQ, int SPL>
+template <typename T, int HD, int MQ, int SPL, int PB = 4>
 __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __restrict__ sp, ModelDims md,
                                                          const float* __restrict__ part, int nparts, int R,
                                                          const float* __restrict__ cs, KvView<T> kv, int layer,
@@ -81,6 +81,9 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
     constexpr int HT = HD / 16, HALF = HD / 2, NSLOT = HT * MQ * 4;
     constexpr int NG = MQ * KK / 2;  // query fragment groups: (q tile, pair of head-dim steps kk, kk + KK/2)
     constexpr int HPW = HT / 4;      // head tiles per wave in the merges: wave w takes tiles w, w + 4, ..
+    // PB = split-K partials of the QKV product fetched per batch of independent loads.  With at most two partials a
+    // batch of four only repeats loads: they fill the wave's load queue ahead of the K / V requests (64 entries; query
+    // fragments + own rows + one key step came to 72) and cost 1.2 us of the 14.5 us launch at batch 1.
     __shared__ AttnSmem<T, HD, MQ, SPL> sm;
 
     const int chunk = blockIdx.x, kvh = blockIdx.y % md.Hkv, qg = blockIdx.y / md.Hkv, bi = blockIdx.z;
@@ -119,7 +122,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
     load_keys(0, min(key_lo, cap - KSTEP));            // capacities are multiples of 64: always inside
 
     // query fragment group gq = (q tile mq, head-dim step kk): 4 split-K partials per batch of loads
-    float4 qa[4][KF / 4], qc[4][KF / 4];
+    float4 qa[PB][KF / 4], qc[PB][KF / 4];
     auto q_row = [&](int gq, int& row, int& head, bool& valid) {
         const int mq = gq / (KK / 2);
         const int m = (qg * MQ + mq) * 16 + r;
@@ -134,7 +137,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
         const int i0 = (gq % (KK / 2)) * KSTEP + g * KF;
         const int off0 = row * N + head * HD + i0;     // the partials hold fewer than 2^31 elements
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < PB; ++u) {
             const float* pl = part + (off0 + min(s0 + u, nparts - 1) * R * N);
 #pragma unroll
             for (int e = 0; e < KF / 4; ++e) {
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
     // and batch (one batch covers 8 rows of head dimension 128), 4 split-K partials of both columns each
     constexpr int NB = 4;
     const int nr_total = rps * HD;
-    float nlo[NB][4], nhi[NB][4], ncs[NB][2];
+    float nlo[NB][PB], nhi[NB][PB], ncs[NB][2];
     auto nr_item = [&](int it, int& j, int& i, bool& isv) {
         j = it / HD;
         const int w = it % HD;
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
             const int row = bi * rps + j, col = (isv ? Nq + Nk : Nq) + kvh * HD + i;
             const int off0 = row * N + col;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
+            for (int v = 0; v < PB; ++v) {
                 const float* pl = part + (off0 + min(s0 + v, nparts - 1) * R * N);
                 nlo[u][v] = pl[0];
                 nhi[u][v] = pl[HALF];
@@ -181,10 +184,10 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
         float lo[KF], hi[KF];
 #pragma unroll
         for (int e = 0; e < KF; ++e) { lo[e] = 0.f; hi[e] = 0.f; }
-        for (int s0 = 0; s0 < nparts; s0 += 4) {
+        for (int s0 = 0; s0 < nparts; s0 += PB) {
             if (gq != wave || s0 != 0) q_issue(gq, s0);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < PB; ++u) {
                 const float wgt = (s0 + u < nparts) ? 1.f : 0.f;
 #pragma unroll
                 for (int e = 0; e < KF / 4; ++e) {
@@ -220,12 +223,12 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const StepParams* __res
             float lo[NB], hi[NB];
 #pragma unroll
             for (int u = 0; u < NB; ++u) { lo[u] = 0.f; hi[u] = 0.f; }
-            for (int s0 = 0; s0 < nparts; s0 += 4) {
+            for (int s0 = 0; s0 < nparts; s0 += PB) {
                 if (base != 0 || s0 != 0) nr_issue(base, s0);
 #pragma unroll
                 for (int u = 0; u < NB; ++u)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
+                    for (int v = 0; v < PB; ++v) {
                         const float wgt = (s0 + v < nparts) ? 1.f : 0.f;
                         lo[u] += wgt * nlo[u][v];
                         hi[u] += wgt * nhi[u][v];

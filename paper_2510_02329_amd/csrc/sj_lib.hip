@@ -1200,16 +1200,20 @@ struct Runner {
         const int mq = small ? 1 : std::min(mtiles, 4);
         const int qgroups = (mtiles + mq - 1) / mq;
         dim3 grid(kv->nchunk_max, md.Hkv * qgroups, nseq);
+        const bool pb2 = nparts(kv->plan_qkv) <= 2;        // at most two QKV partials: fetch them two at a time
+#define ATTN_PB(HD, MQ, PB)                                                                                            \
+    attn_fused_kernel<T, HD, MQ, SPL, PB><<<grid, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->plan_qkv), R, kv->cs, view(), \
+                                                                layer, kv->chunk_keys, kv->nchunk_max, kv->opart, kv->tickets,  \
+                                                                (T*)kv->attn_out, plane(md.Hq * md.hd), tks(md.Hq * md.hd))
 #define ATTN(HD, MQ)                                                                                                   \
-    attn_fused_kernel<T, HD, MQ, SPL><<<grid, 256, 0, st>>>(kv->sp_dev, md, kv->part, nparts(kv->plan_qkv), R, kv->cs, view(), \
-                                                            layer, kv->chunk_keys, kv->nchunk_max, kv->opart, kv->tickets,      \
-                                                            (T*)kv->attn_out, plane(md.Hq * md.hd), tks(md.Hq * md.hd))
+    do { if (pb2) ATTN_PB(HD, MQ, 2); else ATTN_PB(HD, MQ, 4); } while (0)
         if (md.hd == 128) {
             switch (mq) { case 1: ATTN(128, 1); break; case 2: ATTN(128, 2); break; case 3: ATTN(128, 3); break; default: ATTN(128, 4); }
         } else {
             switch (mq) { case 1: ATTN(64, 1); break; case 2: ATTN(64, 2); break; case 3: ATTN(64, 3); break; default: ATTN(64, 4); }
         }
 #undef ATTN
+#undef ATTN_PB
         LAUNCHCHK("attn_fused");
         return SJ_OK;
     }
