@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void step_begin_kernel(const StepParams* __res
 // Residual add + RMSNorm.  x[r] += sum_s part[s][r] (fixed order), then
 // xn[r] = x[r] * gain / sqrt(mean(x[r]^2) + eps) as the next GEMM's operand (three planes in bf16),
 // optionally also in fp32 (final hidden state for the judge, Eq. 4).
-template <typename T>
+template <typename T, int PB = 8>
 __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(int R, int d, float eps, float* __restrict__ x,
                                                            const float* __restrict__ part, int nparts,
                                                            const T* __restrict__ gain, T* __restrict__ xn,
@@ -141,14 +141,14 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(int R, int d, float e
         v[p] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (c < d) {
             v[p] = *reinterpret_cast<const f32x4*>(xr + c);
-            // partials in batches of 8 independent loads (index clamped, surplus ignored), added in order
-            for (int s0 = 0; s0 < nparts; s0 += 8) {
-                f32x4 t[8];
+            // partials in batches of PB independent loads (index clamped, surplus ignored), added in order
+            for (int s0 = 0; s0 < nparts; s0 += PB) {
+                f32x4 t[PB];
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
+                for (int u = 0; u < PB; ++u)
                     t[u] = *reinterpret_cast<const f32x4*>(part + ((size_t)min(s0 + u, nparts - 1) * R + r) * d + c);
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
+                for (int u = 0; u < PB; ++u)
                     if (s0 + u < nparts) v[p] += t[u];
             }
             if (nparts) *reinterpret_cast<f32x4*>(xr + c) = v[p];

@@ -1218,6 +1218,16 @@ struct Runner {
         return SJ_OK;
     }
 
+    // residual add of `parts` pending split-K partials + RMSNorm into the operand planes (at most two partials: a
+    // two-wide batch of loads instead of an eight-wide one that mostly repeats them)
+    void norm(int parts, const void* gain, float* xn32) {
+        const int d = m->md.d;
+        if (parts <= 2)
+            add_rmsnorm_kernel<T, 2><<<R, 1024, 0, st>>>(R, d, m->md.eps, kv->x, kv->part, parts, (const T*)gain, (T*)kv->xn, plane(d), xn32, tks(d));
+        else
+            add_rmsnorm_kernel<T, 8><<<R, 1024, 0, st>>>(R, d, m->md.eps, kv->x, kv->part, parts, (const T*)gain, (T*)kv->xn, plane(d), xn32, tks(d));
+    }
+
     // decoder layers (Eq. 2 / Eq. 4): leaves the last down-projection partials pending in kv->part
     int layers() {
         const ModelDims& md = m->md;
@@ -1230,8 +1240,7 @@ struct Runner {
         int rc;
         for (int l = 0; l < c.n_layers; ++l) {
             const LayerW& L = m->layers[l];
-            add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)L.attn_norm,
-                                                      (T*)kv->xn, plane(d), nullptr, tks(d));
+            norm(pending_parts, L.attn_norm, nullptr);
             LAUNCHCHK("add_rmsnorm");
             if ((rc = time_mark(kv, 1, st))) return rc;
             if ((rc = partial_gemm(L.wqkv, kv->xn, d, d, Nqkv, kv->plan_qkv))) return rc;
@@ -1240,8 +1249,7 @@ struct Runner {
             if ((rc = time_mark(kv, 2, st))) return rc;
             if ((rc = partial_gemm(L.wo, kv->attn_out, Nq, Nq, d, kv->plan_o))) return rc;
             if ((rc = time_mark(kv, 2, st))) return rc;
-            add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, nparts(kv->plan_o), (const T*)L.ffn_norm,
-                                                      (T*)kv->xn, plane(d), nullptr, tks(d));
+            norm(nparts(kv->plan_o), L.ffn_norm, nullptr);
             LAUNCHCHK("add_rmsnorm");
             if ((rc = time_mark(kv, 3, st))) return rc;
             if ((rc = gate_up(L.wgu))) return rc;
@@ -1251,8 +1259,7 @@ struct Runner {
             if ((rc = time_mark(kv, 4, st))) return rc;
             pending_parts = nparts(kv->plan_d);
         }
-        add_rmsnorm_kernel<T><<<R, 1024, 0, st>>>(R, d, md.eps, kv->x, kv->part, pending_parts, (const T*)m->final_norm,
-                                                  (T*)kv->xn, plane(d), kv->hn32, tks(d));
+        norm(pending_parts, m->final_norm, kv->hn32);
         LAUNCHCHK("add_rmsnorm");
         return SJ_OK;
     }
