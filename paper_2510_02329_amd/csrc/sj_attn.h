@@ -33,7 +33,7 @@ namespace sj {
 
 #ifdef SJ_ATTN_PROF
 __device__ unsigned long long attn_prof[4096 * 16];
-#define ATTN_STAMP(k) do { if ((threadIdx.x & 63) == 0) attn_prof[((blockIdx.y * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (k)] = wall_clock64(); } while (0)
+#define ATTN_STAMP(k) do { if ((threadIdx.x & 63) == 0) attn_prof[((((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) & 1023) * 4 + (threadIdx.x >> 6)) * 16 + (k)] = wall_clock64(); } while (0)
 #else
 #define ATTN_STAMP(k) do { } while (0)
 #endif
