@@ -261,8 +261,8 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
         // stream; the compute waves read stage s + 1 while they multiply stage s, so stage s + 2 has to
         // be in LDS when iteration s ends: NS - 3 stages of the wave's loads may still be in flight.
         const int lw = w - R2_CW;
-        auto run = [&](auto nl_tag, auto ns_tag, auto make_src, auto dst_of) {
-            constexpr int NL = decltype(nl_tag)::value, NS = decltype(ns_tag)::value;
+        auto run = [&](auto nl_tag, auto ns_tag, auto aux_tag, auto make_src, auto dst_of) {
+            constexpr int NL = decltype(nl_tag)::value, NS = decltype(ns_tag)::value, AUX = decltype(aux_tag)::value;
             const char* src[NL];
             size_t step[NL];
 #pragma unroll
@@ -272,7 +272,7 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
 #pragma unroll
                 for (int j = 0; j < NL; ++j)
                     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + k * step[j]),
-                                                     (__attribute__((address_space(3))) void*)dst_of(s % NS, j), 16, 0, 0);
+                                                     (__attribute__((address_space(3))) void*)dst_of(s % NS, j), 16, 0, AUX);
             };
             constexpr int BEHIND = (NS - 3) * NL;
             static_assert((NS - 1) * NL < 64, "the load counter holds 63");
@@ -296,7 +296,13 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
                 st = 1024;
             };
             auto dst_of = [&](int buf, int j) { return &Wst[buf][min(lw + 2 * j, NT - 1)][0]; };
-            run(std::integral_constant<int, (NT + 1) / 2>{}, std::integral_constant<int, R4_NSW>{}, make_src, dst_of);
+            // One row group: every weight byte is read once, by this workgroup alone - the streaming cache policy
+            // (measured: the batched step 8.30 -> 8.08 ms).  Several row groups: the workgroups of an n-tile group find
+            // the tile in their L2, which the streaming policy gives up too early (LM-head fetch 1.57 x -> 1.83 x).
+            if (a.rgroups > 1)
+                run(std::integral_constant<int, (NT + 1) / 2>{}, std::integral_constant<int, R4_NSW>{}, std::integral_constant<int, 0>{}, make_src, dst_of);
+            else
+                run(std::integral_constant<int, (NT + 1) / 2>{}, std::integral_constant<int, R4_NSW>{}, std::integral_constant<int, 2>{}, make_src, dst_of);
         } else {                                                      // operand fragments x, x + 2, ..
             const int x = lw - 2;
             auto make_src = [&](int j, const char*& sp, size_t& st) {
@@ -314,7 +320,7 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
                 }
             };
             auto dst_of = [&](int buf, int j) { return &Xst[buf][min(x + 2 * j, NX - 1)][0]; };
-            run(std::integral_constant<int, (NX + 1) / 2>{}, std::integral_constant<int, R4_NSX>{}, make_src, dst_of);
+            run(std::integral_constant<int, (NX + 1) / 2>{}, std::integral_constant<int, R4_NSX>{}, std::integral_constant<int, 0>{}, make_src, dst_of);
         }
         return;
     }
