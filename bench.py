@@ -232,7 +232,7 @@ def bench_head(args, torch, sj, synth) -> dict:
         "mean_tokens_per_seq_step": round(mean_tokens, 3),
         "acceptance_over": f"{len(drafts)} seeded draft batches of {B} sequences",
         "copy_ceiling_gbps": round(ceiling, 1),
-        "roofline": {"kernel": "gemm_rows4 (LM-head product + per-tile softmax partials, all 576 rows in one launch)", "bound": "mfma",
+        "roofline": {"kernel": "gemm_rows8 (LM-head product + per-tile softmax partials, all 576 rows in one launch)", "bound": "mfma",
                      "achieved": round(flops / k_s / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(flops / k_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                      "flops_per_launch": flops, "avg_launch_us": round(k_s * 1e6, 2), "launches_timed": int(k_launches),

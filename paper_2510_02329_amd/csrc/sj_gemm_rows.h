@@ -38,61 +38,65 @@ constexpr int R2_NB = 4;           // LDS stage buffers
 constexpr int R2_MTW = 3;          // row tiles per compute wave (4 waves x 3 >= 9 row tiles)
 constexpr int R2_RING = 4;         // operand ring (k-steps) = k-steps per stage
 
-// Epilogue of the many-row kernels from the accumulators: lane holds columns nt*16 + 4g .. +3 of row
-// m*16 + r; wave w owns row tiles w, w + 4, w + 8.
+// Epilogue of the many-row kernels for ONE accumulator tile (row tile m, n-tile nt): the lane holds columns
+// nt*16 + 4g .. +3 of row m*16 + r.  Uniform per wave; rows >= R take part in the shuffles and store nothing.
+template <typename T, int EPI>
+__device__ __forceinline__ void rows_epilogue_tile(const GemmArgs& a, const f32x4& v, int m, int nt, int ntiles, int r, int g) {
+    const int row = m * 16 + r;
+    const bool valid = row < a.R;
+    if constexpr (EPI == EPI_PARTIAL) {
+        if (valid)
+            *reinterpret_cast<f32x4*>(a.out + ((size_t)blockIdx.y * a.slice_rows + row) * a.N + (size_t)nt * 16 + 4 * g) = v;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // tile rows 0-7 are gate of FFN columns 8*nt .. 8*nt+7, rows 8-15 their up projections:
+        // the up value of this lane's gate sits two lane groups further
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float up = __shfl_down(v[e], 32, 64);
+            const float gate = v[e];
+            y[e] = gate / (1.0f + expf(-gate)) * up;
+        }
+        if (valid && g < 2)
+            Traits<T>::store_split4(reinterpret_cast<T*>(a.act) + opnd_off<T>(row, nt * 8 + 4 * g, a.N / 2, a.act_tks), a.actplane, y);
+    } else {
+        // logits + this tile's softmax partial of the row (max, sum exp((l - max)/T), lowest arg-max)
+        float mx = v[0];
+        int arg = nt * 16 + 4 * g;
+#pragma unroll
+        for (int e = 1; e < 4; ++e)
+            if (v[e] > mx) { mx = v[e]; arg = nt * 16 + 4 * g + e; }
+#pragma unroll
+        for (int o = 16; o < 64; o <<= 1) {
+            const float omx = __shfl_xor(mx, o, 64);
+            const int oarg = __shfl_xor(arg, o, 64);
+            if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+        }
+        float se = 0.f;
+        if (a.inv_temp > 0.f) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) se += expf((v[e] - mx) * a.inv_temp);
+            se += __shfl_xor(se, 16, 64);
+            se += __shfl_xor(se, 32, 64);
+        }
+        if (valid) {
+            *reinterpret_cast<f32x4*>(a.out + (size_t)row * a.N + (size_t)nt * 16 + 4 * g) = v;
+            if (g == 0) a.stats[(size_t)row * ntiles + nt] = float4{mx, se, __int_as_float(arg), 0.f};
+        }
+    }
+}
+
+// The same over a wave's tiles: wave w owns row tiles w, w + 4, w + 8.
 template <typename T, int EPI, int NT = R2_NT>
 __device__ __forceinline__ void rows_epilogue(const GemmArgs& a, const f32x4 (&acc)[R2_MTW][NT], int w, int my_tiles, int nt0,
                                               int ntiles, int r, int g) {
 #pragma unroll
     for (int i = 0; i < R2_MTW; ++i) {
         if (i >= my_tiles) continue;                       // wave-uniform
-        const int row = (w + R2_CW * i) * 16 + r;
-        const bool valid = row < a.R;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int nt = nt0 + t;
-            if (nt >= ntiles) continue;                    // uniform
-            const f32x4 v = acc[i][t];
-            if constexpr (EPI == EPI_PARTIAL) {
-                if (valid)
-                    *reinterpret_cast<f32x4*>(a.out + ((size_t)blockIdx.y * a.slice_rows + row) * a.N + (size_t)nt * 16 + 4 * g) = v;
-            } else if constexpr (EPI == EPI_SWIGLU) {
-                // tile rows 0-7 are gate of FFN columns 8*nt .. 8*nt+7, rows 8-15 their up projections:
-                // the up value of this lane's gate sits two lane groups further
-                float y[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float up = __shfl_down(v[e], 32, 64);
-                    const float gate = v[e];
-                    y[e] = gate / (1.0f + expf(-gate)) * up;
-                }
-                if (valid && g < 2)
-                    Traits<T>::store_split4(reinterpret_cast<T*>(a.act) + opnd_off<T>(row, nt * 8 + 4 * g, a.N / 2, a.act_tks), a.actplane, y);
-            } else {
-                // logits + this tile's softmax partial of the row (max, sum exp((l - max)/T), lowest arg-max)
-                float mx = v[0];
-                int arg = nt * 16 + 4 * g;
-#pragma unroll
-                for (int e = 1; e < 4; ++e)
-                    if (v[e] > mx) { mx = v[e]; arg = nt * 16 + 4 * g + e; }
-#pragma unroll
-                for (int o = 16; o < 64; o <<= 1) {
-                    const float omx = __shfl_xor(mx, o, 64);
-                    const int oarg = __shfl_xor(arg, o, 64);
-                    if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
-                }
-                float se = 0.f;
-                if (a.inv_temp > 0.f) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) se += expf((v[e] - mx) * a.inv_temp);
-                    se += __shfl_xor(se, 16, 64);
-                    se += __shfl_xor(se, 32, 64);
-                }
-                if (valid) {
-                    *reinterpret_cast<f32x4*>(a.out + (size_t)row * a.N + (size_t)nt * 16 + 4 * g) = v;
-                    if (g == 0) a.stats[(size_t)row * ntiles + nt] = float4{mx, se, __int_as_float(arg), 0.f};
-                }
-            }
+            if (nt0 + t >= ntiles) continue;               // uniform
+            rows_epilogue_tile<T, EPI>(a, acc[i][t], w + R2_CW * i, nt0 + t, ntiles, r, g);
         }
     }
 }
@@ -224,14 +228,23 @@ constexpr int R4_LW = 4;           // loader waves: two for the weights, two for
 // are handed to the 8 XCDs (each with an L2 of its own) round robin by index, so workgroup i works for XCD i % 8;
 // within an XCD consecutive workgroups take the row groups of one n-tile group, then the next n-tile group: the first
 // of them pulls a weight tile from HBM, the others find it in their L2 a moment later.
+//
+// EIGHT compute waves with an even split of the 9 x NT accumulator tiles: wave w = (a = w % 4, b = w / 4) owns row tiles
+// a and a + 4 for the n-tiles of half b, and n-tile w of row tile 8: 9 tiles each for NT = 8 (8 / 8 / 8 / 8 / 7 / 7 / 7 / 6
+// for NT = 7), 36 accumulator registers, two compute waves per SIMD.  An earlier form with four compute waves (row tiles
+// w, w + 4, w + 8: one wave with three) measured the same on two-plane operands, where the L2 traffic of the operand sets
+// the pace, and 12 % slower on the one-plane LM head of the verify-head workload (909 -> 799 us).
+constexpr int R8_CW = 8;
+
 template <typename T, int EPI, int SPL, int NT = R2_NT>
-__global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmArgs a, int mt) {
+__global__ __launch_bounds__((R8_CW + R4_LW) * 64) void gemm_rows8_kernel(GemmArgs a, int mt) {
     static_assert(SPL <= 2, "three operand planes do not fit");
+    static_assert(NT == 7 || NT == 8, "n-tile halves are 4 + 4 or 4 + 3");
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
     constexpr int NX = ROWS_MT * SPL;                  // operand fragments per stage
-    __shared__ u32x4 Wst[R4_NSW][NT][64];              // 64 KB
-    __shared__ u32x4 Xst[R4_NSX][NX][64];              // 90 KB with two planes
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    __shared__ u32x4 Wst[R4_NSW][NT][64];
+    __shared__ u32x4 Xst[R4_NSX][NX][64];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
     const int KS = a.K / KSTEP, ntiles = a.N / 16;
     int bx = blockIdx.x;
@@ -253,14 +266,13 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
     const int nks = ks1 - ks0;
     if (nks <= 0) return;                              // uniform for the workgroup
 
-    if (w >= R2_CW) {
+    if (w >= R8_CW) {
         // ---------------- loader waves ----------------
-        // A wave's loads come back in the order it issued them, so the weights (HBM, deep ring) and the
-        // operand (L2, shallow ring) are fetched by different waves.  Stage = k-step of the slice (clamped:
-        // a stage past the end re-reads the last one into its own buffer).  NS = ring depth of the wave's
-        // stream; the compute waves read stage s + 1 while they multiply stage s, so stage s + 2 has to
-        // be in LDS when iteration s ends: NS - 3 stages of the wave's loads may still be in flight.
-        const int lw = w - R2_CW;
+        // A wave's loads come back in the order it issued them, so the weights (HBM, deep ring) and the operand (L2, shallow
+        // ring) are fetched by different waves.  Stage = k-step of the slice (clamped: a stage past the end re-reads the last
+        // one into its own buffer).  The compute waves read stage s + 1 while they multiply stage s, so stage s + 2 has to be
+        // in LDS when iteration s ends: NS - 3 stages of a loader wave's loads may still be in flight.
+        const int lw = w - R8_CW;
         auto run = [&](auto nl_tag, auto ns_tag, auto aux_tag, auto make_src, auto dst_of) {
             constexpr int NL = decltype(nl_tag)::value, NS = decltype(ns_tag)::value, AUX = decltype(aux_tag)::value;
             const char* src[NL];
@@ -281,36 +293,31 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(BEHIND));            // stages 0 and 1 have landed
             lds_barrier();
             for (int s = 0; s < nks; ++s) {
-                // buffer (s + NS - 1) % NS = (s - 1) % NS: its fragments went to registers during iteration s - 2
                 issue(s + NS - 1);
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(BEHIND));        // stage s + 2 has landed
                 lds_barrier();
             }
             wait_vm0();
         };
-        if (lw < 2) {                                                 // weight tiles lw, lw + 2, ..
+        if (lw < 2) {
             auto make_src = [&](int j, const char*& sp, size_t& st) {
-                // an odd tile count: the second wave repeats the last tile; tiles past N re-read the last
                 const size_t tile = (size_t)min(nt0 + min(lw + 2 * j, NT - 1), ntiles - 1);
                 sp = reinterpret_cast<const char*>(a.Wt) + ((tile * KS + ks0) * 64 + lane) * 16;
                 st = 1024;
             };
             auto dst_of = [&](int buf, int j) { return &Wst[buf][min(lw + 2 * j, NT - 1)][0]; };
-            // One row group: every weight byte is read once, by this workgroup alone - the streaming cache policy
-            // (measured: the batched step 8.30 -> 8.08 ms).  Several row groups: the workgroups of an n-tile group find
-            // the tile in their L2, which the streaming policy gives up too early (LM-head fetch 1.57 x -> 1.83 x).
             if (a.rgroups > 1)
                 run(std::integral_constant<int, (NT + 1) / 2>{}, std::integral_constant<int, R4_NSW>{}, std::integral_constant<int, 0>{}, make_src, dst_of);
             else
                 run(std::integral_constant<int, (NT + 1) / 2>{}, std::integral_constant<int, R4_NSW>{}, std::integral_constant<int, 2>{}, make_src, dst_of);
-        } else {                                                      // operand fragments x, x + 2, ..
+        } else {
             const int x = lw - 2;
             auto make_src = [&](int j, const char*& sp, size_t& st) {
-                const int it = min(x + 2 * j, NX - 1);                // an odd count: the last wave repeats the last item
+                const int it = min(x + 2 * j, NX - 1);
                 const int m = it / SPL, p = it % SPL;
                 const T* plane = reinterpret_cast<const T*>(a.X) + (size_t)p * a.xplane;
-                if (a.x_tks) {                                        // plane in fragment blocks: 1 KB per (row tile, k-step)
-                    const size_t mt_ok = m * 16 < a.R ? m : 0;        // whole tiles past R re-read tile 0
+                if (a.x_tks) {
+                    const size_t mt_ok = m * 16 < a.R ? m : 0;
                     sp = reinterpret_cast<const char*>(plane + ((mt_ok * a.x_tks + ks0) * 16 + r) * KSTEP + g * KF);
                     st = (size_t)16 * KSTEP * sizeof(T);
                 } else {
@@ -325,51 +332,64 @@ __global__ __launch_bounds__((R2_CW + R4_LW) * 64) void gemm_rows4_kernel(GemmAr
         return;
     }
 
-    // ---------------- compute waves: row tiles w, w + 4, w + 8 ----------------
-    const int my_tiles = (mt > w) ? (mt - w + R2_CW - 1) / R2_CW : 0;
-    f32x4 acc[R2_MTW][NT];
+    // ---------------- compute waves ----------------
+    const int ra = w & 3, nb = w >> 2;                 // row tiles ra, ra + 4; n-tiles of half nb; n-tile w of row tile 8
+    constexpr int NH = 4;                              // n-tiles of half 0 (half 1 has NT - 4)
+    const int t0 = nb * NH, nh = nb == 0 ? NH : NT - NH;
+    const bool has0 = ra < mt, has1 = ra + 4 < mt, has8 = (mt == ROWS_MT) && (w < NT);
+    f32x4 acc[2][NH], acc8 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < R2_MTW; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NH; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // two register sets of fragments: the next k-step is read from LDS while the current one is multiplied
-    Frag wfA[NT], bqA[R2_MTW][SPL], wfB[NT], bqB[R2_MTW][SPL];
-    auto fetch = [&](Frag (&wf)[NT], Frag (&bq)[R2_MTW][SPL], int s) {
-        // a stage past the end holds a copy of the last one
+    struct Frags { Frag wf[NH]; Frag w8; Frag bq[3][SPL]; };
+    Frags fA, fB;
+    auto fetch = [&](Frags& f, int s) {
         const u32x4* Xs = &Xst[s % R4_NSX][0][0];
         const u32x4* Ws = &Wst[s % R4_NSW][0][0];
 #pragma unroll
-        for (int i = 0; i < R2_MTW; ++i)
+        for (int sp = 0; sp < SPL; ++sp) {
+            f.bq[0][sp].u = Xs[(ra * SPL + sp) * 64 + lane];
+            f.bq[1][sp].u = Xs[((ra + 4) * SPL + sp) * 64 + lane];
+            f.bq[2][sp].u = Xs[((ROWS_MT - 1) * SPL + sp) * 64 + lane];
+        }
 #pragma unroll
-            for (int sp = 0; sp < SPL; ++sp) bq[i][sp].u = Xs[(min(w + R2_CW * i, ROWS_MT - 1) * SPL + sp) * 64 + lane];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) wf[t].u = Ws[t * 64 + lane];
+        for (int t = 0; t < NH; ++t) f.wf[t].u = Ws[min(t0 + t, NT - 1) * 64 + lane];
+        f.w8.u = Ws[min(w, NT - 1) * 64 + lane];
     };
-    auto multiply = [&](const Frag (&wf)[NT], const Frag (&bq)[R2_MTW][SPL]) {
+    // No predicate in the k-step: a tile that does not exist (row tiles past the rows re-read tile 0, n-tiles past the
+    // workgroup's are clamped) is multiplied into an accumulator that the epilogue never stores.
+    auto multiply = [&](const Frags& f) {
 #pragma unroll
-        for (int i = 0; i < R2_MTW; ++i) {
-            if (i < my_tiles) {
+        for (int sp = 0; sp < SPL; ++sp) {
 #pragma unroll
-                for (int sp = 0; sp < SPL; ++sp)
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) Traits<T>::mma(wf[t], bq[i][sp], acc[i][t]);
+            for (int t = 0; t < NH; ++t) {
+                Traits<T>::mma(f.wf[t], f.bq[0][sp], acc[0][t]);
+                Traits<T>::mma(f.wf[t], f.bq[1][sp], acc[1][t]);
             }
+            Traits<T>::mma(f.w8, f.bq[2][sp], acc8);
         }
     };
     lds_barrier();                                     // stages 0 and 1 are in LDS
-    fetch(wfA, bqA, 0);
+    fetch(fA, 0);
     for (int s = 0; s < nks; s += 2) {
-        fetch(wfB, bqB, s + 1);
-        multiply(wfA, bqA);
+        fetch(fB, s + 1);
+        multiply(fA);
         lds_barrier();                                 // stage s + 2 has landed
         if (s + 1 < nks) {                             // uniform
-            fetch(wfA, bqA, s + 2);
-            multiply(wfB, bqB);
+            fetch(fA, s + 2);
+            multiply(fB);
             lds_barrier();                             // stage s + 3 has landed
         }
     }
-    rows_epilogue<T, EPI, NT>(a, acc, w, my_tiles, nt0, ntiles, r, g);
+#pragma unroll
+    for (int t = 0; t < NH; ++t) {
+        if (t >= nh || nt0 + t0 + t >= ntiles) continue;   // uniform
+        if (has0) rows_epilogue_tile<T, EPI>(a, acc[0][t], ra, nt0 + t0 + t, ntiles, r, g);
+        if (has1) rows_epilogue_tile<T, EPI>(a, acc[1][t], ra + 4, nt0 + t0 + t, ntiles, r, g);
+    }
+    if (has8 && nt0 + w < ntiles) rows_epilogue_tile<T, EPI>(a, acc8, ROWS_MT - 1, nt0 + w, ntiles, r, g);
 }
 
 }  // namespace sj

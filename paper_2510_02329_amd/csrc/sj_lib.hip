@@ -576,7 +576,7 @@ extern "C" int sj_kernel_class_shape(const sj_kv* kv, int32_t kernel_class, int3
     if (rows > FEW_ROWS) {
         const GemmPlan* p = kernel_class == 1 ? &kv->plan_qkv[1] : kernel_class == 2 ? &kv->plan_o[1] : kernel_class == 4 ? &kv->plan_d[1] : nullptr;
         snprintf(buf, (size_t)buf_len, "gemm_rows%s: row groups of 144 in one launch, 8 or 7 n-tiles per workgroup, %d K-slice(s)",
-                 kv->planes == 3 ? "2" : "4", p ? p->split : 1);
+                 kv->planes == 3 ? "2" : "8", p ? p->split : 1);
         return SJ_OK;
     }
     const GemmPlan& p = kernel_class == 1 ? kv->plan_qkv[0] : kernel_class == 2 ? kv->plan_o[0] : kernel_class == 3 ? kv->plan_gu
@@ -1130,7 +1130,7 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
     };
     if constexpr (SPL <= 2) {
         // one launch for all row groups: the workgroups of an n-tile group run side by side on one XCD, so the
-        // weights are fetched from HBM once for all rows (gemm_rows4_kernel).  7 n-tiles per workgroup where that
+        // weights are fetched from HBM once for all rows (gemm_rows8_kernel).  7 n-tiles per workgroup where that
         // fills whole rounds of the chip and 8 do not (gate/up of the 8B shape: 256 workgroups instead of 224), from
         // 8 row tiles on (below that the lighter weight stream per CU loses)
         const int rgroups = (rows + group_rows - 1) / group_rows;
@@ -1141,8 +1141,8 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
         const int per = seven ? 7 : R2_NT, ngroups = (ntiles + per - 1) / per;
         const int gx = rgroups > 1 ? (ngroups + 7) / 8 * 8 * rgroups : ngroups;
         const dim3 grid(gx, EPI == EPI_PARTIAL ? split : 1);
-        if (seven) gemm_rows4_kernel<T, EPI, SPL, 7><<<grid, (R2_CW + R4_LW) * 64, 0, st>>>(a, mt);
-        else gemm_rows4_kernel<T, EPI, SPL><<<grid, (R2_CW + R4_LW) * 64, 0, st>>>(a, mt);
+        if (seven) gemm_rows8_kernel<T, EPI, SPL, 7><<<grid, (R8_CW + R4_LW) * 64, 0, st>>>(a, mt);
+        else gemm_rows8_kernel<T, EPI, SPL><<<grid, (R8_CW + R4_LW) * 64, 0, st>>>(a, mt);
         LAUNCHCHK("gemm_rows");
     } else {
         for (int row0 = 0; row0 < rows; row0 += group_rows) {
