@@ -236,12 +236,17 @@ constexpr int R4_LW = 4;           // loader waves: two for the weights, two for
 // the pace, and 12 % slower on the one-plane LM head of the verify-head workload (909 -> 799 us).
 constexpr int R8_CW = 8;
 
-template <typename T, int EPI, int SPL, int NT = R2_NT>
+// RT = row tiles of a row group: 9 (144 rows), or 18 with a single operand plane (288 rows: the same 18 operand
+// fragments per k-step in LDS, half as many workgroups re-reading every weight tile through L2).  A wave owns RT / 4
+// whole row tiles for its half of the n-tiles and n-tile w of each of the RT % 4 tiles left over.
+template <typename T, int EPI, int SPL, int NT = R2_NT, int RT = ROWS_MT>
 __global__ __launch_bounds__((R8_CW + R4_LW) * 64) void gemm_rows8_kernel(GemmArgs a, int mt) {
     static_assert(SPL <= 2, "three operand planes do not fit");
     static_assert(NT == 7 || NT == 8, "n-tile halves are 4 + 4 or 4 + 3");
+    static_assert(RT * SPL <= 2 * ROWS_MT, "the operand stages in LDS hold 18 fragments");
     constexpr int KF = Traits<T>::KF, KSTEP = Traits<T>::KSTEP;
-    constexpr int NX = ROWS_MT * SPL;                  // operand fragments per stage
+    constexpr int NX = RT * SPL;                       // operand fragments per stage
+    constexpr int NFULL = RT / 4, NREM = RT % 4;       // whole row tiles per wave; tiles shared out by n-tile
     __shared__ u32x4 Wst[R4_NSW][NT][64];
     __shared__ u32x4 Xst[R4_NSX][NX][64];
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -253,7 +258,7 @@ __global__ __launch_bounds__((R8_CW + R4_LW) * 64) void gemm_rows8_kernel(GemmAr
         const int rg = j % a.rgroups;
         bx = (j / a.rgroups) * 8 + xcd;
         if (bx * NT >= ntiles) return;                 // padding of the grid to whole XCD rounds (uniform)
-        const int row0 = rg * (ROWS_MT * 16), nr = min(ROWS_MT * 16, a.R - row0);
+        const int row0 = rg * (RT * 16), nr = min(RT * 16, a.R - row0);
         a.X = reinterpret_cast<const char*>(a.X) + (size_t)row0 * a.ldx * sizeof(T);
         if (EPI == EPI_SWIGLU) a.act = reinterpret_cast<char*>(a.act) + (size_t)row0 * (a.N / 2) * sizeof(T);
         else a.out += (size_t)row0 * a.N;
@@ -336,23 +341,25 @@ __global__ __launch_bounds__((R8_CW + R4_LW) * 64) void gemm_rows8_kernel(GemmAr
     const int ra = w & 3, nb = w >> 2;                 // row tiles ra, ra + 4; n-tiles of half nb; n-tile w of row tile 8
     constexpr int NH = 4;                              // n-tiles of half 0 (half 1 has NT - 4)
     const int t0 = nb * NH, nh = nb == 0 ? NH : NT - NH;
-    const bool has0 = ra < mt, has1 = ra + 4 < mt, has8 = (mt == ROWS_MT) && (w < NT);
-    f32x4 acc[2][NH], acc8 = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[NFULL][NH], acc8[NREM];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NFULL; ++i)
 #pragma unroll
         for (int t = 0; t < NH; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < NREM; ++j) acc8[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    struct Frags { Frag wf[NH]; Frag w8; Frag bq[3][SPL]; };
+    struct Frags { Frag wf[NH]; Frag w8; Frag bq[NFULL + NREM][SPL]; };
     Frags fA, fB;
     auto fetch = [&](Frags& f, int s) {
         const u32x4* Xs = &Xst[s % R4_NSX][0][0];
         const u32x4* Ws = &Wst[s % R4_NSW][0][0];
 #pragma unroll
         for (int sp = 0; sp < SPL; ++sp) {
-            f.bq[0][sp].u = Xs[(ra * SPL + sp) * 64 + lane];
-            f.bq[1][sp].u = Xs[((ra + 4) * SPL + sp) * 64 + lane];
-            f.bq[2][sp].u = Xs[((ROWS_MT - 1) * SPL + sp) * 64 + lane];
+#pragma unroll
+            for (int i = 0; i < NFULL; ++i) f.bq[i][sp].u = Xs[((ra + 4 * i) * SPL + sp) * 64 + lane];
+#pragma unroll
+            for (int j = 0; j < NREM; ++j) f.bq[NFULL + j][sp].u = Xs[((4 * NFULL + j) * SPL + sp) * 64 + lane];
         }
 #pragma unroll
         for (int t = 0; t < NH; ++t) f.wf[t].u = Ws[min(t0 + t, NT - 1) * 64 + lane];
@@ -364,11 +371,11 @@ __global__ __launch_bounds__((R8_CW + R4_LW) * 64) void gemm_rows8_kernel(GemmAr
 #pragma unroll
         for (int sp = 0; sp < SPL; ++sp) {
 #pragma unroll
-            for (int t = 0; t < NH; ++t) {
-                Traits<T>::mma(f.wf[t], f.bq[0][sp], acc[0][t]);
-                Traits<T>::mma(f.wf[t], f.bq[1][sp], acc[1][t]);
-            }
-            Traits<T>::mma(f.w8, f.bq[2][sp], acc8);
+            for (int t = 0; t < NH; ++t)
+#pragma unroll
+                for (int i = 0; i < NFULL; ++i) Traits<T>::mma(f.wf[t], f.bq[i][sp], acc[i][t]);
+#pragma unroll
+            for (int j = 0; j < NREM; ++j) Traits<T>::mma(f.w8, f.bq[NFULL + j][sp], acc8[j]);
         }
     };
     lds_barrier();                                     // stages 0 and 1 are in LDS
@@ -386,10 +393,15 @@ __global__ __launch_bounds__((R8_CW + R4_LW) * 64) void gemm_rows8_kernel(GemmAr
 #pragma unroll
     for (int t = 0; t < NH; ++t) {
         if (t >= nh || nt0 + t0 + t >= ntiles) continue;   // uniform
-        if (has0) rows_epilogue_tile<T, EPI>(a, acc[0][t], ra, nt0 + t0 + t, ntiles, r, g);
-        if (has1) rows_epilogue_tile<T, EPI>(a, acc[1][t], ra + 4, nt0 + t0 + t, ntiles, r, g);
+#pragma unroll
+        for (int i = 0; i < NFULL; ++i)
+            if (ra + 4 * i < mt) rows_epilogue_tile<T, EPI>(a, acc[i][t], ra + 4 * i, nt0 + t0 + t, ntiles, r, g);
     }
-    if (has8 && nt0 + w < ntiles) rows_epilogue_tile<T, EPI>(a, acc8, ROWS_MT - 1, nt0 + w, ntiles, r, g);
+    if (w < NT && nt0 + w < ntiles) {
+#pragma unroll
+        for (int j = 0; j < NREM; ++j)
+            if (4 * NFULL + j < mt) rows_epilogue_tile<T, EPI>(a, acc8[j], 4 * NFULL + j, nt0 + w, ntiles, r, g);
+    }
 }
 
 }  // namespace sj

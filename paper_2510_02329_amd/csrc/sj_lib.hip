@@ -1112,7 +1112,9 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
     const int ntiles = N / 16;
     // fragment-tiled operand planes: a group of 144 rows starts row0 * K elements into the plane in either layout
     if (tiled && ldx != K) return fail(SJ_EINVAL, "a tiled operand has no padding between rows");
-    const int group_rows = ROWS_MT * 16;
+    // a single operand plane: row groups of 288 (the 18 operand fragments of a k-step fill the same LDS stages)
+    constexpr int RT = (SPL == 1) ? 2 * ROWS_MT : ROWS_MT;
+    const int group_rows = RT * 16;
     auto args_of = [&](int row0, int nr) {
         GemmArgs a{};
         a.Wt = Wt;
@@ -1141,8 +1143,8 @@ static int gemm_rows(hipStream_t st, const void* Wt, const void* X, size_t xplan
         const int per = seven ? 7 : R2_NT, ngroups = (ntiles + per - 1) / per;
         const int gx = rgroups > 1 ? (ngroups + 7) / 8 * 8 * rgroups : ngroups;
         const dim3 grid(gx, EPI == EPI_PARTIAL ? split : 1);
-        if (seven) gemm_rows8_kernel<T, EPI, SPL, 7><<<grid, (R8_CW + R4_LW) * 64, 0, st>>>(a, mt);
-        else gemm_rows8_kernel<T, EPI, SPL><<<grid, (R8_CW + R4_LW) * 64, 0, st>>>(a, mt);
+        if (seven) gemm_rows8_kernel<T, EPI, SPL, 7, RT><<<grid, (R8_CW + R4_LW) * 64, 0, st>>>(a, mt);
+        else gemm_rows8_kernel<T, EPI, SPL, R2_NT, RT><<<grid, (R8_CW + R4_LW) * 64, 0, st>>>(a, mt);
         LAUNCHCHK("gemm_rows");
     } else {
         for (int row0 = 0; row0 < rows; row0 += group_rows) {
