@@ -1220,12 +1220,14 @@ struct Runner {
         return SJ_OK;
     }
 
-    // residual add of `parts` pending split-K partials + RMSNorm into the operand planes (at most two partials: a
-    // two-wide batch of loads instead of an eight-wide one that mostly repeats them)
+    // residual add of `parts` pending split-K partials + RMSNorm into the operand planes (batches of loads as wide as
+    // the partials there are: an eight-wide clamped batch for two partials repeats six loads)
     void norm(int parts, const void* gain, float* xn32) {
         const int d = m->md.d;
         if (parts <= 2)
             add_rmsnorm_kernel<T, 2><<<R, 1024, 0, st>>>(R, d, m->md.eps, kv->x, kv->part, parts, (const T*)gain, (T*)kv->xn, plane(d), xn32, tks(d));
+        else if (parts <= 4)
+            add_rmsnorm_kernel<T, 4><<<R, 1024, 0, st>>>(R, d, m->md.eps, kv->x, kv->part, parts, (const T*)gain, (T*)kv->xn, plane(d), xn32, tks(d));
         else
             add_rmsnorm_kernel<T, 8><<<R, 1024, 0, st>>>(R, d, m->md.eps, kv->x, kv->part, parts, (const T*)gain, (T*)kv->xn, plane(d), xn32, tks(d));
     }
