@@ -10,7 +10,7 @@ sequence state is rewound before every step so that all timed steps are identica
 `--workload 1` times the verification tail alone (sj_verify_head on given hidden states: LM head, softmax, ratio test,
 judge, scan, extra token) at batch 64, gamma 8: a dense contraction, priced against the bf16 MFMA peak.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (the fields are described in the README).
 """
 from __future__ import annotations
 
