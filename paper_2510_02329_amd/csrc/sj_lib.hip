@@ -1320,8 +1320,10 @@ struct Runner {
             dim3 g(kv->nslab / 256, nseq);
             scan_resample_e_kernel<<<g, 256, 0, st>>>(kv->sp_dev, ra, kv->scores, kv->p_at_d, kv->bits, kv->nacc, kv->ranks);
             LAUNCHCHK("scan_resample_e");
-            resample_w_kernel<<<g, 256, 0, st>>>(kv->sp_dev, ra);
-            LAUNCHCHK("resample_w");
+            if (gamma > 0) {                               // gamma = 0: always the bonus draw from the row itself, no residual
+                resample_w_kernel<<<g, 256, 0, st>>>(kv->sp_dev, ra);
+                LAUNCHCHK("resample_w");
+            }
         } else {
             accept_scan_kernel<<<nseq, 64, 0, st>>>(kv->sp_dev, md.V, md.inv_temp, kv->logits, kv->rowstat, kv->scores, kv->p_at_d,
                                                      kv->bits, kv->nacc, kv->ranks);
